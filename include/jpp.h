@@ -1,0 +1,223 @@
+/* jpp.h -- C ABI of the MI355X pipeline-stage executor.
+ *
+ * One `jpp_stage` is one actor of an MPMD pipeline (paper, Section 2.2: an actor
+ * is a group of devices executing the same logic; here: one gfx950 GPU).  It owns
+ * one or more pipeline stages ("circular repeat", Section 2.2.1), each made of
+ * transformer decoder layers, and executes a per-actor list of Task(i, ty, stage)
+ * records (Section 4.2) in ONE call (Section 4.4, task fusion), accumulating
+ * parameter gradients over the microbatches (Section 3.1: grads start at zero and
+ * are summed, no 1/M; per-microbatch losses are collected as a vector).
+ *
+ * Conventions
+ *  - Plain C.  No exception crosses the boundary; every entry point returns a
+ *    jpp_status (or a size / pointer where stated) and records a message that
+ *    jpp_last_error() returns (thread-local).
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
+ *    pointers are ordinary process memory.  Streams are hipStream_t passed as
+ *    void*.  The library allocates no device memory: everything lives in the
+ *    caller's arena and boundary buffers.
+ *  - Storage type of parameters, activations and boundary tensors is given by
+ *    jpp_layer_config.dtype; gradients and losses are always fp32.
+ *  - Tensors are row-major.  A boundary tensor is [microbatch, seq_len, d_model].
+ *    A linear weight is [out_features, in_features] (y = x W^T).
+ */
+#ifndef JPP_H
+#define JPP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct jpp_stage jpp_stage; /* opaque; created and destroyed by the library */
+
+typedef enum {
+  JPP_OK = 0,
+  JPP_EINVAL = 1,    /* bad config, NULL pointer, size mismatch, unsupported shape        */
+  JPP_ESCHED = 2,    /* task list violates a rule of jpp_schedule_validate; nothing ran  */
+  JPP_ECAPACITY = 3, /* task list needs more live stashes than max_in_flight             */
+  JPP_EDEVICE = 4,   /* a HIP call failed (message holds the HIP error string)           */
+  JPP_ESTATE = 5     /* e.g. run before parameters or boundary buffers were supplied     */
+} jpp_status;
+
+enum { JPP_FWD = 0, JPP_BWD = 1 };
+enum { JPP_F32 = 0, JPP_BF16 = 1 };
+enum { JPP_LAYERNORM = 0, JPP_RMSNORM = 1 };
+enum { JPP_GELU = 0, JPP_GELU_TANH = 1, JPP_SWIGLU = 2 };
+enum { JPP_GPIPE = 0, JPP_1F1B = 1, JPP_INTERLEAVED_1F1B = 2 };
+#define JPP_MAX_VIRTUAL 8
+
+/* Task(i, ty, stage) of Section 4.2: microbatch index, JPP_FWD/JPP_BWD, GLOBAL stage index. */
+typedef struct { int32_t i; int32_t ty; int32_t stage; } jpp_task;
+
+/* The paper does not define the layer (its Evaluation section only names GPT-3 and
+ * Llama 2); a stage is n_layers pre-norm decoder layers
+ *     n1 = Norm(x); [q|k|v] = n1 Wqkv^T (+b); q,k <- RoPE (opt); O = causal attention;
+ *     x1 = x + O Wo^T (+b); n2 = Norm(x1);
+ *     GeLU:   y = x1 + gelu(n2 W1^T + b1) W2^T + b2
+ *     SwiGLU: [g|u] = n2 W1^T (W1 is [2*d_ffn, d_model], gate rows first); y = x1 + (silu(g)*u) W2^T
+ * optionally followed (loss_head) by a final norm, an untied LM head [vocab, d_model]
+ * and the mean-token cross-entropy, whose backward is seeded with dloss = 1. */
+typedef struct {
+  int32_t dtype;      /* JPP_F32: everything fp32.  JPP_BF16: bf16 storage, fp32 accumulate   */
+  int32_t n_layers;   /* decoder layers per (virtual) stage                                   */
+  int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, seq_len, microbatch;
+  int32_t norm;       /* JPP_LAYERNORM (gain, offset) or JPP_RMSNORM (gain); biased variance  */
+  int32_t act;        /* JPP_GELU (erf form), JPP_GELU_TANH, JPP_SWIGLU                       */
+  int32_t use_bias;   /* 1: bqkv, bo, b1, b2 exist (and get gradients)                        */
+  int32_t rope;       /* 1: rotate q,k; pairs (j, j+head_dim/2), angle pos*theta^(-2j/hd)     */
+  float rope_theta;
+  float norm_eps;
+  int32_t loss_head;  /* 1: final norm + LM head + mean-token CE; output is loss[i]           */
+  int32_t vocab;
+  int32_t n_virtual;  /* stages owned by this actor                                           */
+  int32_t stage_ids[JPP_MAX_VIRTUAL]; /* their global indices (interleaved: v*P + rank)       */
+} jpp_layer_config;
+
+/* ---- host-only schedule helpers (no GPU needed) ------------------------------------ */
+
+/* Number of tasks of a schedule for one actor: 2*M*V (V = 1 for GPipe and 1F1B).
+ * Returns -1 on invalid arguments (P<1, rank outside [0,P), V<1, M<1, interleaved with
+ * M % P != 0). */
+int jpp_schedule_len(int kind, int P, int rank, int V, int M);
+
+/* Writes actor `rank`'s task list for a pipeline of P actors and M microbatches
+ * (Section 2.2.1 for the three orders; Section 4.2 for the record format and the
+ * interleaved example).  Every generator emits, per stage, backward tasks in ascending
+ * microbatch order.  `out` (host) must hold `cap` >= jpp_schedule_len() records.
+ * JPP_EINVAL on bad arguments or insufficient cap. */
+jpp_status jpp_schedule_make(int kind, int P, int rank, int V, int M, jpp_task* out, int cap);
+
+/* Checks a task list (host) against the rules that follow from Section 2.2.1: every
+ * (i, ty, stage) with stage in cfg->stage_ids and 0 <= i < M appears exactly once, and
+ * BWD(i, s) comes after FWD(i, s).  On success *peak_in_flight (optional) receives the
+ * largest number of (microbatch, stage) activation stashes alive at once.
+ * JPP_ESCHED on violation. */
+jpp_status jpp_schedule_validate(const jpp_layer_config* cfg, int M, const jpp_task* tasks, int n,
+                                 int* peak_in_flight);
+
+/* ---- stage life cycle --------------------------------------------------------------- */
+
+/* Bytes of device memory a stage needs for parameters, fp32 gradients, `max_in_flight`
+ * activation stash slots (Section 2.2.1: GPipe needs M, 1F1B about the number of
+ * stages), backward workspace and send/receive staging.  0 on invalid config. */
+size_t jpp_stage_arena_bytes(const jpp_layer_config* cfg, int n_microbatches, int max_in_flight);
+
+/* Creates the executor inside the caller-owned arena (`arena_dev`, 256-byte aligned,
+ * at least jpp_stage_arena_bytes()).  The arena must outlive the stage; the library
+ * never frees it.  Gradients and parameters are NOT initialised: call
+ * jpp_stage_set_params and jpp_stage_zero_grads.  `max_in_flight` one above the
+ * schedule's peak lets the next forward's input be prefetched while a slot is still held. */
+jpp_status jpp_stage_create(const jpp_layer_config* cfg, int n_microbatches, int max_in_flight,
+                            void* arena_dev, size_t arena_bytes, jpp_stage** out);
+void jpp_stage_destroy(jpp_stage* st);
+
+/* Parameter layout of one virtual stage: tensors 0..n-1 in order (layer by layer:
+ * ln1_g [ln1_b] wqkv [bqkv] wo [bo] ln2_g [ln2_b] w1 [b1] w2 [b2]; then lnf_g [lnf_b]
+ * w_head).  shape[1] = 0 for vectors.  elem_offset is the tensor's element offset in
+ * the flat parameter buffer AND in the flat fp32 gradient buffer.  Returns the number
+ * of tensors when idx < 0 (other outputs untouched), JPP_OK (0) otherwise; a negative
+ * value (-JPP_EINVAL) on error. */
+int jpp_stage_param_info(const jpp_stage* st, int idx, const char** name, int64_t shape[2],
+                         size_t* elem_offset);
+size_t jpp_stage_param_count(const jpp_stage* st); /* elements per virtual stage */
+
+/* Copies one virtual stage's flat parameter buffer (storage dtype, param_count elements,
+ * layout above) into the arena.  vstage is the LOCAL index 0..n_virtual-1.  `src` may be
+ * a host or a device pointer (src_on_device).  Synchronous. */
+jpp_status jpp_stage_set_params(jpp_stage* st, int vstage, const void* src, int src_on_device);
+
+/* Boundary buffers, caller-owned, all device pointers to [microbatch, seq_len, d_model]
+ * tensors of the storage dtype; each host array has n_virtual * M entries indexed
+ * [vstage * M + i].  inbox_x[i]: activation received for FWD(i); inbox_cot[i]: cotangent
+ * received for BWD(i) (ignored / may be NULL for a loss_head stage); outbox_y[i]: output
+ * sent after FWD(i) (NULL array allowed for a loss_head stage); outbox_dx[i]: input
+ * cotangent sent after BWD(i).  targets[i] (loss_head only): device int32
+ * [microbatch, seq_len] token ids in [0, vocab).  The host arrays are copied. */
+jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x,
+                                   const void* const* inbox_cot, void* const* outbox_y,
+                                   void* const* outbox_dx, const int32_t* const* targets);
+
+/* grads <- 0 and losses <- 0 for all virtual stages, enqueued on `stream`. */
+jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream);
+
+/* Executes the task list (host array, read during the call only) in the order given:
+ * validation first (JPP_ESCHED / JPP_ECAPACITY: nothing is launched), then every kernel
+ * of every task is enqueued on compute_stream without any host synchronisation
+ * (Section 4.4).  Receives are copies inbox -> stage input issued on side_stream ahead of
+ * their consumer (prefetch), sends are copies stage output -> outbox issued on
+ * side_stream right after the producing task (Section 4.2); staging buffers whose send
+ * has not completed are parked in a pending-deletion queue and reclaimed later
+ * (Section 4.3).  Returns after enqueueing; results are complete when both streams are.
+ * The two streams must differ and have the default priority.  Calls on one stage must
+ * not overlap. */
+jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream,
+                         void* side_stream);
+
+/* Synchronises the streams of the last run and returns a borrowed device pointer to the
+ * flat fp32 gradient buffer of local virtual stage `vstage` (param_count elements, same
+ * offsets as the parameters).  Valid until zero_grads / destroy. */
+jpp_status jpp_stage_grads(jpp_stage* st, int vstage, const float** grads_dev, size_t* n_elems);
+
+/* loss_head stages: borrowed device pointer to the fp32 loss vector [M] (Section 3.1:
+ * losses are collected per microbatch, not averaged over microbatches). Synchronises. */
+jpp_status jpp_stage_losses(jpp_stage* st, const float** loss_dev);
+
+/* Introspection of the last run (host bookkeeping, used by tests). */
+int jpp_stage_peak_in_flight(const jpp_stage* st);   /* stash slots high-water mark            */
+int jpp_stage_pending_peak(const jpp_stage* st);     /* pending-deletion queue high-water mark */
+int jpp_stage_prefetched(const jpp_stage* st);       /* receives issued ahead of their consumer */
+int jpp_stage_host_syncs(const jpp_stage* st);       /* host-side waits inside the last run (0) */
+
+const char* jpp_last_error(void);
+
+/* ---- single operations (the kernels the executor is made of) ------------------------
+ * Exposed for op-level parity at shapes the CPU oracle cannot run end to end, and for
+ * per-kernel profiling.  All pointers are device pointers; work is enqueued on `stream`.
+ * dtype is JPP_F32 or JPP_BF16 storage; accumulation is fp32. */
+
+/* C[M,N] (op)= sum_k A(m,k) * B(n,k)  (+ bias[n]) (+ residual[m,n]).
+ * a_kstrided = 0: A(m,k) at A[m*lda + k];  1: at A[k*lda + m]  (same for B).
+ * out_mode 0: store in storage dtype; 1: store fp32; 2: C(fp32) += result.
+ * bias (storage dtype, [N]) and residual (storage dtype, ldc) may be NULL.
+ * bf16 path requires M, N, K and leading dimensions to be multiples of 8. */
+jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, int a_kstrided,
+                       const void* B, int ldb, int b_kstrided, void* C, int ldc, int out_mode,
+                       const void* bias, const void* residual, void* stream);
+
+/* Causal self-attention over a fused qkv tensor [mb*seq, (Hq + 2*Hkv)*hd] (q heads, then
+ * k heads, then v heads; query head h reads kv head h / (Hq/Hkv)).  out: [mb*seq, Hq*hd];
+ * lse: fp32 [mb, Hq, seq] natural-log-sum-exp of the scaled scores. */
+jpp_status jpp_op_attention_fwd(int dtype, int mb, int seq, int Hq, int Hkv, int hd,
+                                const void* qkv, void* out, float* lse, void* stream);
+/* dqkv has the layout of qkv.  Deterministic: no floating-point atomics.  `delta` is
+ * fp32 scratch [mb, Hq, seq]. */
+jpp_status jpp_op_attention_bwd(int dtype, int mb, int seq, int Hq, int Hkv, int hd,
+                                const void* qkv, const void* out, const float* lse,
+                                const void* dout, void* dqkv, float* delta, void* stream);
+
+/* Norm over the last axis of x [rows, d].  stats: fp32 [2*rows] (mean, rstd; mean = 0 for
+ * RMSNorm).  beta may be NULL (RMSNorm). */
+jpp_status jpp_op_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x,
+                           const void* gamma, const void* beta, void* y, float* stats,
+                           void* stream);
+/* dx = (optional dx_add) + Norm'(dy); g_gamma += sum_rows dy*xhat; g_beta += sum_rows dy
+ * (fp32, deterministic two-stage column reduction through `partial`, fp32 scratch of
+ * jpp_op_colreduce_scratch(rows, d) elements). */
+jpp_status jpp_op_norm_bwd(int dtype, int norm, int rows, int d, const void* x, const void* gamma,
+                           const float* stats, const void* dy, const void* dx_add, void* dx,
+                           float* g_gamma, float* g_beta, float* partial, void* stream);
+size_t jpp_op_colreduce_scratch(int rows, int d);
+
+/* a = act(h): h [rows, f] (GeLU) or [rows, 2f] (SwiGLU, gate | up), a [rows, f]. */
+jpp_status jpp_op_act_fwd(int dtype, int act, int rows, int f, const void* h, void* a, void* stream);
+/* dh = da * act'(h), shaped like h. */
+jpp_status jpp_op_act_bwd(int dtype, int act, int rows, int f, const void* h, const void* da,
+                          void* dh, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JPP_H */

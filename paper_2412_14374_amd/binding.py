@@ -1,0 +1,270 @@
+"""Thin ctypes binding over libjpp.so: same names as include/jpp.h, argument marshalling
+only.  Every computation happens inside the library's HIP kernels; there is no fallback.
+If the library has not been built, loading raises (build with
+`python -m paper_2412_14374_amd.build`)."""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libjpp.so")
+
+JPP_OK, JPP_EINVAL, JPP_ESCHED, JPP_ECAPACITY, JPP_EDEVICE, JPP_ESTATE = range(6)
+JPP_FWD, JPP_BWD = 0, 1
+JPP_F32, JPP_BF16 = 0, 1
+JPP_MAX_VIRTUAL = 8
+OUT_STORE, OUT_STORE_F32, OUT_ACC_F32 = 0, 1, 2
+
+
+class JppError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"jpp status {status}: {message}")
+        self.status = status
+
+
+class jpp_task(C.Structure):
+    _fields_ = [("i", C.c_int32), ("ty", C.c_int32), ("stage", C.c_int32)]
+
+
+class jpp_layer_config(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n_layers", C.c_int32), ("d_model", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("d_ffn", C.c_int32), ("seq_len", C.c_int32), ("microbatch", C.c_int32),
+                ("norm", C.c_int32), ("act", C.c_int32), ("use_bias", C.c_int32), ("rope", C.c_int32),
+                ("rope_theta", C.c_float), ("norm_eps", C.c_float), ("loss_head", C.c_int32),
+                ("vocab", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
+
+
+_lib = None
+
+_SIGNATURES = {
+    "jpp_schedule_len": (C.c_int, [C.c_int] * 5),
+    "jpp_schedule_make": (C.c_int, [C.c_int] * 5 + [C.POINTER(jpp_task), C.c_int]),
+    "jpp_schedule_validate": (C.c_int, [C.POINTER(jpp_layer_config), C.c_int, C.POINTER(jpp_task), C.c_int,
+                                        C.POINTER(C.c_int)]),
+    "jpp_stage_arena_bytes": (C.c_size_t, [C.POINTER(jpp_layer_config), C.c_int, C.c_int]),
+    "jpp_stage_create": (C.c_int, [C.POINTER(jpp_layer_config), C.c_int, C.c_int, C.c_void_p, C.c_size_t,
+                                   C.POINTER(C.c_void_p)]),
+    "jpp_stage_destroy": (None, [C.c_void_p]),
+    "jpp_stage_param_info": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
+                                       C.POINTER(C.c_size_t)]),
+    "jpp_stage_param_count": (C.c_size_t, [C.c_void_p]),
+    "jpp_stage_set_params": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int]),
+    "jpp_stage_bind_boundary": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_void_p)] * 5),
+    "jpp_stage_zero_grads": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "jpp_stage_run": (C.c_int, [C.c_void_p, C.POINTER(jpp_task), C.c_int, C.c_void_p, C.c_void_p]),
+    "jpp_stage_grads": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
+    "jpp_stage_losses": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p)]),
+    "jpp_stage_peak_in_flight": (C.c_int, [C.c_void_p]),
+    "jpp_stage_pending_peak": (C.c_int, [C.c_void_p]),
+    "jpp_stage_prefetched": (C.c_int, [C.c_void_p]),
+    "jpp_stage_host_syncs": (C.c_int, [C.c_void_p]),
+    "jpp_last_error": (C.c_char_p, []),
+    "jpp_op_gemm": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                              C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "jpp_op_attention_fwd": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 4),
+    "jpp_op_attention_bwd": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 7),
+    "jpp_op_norm_fwd": (C.c_int, [C.c_int] * 4 + [C.c_float] + [C.c_void_p] * 6),
+    "jpp_op_norm_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 10),
+    "jpp_op_colreduce_scratch": (C.c_size_t, [C.c_int, C.c_int]),
+    "jpp_op_act_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 3),
+    "jpp_op_act_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
+}
+
+
+def lib():
+    """Loads libjpp.so once.  Raises if it has not been built: there is no other path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_14374_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def exported_names():
+    return sorted(_SIGNATURES)
+
+
+def last_error():
+    return lib().jpp_last_error().decode()
+
+
+def _check(status):
+    if status != JPP_OK:
+        raise JppError(status, last_error())
+
+
+def make_config(w):
+    """w: any object with the jpp_layer_config field names as attributes plus `stage_ids`."""
+    c = jpp_layer_config()
+    for f, _ in jpp_layer_config._fields_:
+        if f in ("stage_ids", "n_virtual"):
+            continue
+        setattr(c, f, getattr(w, f))
+    ids = list(w.stage_ids)
+    c.n_virtual = len(ids)
+    for k, s in enumerate(ids):
+        c.stage_ids[k] = s
+    return c
+
+
+def tasks_array(tasks):
+    """tasks: iterable of (i, ty, stage) with ty 0/1 or 'fwd'/'bwd'."""
+    tasks = list(tasks)
+    arr = (jpp_task * max(1, len(tasks)))()
+    for k, (i, ty, s) in enumerate(tasks):
+        arr[k].i = i
+        arr[k].ty = {"fwd": JPP_FWD, "bwd": JPP_BWD}.get(ty, ty)
+        arr[k].stage = s
+    return arr, len(tasks)
+
+
+def jpp_schedule_len(kind, P, rank, V, M):
+    return lib().jpp_schedule_len(kind, P, rank, V, M)
+
+
+def jpp_schedule_make(kind, P, rank, V, M):
+    n = jpp_schedule_len(kind, P, rank, V, M)
+    if n < 0:
+        raise JppError(JPP_EINVAL, "bad schedule arguments")
+    arr = (jpp_task * n)()
+    _check(lib().jpp_schedule_make(kind, P, rank, V, M, arr, n))
+    return [(t.i, t.ty, t.stage) for t in arr]
+
+
+def jpp_schedule_validate(cfg, M, tasks):
+    arr, n = tasks_array(tasks)
+    peak = C.c_int(0)
+    _check(lib().jpp_schedule_validate(C.byref(cfg), M, arr, n, C.byref(peak)))
+    return peak.value
+
+
+def jpp_stage_arena_bytes(cfg, M, max_in_flight):
+    n = lib().jpp_stage_arena_bytes(C.byref(cfg), M, max_in_flight)
+    if n == 0:
+        raise JppError(JPP_EINVAL, last_error())
+    return n
+
+
+def jpp_stage_create(cfg, M, max_in_flight, arena_ptr, arena_bytes):
+    h = C.c_void_p()
+    _check(lib().jpp_stage_create(C.byref(cfg), M, max_in_flight, C.c_void_p(arena_ptr), arena_bytes, C.byref(h)))
+    return h
+
+
+def jpp_stage_destroy(h):
+    lib().jpp_stage_destroy(h)
+
+
+def jpp_stage_param_info(h):
+    """Returns [(name, shape tuple, element offset)]."""
+    n = lib().jpp_stage_param_info(h, -1, None, None, None)
+    if n < 0:
+        raise JppError(-n, last_error())
+    out = []
+    for k in range(n):
+        name = C.c_char_p()
+        shape = (C.c_int64 * 2)()
+        off = C.c_size_t()
+        _check(lib().jpp_stage_param_info(h, k, C.byref(name), shape, C.byref(off)))
+        shp = (shape[0],) if shape[1] == 0 else (shape[0], shape[1])
+        out.append((name.value.decode(), shp, off.value))
+    return out
+
+
+def jpp_stage_param_count(h):
+    return lib().jpp_stage_param_count(h)
+
+
+def jpp_stage_set_params(h, vstage, ptr, on_device):
+    _check(lib().jpp_stage_set_params(h, vstage, C.c_void_p(ptr), 1 if on_device else 0))
+
+
+def _ptr_array(ptrs):
+    if ptrs is None:
+        return None
+    arr = (C.c_void_p * len(ptrs))()
+    for k, p in enumerate(ptrs):
+        arr[k] = p
+    return arr
+
+
+def jpp_stage_bind_boundary(h, inbox_x, inbox_cot, outbox_y, outbox_dx, targets):
+    """Each argument: list of device addresses (ints), indexed [vstage*M + i], or None."""
+    _check(lib().jpp_stage_bind_boundary(h, _ptr_array(inbox_x), _ptr_array(inbox_cot), _ptr_array(outbox_y),
+                                         _ptr_array(outbox_dx), _ptr_array(targets)))
+
+
+def jpp_stage_zero_grads(h, stream):
+    _check(lib().jpp_stage_zero_grads(h, C.c_void_p(stream)))
+
+
+def jpp_stage_run(h, tasks_arr, n, compute_stream, side_stream):
+    _check(lib().jpp_stage_run(h, tasks_arr, n, C.c_void_p(compute_stream), C.c_void_p(side_stream)))
+
+
+def jpp_stage_grads(h, vstage):
+    p = C.c_void_p()
+    n = C.c_size_t()
+    _check(lib().jpp_stage_grads(h, vstage, C.byref(p), C.byref(n)))
+    return p.value, n.value
+
+
+def jpp_stage_losses(h):
+    p = C.c_void_p()
+    _check(lib().jpp_stage_losses(h, C.byref(p)))
+    return p.value
+
+
+def jpp_stage_peak_in_flight(h):
+    return lib().jpp_stage_peak_in_flight(h)
+
+
+def jpp_stage_pending_peak(h):
+    return lib().jpp_stage_pending_peak(h)
+
+
+def jpp_stage_prefetched(h):
+    return lib().jpp_stage_prefetched(h)
+
+
+def jpp_stage_host_syncs(h):
+    return lib().jpp_stage_host_syncs(h)
+
+
+def jpp_op_gemm(dtype, M, N, K, A, lda, a_ks, B, ldb, b_ks, Cp, ldc, out_mode, bias, residual, stream):
+    _check(lib().jpp_op_gemm(dtype, M, N, K, A, lda, int(a_ks), B, ldb, int(b_ks), Cp, ldc, out_mode, bias,
+                             residual, stream))
+
+
+def jpp_op_attention_fwd(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, stream):
+    _check(lib().jpp_op_attention_fwd(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, stream))
+
+
+def jpp_op_attention_bwd(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, stream):
+    _check(lib().jpp_op_attention_bwd(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, stream))
+
+
+def jpp_op_norm_fwd(dtype, norm, rows, d, eps, x, gamma, beta, y, stats, stream):
+    _check(lib().jpp_op_norm_fwd(dtype, norm, rows, d, eps, x, gamma, beta, y, stats, stream))
+
+
+def jpp_op_norm_bwd(dtype, norm, rows, d, x, gamma, stats, dy, dx_add, dx, g_gamma, g_beta, partial, stream):
+    _check(lib().jpp_op_norm_bwd(dtype, norm, rows, d, x, gamma, stats, dy, dx_add, dx, g_gamma, g_beta, partial,
+                                 stream))
+
+
+def jpp_op_colreduce_scratch(rows, d):
+    return lib().jpp_op_colreduce_scratch(rows, d)
+
+
+def jpp_op_act_fwd(dtype, act, rows, f, h, a, stream):
+    _check(lib().jpp_op_act_fwd(dtype, act, rows, f, h, a, stream))
+
+
+def jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream):
+    _check(lib().jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream))

@@ -1,0 +1,342 @@
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+//
+//   C[M,N] (op)= sum_k A(m,k) * B(n,k)  (+ bias[n]) (+ residual[m,n])
+//
+// Either operand may be stored "k-contiguous" (element (r,k) at P[r*ld + k]) or
+// "k-strided" (at P[k*ld + r]).  The three GEMMs of a linear layer y = x W^T map to
+//   forward  y  = x  W^T : A = x  (k-contig), B = W  (k-contig)
+//   dgrad    dx = dy W   : A = dy (k-contig), B = W  (k-strided)
+//   wgrad    G += dy^T x : A = dy (k-strided), B = x (k-strided), fp32 read-modify-write of G
+// so no transposed copy of a weight or an activation ever exists in HBM.  The last form is
+// the `grads += mugrads` of the paper's Section 3.1 fused into the producing GEMM: the
+// unrounded fp32 accumulator is added to the fp32 gradient.
+//
+// Design (one workgroup = one BM x BN tile of C, BK = 64):
+//  * LDS holds each operand tile as [rows][64 k] bf16, 128 bytes per row, with the 16-byte
+//    chunk index XOR-swizzled by ((row ^ row>>3) & 7): the 16-byte MFMA fragment reads
+//    (lanes = consecutive rows, same k chunk), the row-major staging writes (lanes =
+//    consecutive k chunks) and the transposing staging writes (lanes = rows 8 apart) all
+//    spread over all banks.
+//  * A k-strided operand is transposed on the way in: a thread loads an 8(k) x 8(row) block
+//    as eight 16-byte row segments, transposes it in registers with byte permutes and writes
+//    eight 16-byte k-runs.  The MFMA loop is identical for all four layout combinations.
+//  * Global loads are raw buffer loads: rows beyond the matrix read as zero through the
+//    hardware range check, the contiguous dimension is predicated, so M, N, K need only be
+//    multiples of 8.  Loads for tile k+1 are issued before the MFMAs of tile k and written
+//    to the other LDS buffer afterwards (one barrier per k tile).
+//  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
+//    works on a contiguous band of tiles and shares operand panels in its own L2.
+#include "device_utils.h"
+#include "internal.h"
+
+namespace jpp {
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int kRowBytes = BK * 2;  // 128
+constexpr uint32_t kOOB = 0x7FFFFFFFu;
+constexpr uint32_t kMaxRecords = 0x7FFFFF00u;
+
+__device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  // 0x00020000: raw buffer, 32-bit data format field for gfx9 (DATA_FORMAT = 32)
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+struct Epilogue {
+  void* C; int ldc; int out_mode;
+  const bf16* bias; const bf16* residual;
+};
+
+struct Operand {
+  const bf16* p; int ld; int rows;  // rows = M (for A) or N (for B)
+};
+
+// Transposes an 8x8 block of bf16: in[j] holds 8 consecutive rows' elements at k = j; out[r]
+// holds 8 consecutive k at row r.
+__device__ inline void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int w = r >> 1;
+    const uint32_t sel = (r & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) out[r][p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
+  }
+}
+
+template <int R, int NT, bool KS, int PHASE>
+struct Loader {
+  // k-contiguous: R*8 chunks over NT threads.  k-strided: R units (8k x 8rows blocks), unit u
+  // handled by thread (u + PHASE) % NT when R <= NT.
+  static constexpr int kChunksPerThread = KS ? 8 : (R * 8 / NT);
+  static constexpr int kUnits = KS ? ((R + NT - 1) / NT) : 1;
+  static_assert(KS || (R * 8) % NT == 0, "tile rows x 8 must be a multiple of the thread count");
+  static_assert(!KS || R <= NT, "k-strided loader expects at most one unit per thread");
+  u32x4 regs[kChunksPerThread];
+  uint32_t goff[kChunksPerThread];  // tile-local byte offsets (k-contig) / row offsets (k-strided)
+  bool active;
+  int unit;
+
+  __device__ inline void init(const Operand& op, int r0) {
+    const int tid = threadIdx.x;
+    if constexpr (!KS) {
+      active = true;
+#pragma unroll
+      for (int i = 0; i < kChunksPerThread; ++i) {
+        const int c = tid + NT * i;
+        const int row = c >> 3, kc = c & 7;
+        goff[i] = (uint32_t)(row * op.ld + kc * 8) * 2u;
+      }
+    } else {
+      unit = (tid + NT - PHASE) % NT;
+      active = unit < R;
+      const int rb = unit % (R / 8), kb = unit / (R / 8);
+      const bool col_ok = (r0 + rb * 8) < op.rows;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        goff[j] = (active && col_ok) ? (uint32_t)((kb * 8 + j) * op.ld + rb * 8) * 2u : kOOB;
+    }
+  }
+
+  __device__ inline void issue(const Operand& op, int r0, int k0, int K) {
+    if constexpr (!KS) {
+      const bf16* base = op.p + (size_t)r0 * op.ld + k0;
+      const long long rem = ((long long)(op.rows - r0) * op.ld - k0) * 2;
+      const auto rs = make_rsrc(base, (uint32_t)(rem > (long long)kMaxRecords ? kMaxRecords : (rem < 0 ? 0 : rem)));
+#pragma unroll
+      for (int i = 0; i < kChunksPerThread; ++i) {
+        const int kc = (threadIdx.x + NT * i) & 7;
+        const uint32_t off = (k0 + kc * 8 < K) ? goff[i] : kOOB;
+        regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+      }
+    } else {
+      const bf16* base = op.p + (size_t)k0 * op.ld + r0;
+      const long long rem = ((long long)(K - k0) * op.ld - r0) * 2;
+      const auto rs = make_rsrc(base, (uint32_t)(rem > (long long)kMaxRecords ? kMaxRecords : (rem < 0 ? 0 : rem)));
+#pragma unroll
+      for (int j = 0; j < 8; ++j) regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)goff[j], 0, 0);
+    }
+  }
+
+  __device__ inline void store(char* lds) {
+    if constexpr (!KS) {
+#pragma unroll
+      for (int i = 0; i < kChunksPerThread; ++i) {
+        const int c = threadIdx.x + NT * i;
+        const int row = c >> 3, kc = c & 7;
+        *reinterpret_cast<u32x4*>(lds + row * kRowBytes + ((kc ^ swz(row)) << 4)) = regs[i];
+      }
+    } else {
+      if (active) {
+        u32x4 t[8];
+        transpose8x8(regs, t);
+        const int rb = unit % (R / 8), kb = unit / (R / 8);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const int row = rb * 8 + r;
+          *reinterpret_cast<u32x4*>(lds + row * kRowBytes + ((kb ^ swz(row)) << 4)) = t[r];
+        }
+      }
+    }
+  }
+};
+
+// Maps the linear workgroup id to a tile.  Ids are dealt round-robin to the 8 XCDs, so the
+// ids {x, x+8, x+16, ...} share one L2: give each XCD a contiguous range of tile numbers, and
+// number tiles in bands of kBand tile-rows, column-major inside a band.
+__device__ inline void tile_of(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int total = tiles_m * tiles_n;
+  constexpr int kXcd = 8;
+  int t = pid;
+  if (total >= kXcd * 4) {
+    const int per = (total + kXcd - 1) / kXcd;
+    const int x = pid % kXcd, r = pid / kXcd;
+    const int full = total % kXcd == 0 ? kXcd : total % kXcd;  // XCDs holding `per` tiles
+    // XCD x owns tiles [start_x, start_x + count_x): the first `full` XCDs get `per`, the rest per-1.
+    const int start = x < full ? x * per : full * per + (x - full) * (per - 1);
+    t = start + r;
+  }
+  constexpr int kBand = 8;
+  const int band_tiles = kBand * tiles_n;
+  const int band = t / band_tiles;
+  const int first_m = band * kBand;
+  const int rows_in_band = (tiles_m - first_m) < kBand ? (tiles_m - first_m) : kBand;
+  const int in_band = t - band * band_tiles;
+  tm = first_m + in_band % rows_in_band;
+  tn = in_band / rows_in_band;
+}
+
+template <int BM, int BN, int WM, int WN, bool AKS, bool BKS>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, int K, Operand A, Operand B,
+                                                                  Epilogue ep) {
+  constexpr int NT = 64 * WM * WN;
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int MI = TM / 32, NI = TN / 32;
+  constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  // buffer s: A at lds + s*(kABytes + kBBytes), B right after it
+
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  int tm, tn;
+  tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  Loader<BM, NT, AKS, 0> la;
+  Loader<BN, NT, BKS, NT / 2> lb;
+  la.init(A, m0);
+  lb.init(B, n0);
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment read offsets: row-dependent part is loop invariant
+  int a_row_off[MI], a_swz[MI], b_row_off[NI], b_swz[NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int row = wm * TM + i * 32 + l32;
+    a_row_off[i] = row * kRowBytes;
+    a_swz[i] = swz(row);
+  }
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int row = wn * TN + j * 32 + l32;
+    b_row_off[j] = row * kRowBytes;
+    b_swz[j] = swz(row);
+  }
+
+  const int nk = (K + BK - 1) / BK;
+  la.issue(A, m0, 0, K);
+  lb.issue(B, n0, 0, K);
+  la.store(lds);
+  lb.store(lds + kABytes);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    char* cur = lds + (kt & 1) * (kABytes + kBBytes);
+    char* nxt = lds + ((kt + 1) & 1) * (kABytes + kBBytes);
+    const bool more = kt + 1 < nk;
+    if (more) {
+      la.issue(A, m0, (kt + 1) * BK, K);
+      lb.issue(B, n0, (kt + 1) * BK, K);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 af[MI], bfr[NI];
+      const int chunk = kk * 2 + half;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(cur + a_row_off[i] + ((chunk ^ a_swz[i]) << 4));
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(cur + kABytes + b_row_off[j] + ((chunk ^ b_swz[j]) << 4));
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      la.store(nxt);
+      lb.store(nxt + kABytes);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue.  Accumulator register r of lane (l32, half) is C[8*(r/4) + 4*half + r%4][l32]
+  // of its 32x32 block.
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int n = n0 + wn * TN + j * 32 + l32;
+    if (n >= N) continue;
+    const float bias = ep.bias ? (float)ep.bias[n] : 0.f;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (m >= M) continue;
+        const size_t idx = (size_t)m * ep.ldc + n;
+        float v = acc[i][j][r] + bias;
+        if (ep.residual) v += (float)ep.residual[idx];
+        if (ep.out_mode == OUT_STORE) {
+          reinterpret_cast<bf16*>(ep.C)[idx] = (bf16)v;
+        } else if (ep.out_mode == OUT_STORE_F32) {
+          reinterpret_cast<float*>(ep.C)[idx] = v;
+        } else {
+          float* c = reinterpret_cast<float*>(ep.C) + idx;
+          *c = *c + v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, bool AKS, bool BKS>
+hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
+  constexpr int NT = 64 * WM * WN;
+  constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * kRowBytes;
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, AKS, BKS>;
+  static bool attr_set = false;  // per instantiation; the attribute is per function, set once
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  Operand A{(const bf16*)g.A, g.lda, g.M};
+  Operand B{(const bf16*)g.B, g.ldb, g.N};
+  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual};
+  kern<<<tiles, NT, lds_bytes, s>>>(g.M, g.N, g.K, A, B, ep);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_layout(const GemmDesc& g, hipStream_t s) {
+  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, WM, WN, false, false>(g, s);
+  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, WM, WN, false, true>(g, s);
+  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, WM, WN, true, true>(g, s);
+  return launch_cfg<BM, BN, WM, WN, true, false>(g, s);
+}
+
+}  // namespace
+
+bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why) {
+  auto mult8 = [](long long v) { return v > 0 && v % 8 == 0; };
+  if (!mult8(g.M) || !mult8(g.N) || !mult8(g.K) || !mult8(g.lda) || !mult8(g.ldb) || !mult8(g.ldc)) {
+    why = "bf16 GEMM needs M, N, K and leading dimensions to be positive multiples of 8";
+    return false;
+  }
+  // tile-local offsets are 32-bit byte offsets: 256 rows (k-contig) or 64 k-rows (k-strided) of ld
+  const long long a_span = (g.a_kstrided ? 64LL : 256LL) * g.lda * 2;
+  const long long b_span = (g.b_kstrided ? 64LL : 256LL) * g.ldb * 2;
+  if (a_span >= (long long)kMaxRecords || b_span >= (long long)kMaxRecords) {
+    why = "leading dimension too large for 32-bit tile offsets";
+    return false;
+  }
+  if ((g.a_kstrided ? g.lda < g.M : g.lda < g.K) || (g.b_kstrided ? g.ldb < g.N : g.ldb < g.K) || g.ldc < g.N) {
+    why = "leading dimension smaller than the row length";
+    return false;
+  }
+  return true;
+}
+
+hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
+  // Large tiles when they still give every CU work; smaller ones otherwise.
+  const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  if (big_tiles >= 192) return launch_layout<256, 256, 2, 2>(g, s);
+  return launch_layout<128, 128, 2, 2>(g, s);
+}
+
+}  // namespace jpp

@@ -1,0 +1,111 @@
+// C entry points for single operations (see include/jpp.h): argument checks, then the same
+// launchers the stage executor uses.
+#include "internal.h"
+
+using namespace jpp;
+
+namespace {
+bool dtype_ok(int dtype) { return dtype == JPP_F32 || dtype == JPP_BF16; }
+int chunk_of(int dtype) { return dtype == JPP_BF16 ? 8 : 4; }
+}  // namespace
+
+extern "C" {
+
+jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, int a_kstrided, const void* B,
+                       int ldb, int b_kstrided, void* C, int ldc, int out_mode, const void* bias,
+                       const void* residual, void* stream) {
+  if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
+  if (!A || !B || !C) return fail(JPP_EINVAL, "null operand");
+  if (M < 1 || N < 1 || K < 1) return fail(JPP_EINVAL, "sizes must be positive");
+  if (out_mode < OUT_STORE || out_mode > OUT_ACC_F32) return fail(JPP_EINVAL, "bad out_mode");
+  GemmDesc g{M, N, K, A, lda, a_kstrided != 0, B, ldb, b_kstrided != 0, C, ldc, out_mode, bias, residual};
+  hipError_t e;
+  if (dtype == JPP_BF16) {
+    std::string why;
+    if (!gemm_bf16_shape_ok(g, why)) return fail(JPP_EINVAL, why);
+    e = launch_gemm_bf16(g, (hipStream_t)stream);
+  } else {
+    if ((a_kstrided ? lda < M : lda < K) || (b_kstrided ? ldb < N : ldb < K) || ldc < N)
+      return fail(JPP_EINVAL, "leading dimension smaller than the row length");
+    e = launch_gemm_f32(g, (hipStream_t)stream);
+  }
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "gemm launch");
+}
+
+static jpp_status attn_check(int dtype, int mb, int seq, int Hq, int Hkv, int hd) {
+  if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
+  if (mb < 1 || seq < 1 || Hq < 1 || Hkv < 1 || hd < 1) return fail(JPP_EINVAL, "sizes must be positive");
+  if (Hq % Hkv != 0) return fail(JPP_EINVAL, "Hq must be a multiple of Hkv");
+  if (hd % chunk_of(dtype) != 0 || hd > 256) return fail(JPP_EINVAL, "unsupported head_dim");
+  return JPP_OK;
+}
+
+jpp_status jpp_op_attention_fwd(int dtype, int mb, int seq, int Hq, int Hkv, int hd, const void* qkv, void* out,
+                                float* lse, void* stream) {
+  jpp_status rc = attn_check(dtype, mb, seq, Hq, Hkv, hd);
+  if (rc != JPP_OK) return rc;
+  if (!qkv || !out || !lse) return fail(JPP_EINVAL, "null operand");
+  AttnDesc a{mb, seq, Hq, Hkv, hd, qkv, out, lse, nullptr, nullptr, nullptr};
+  hipError_t e = (dtype == JPP_BF16 && attention_mfma_supported(a))
+                     ? launch_attention_fwd_mfma(a, (hipStream_t)stream)
+                     : launch_attention_fwd_generic(dtype, a, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "attention forward launch");
+}
+
+jpp_status jpp_op_attention_bwd(int dtype, int mb, int seq, int Hq, int Hkv, int hd, const void* qkv,
+                                const void* out, const float* lse, const void* dout, void* dqkv, float* delta,
+                                void* stream) {
+  jpp_status rc = attn_check(dtype, mb, seq, Hq, Hkv, hd);
+  if (rc != JPP_OK) return rc;
+  if (!qkv || !out || !lse || !dout || !dqkv || !delta) return fail(JPP_EINVAL, "null operand");
+  AttnDesc a{mb, seq, Hq, Hkv, hd, qkv, const_cast<void*>(out), const_cast<float*>(lse), dout, dqkv, delta};
+  hipError_t e = (dtype == JPP_BF16 && attention_mfma_supported(a))
+                     ? launch_attention_bwd_mfma(a, (hipStream_t)stream)
+                     : launch_attention_bwd_generic(dtype, a, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "attention backward launch");
+}
+
+jpp_status jpp_op_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x, const void* gamma,
+                           const void* beta, void* y, float* stats, void* stream) {
+  if (!dtype_ok(dtype) || (norm != JPP_LAYERNORM && norm != JPP_RMSNORM)) return fail(JPP_EINVAL, "bad dtype/norm");
+  if (rows < 1 || !norm_shape_ok(dtype, d)) return fail(JPP_EINVAL, "unsupported norm shape");
+  if (!x || !gamma || !y || !stats) return fail(JPP_EINVAL, "null operand");
+  hipError_t e = launch_norm_fwd(dtype, norm, rows, d, eps, x, gamma, beta, y, stats, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "norm forward launch");
+}
+
+size_t jpp_op_colreduce_scratch(int rows, int d) {
+  if (rows < 1 || d < 1) return 0;
+  return 2 * (size_t)colreduce_blocks(rows) * d;
+}
+
+jpp_status jpp_op_norm_bwd(int dtype, int norm, int rows, int d, const void* x, const void* gamma,
+                           const float* stats, const void* dy, const void* dx_add, void* dx, float* g_gamma,
+                           float* g_beta, float* partial, void* stream) {
+  if (!dtype_ok(dtype) || (norm != JPP_LAYERNORM && norm != JPP_RMSNORM)) return fail(JPP_EINVAL, "bad dtype/norm");
+  if (rows < 1 || !norm_shape_ok(dtype, d)) return fail(JPP_EINVAL, "unsupported norm shape");
+  if (!x || !gamma || !stats || !dy || !dx || !g_gamma || !partial) return fail(JPP_EINVAL, "null operand");
+  if (dx == dx_add) return fail(JPP_EINVAL, "dx must not alias dx_add");
+  hipError_t e = launch_norm_bwd(dtype, norm, rows, d, x, gamma, stats, dy, dx_add, dx, g_gamma, g_beta, partial,
+                                 (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "norm backward launch");
+}
+
+jpp_status jpp_op_act_fwd(int dtype, int act, int rows, int f, const void* h, void* a, void* stream) {
+  if (!dtype_ok(dtype) || act < JPP_GELU || act > JPP_SWIGLU) return fail(JPP_EINVAL, "bad dtype/act");
+  if (rows < 1 || f < 1 || f % chunk_of(dtype) != 0) return fail(JPP_EINVAL, "f must be a multiple of the 16-byte chunk");
+  if (!h || !a) return fail(JPP_EINVAL, "null operand");
+  hipError_t e = launch_act_fwd(dtype, act, rows, f, h, a, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "activation forward launch");
+}
+
+jpp_status jpp_op_act_bwd(int dtype, int act, int rows, int f, const void* h, const void* da, void* dh,
+                          void* stream) {
+  if (!dtype_ok(dtype) || act < JPP_GELU || act > JPP_SWIGLU) return fail(JPP_EINVAL, "bad dtype/act");
+  if (rows < 1 || f < 1 || f % chunk_of(dtype) != 0) return fail(JPP_EINVAL, "f must be a multiple of the 16-byte chunk");
+  if (!h || !da || !dh) return fail(JPP_EINVAL, "null operand");
+  hipError_t e = launch_act_bwd(dtype, act, rows, f, h, da, dh, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "activation backward launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,550 @@
+// Bandwidth-bound kernels of the stage: norms, activations, RoPE, bias/gain gradients,
+// cross-entropy, zero fill.  All are written for 64-wide wavefronts with 16-byte
+// accesses per lane and deterministic (fixed-order) reductions; math is fp32.
+//
+// The paper defines none of these operations (its Evaluation section only names the
+// GPT-3 and Llama 2 model families); the formulas are the standard ones and are stated
+// next to each kernel.
+#include "device_utils.h"
+#include "internal.h"
+
+namespace jpp {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+// Reduces two values at once over the workgroup.
+__device__ inline void block_sum2(float& a, float& b, float* red /* >= 2*kWaves */) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int w = threadIdx.x / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) { red[w] = a; red[kWaves + w] = b; }
+  __syncthreads();
+  float ta = 0.f, tb = 0.f;
+#pragma unroll
+  for (int i = 0; i < kWaves; ++i) { ta += red[i]; tb += red[kWaves + i]; }
+  a = ta; b = tb;
+}
+
+// ---------------------------------------------------------------------------------------
+// Norm forward.  LayerNorm: y = (x - mean) * rstd * gamma + beta, rstd = 1/sqrt(var + eps),
+// biased variance.  RMSNorm: y = x * rstd * gamma, rstd = 1/sqrt(mean(x^2) + eps).
+// One workgroup per row; the row stays in registers between the statistics and the
+// normalisation, so x is read once.  stats[2r] = mean (0 for RMSNorm), stats[2r+1] = rstd.
+template <typename T, int MAXC>
+__global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const T* __restrict__ x,
+                                                            const T* __restrict__ gamma,
+                                                            const T* __restrict__ beta,
+                                                            T* __restrict__ y, float* __restrict__ stats,
+                                                            int d, float eps, int norm) {
+  __shared__ float red[2 * kWaves];
+  constexpr int N = Chunk<T>::N;
+  const int nchunks = d / N;
+  const size_t base = (size_t)blockIdx.x * d;
+  Chunk<T> xs[MAXC];
+  float s = 0.f, ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < nchunks) {
+      xs[j] = load_chunk(x + base + (size_t)c * N);
+#pragma unroll
+      for (int e = 0; e < N; ++e) { const float v = xs[j].get(e); s += v; ss += v * v; }
+    }
+  }
+  float mean = 0.f, rstd;
+  const float inv_d = 1.f / (float)d;
+  if (norm == JPP_LAYERNORM) {
+    float dummy = 0.f;
+    block_sum2(s, dummy, red);
+    mean = s * inv_d;
+    float v2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+      const int c = threadIdx.x + j * kThreads;
+      if (c < nchunks) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) { const float t = xs[j].get(e) - mean; v2 += t * t; }
+      }
+    }
+    dummy = 0.f;
+    block_sum2(v2, dummy, red);
+    rstd = rsqrtf(v2 * inv_d + eps);
+  } else {
+    float dummy = 0.f;
+    block_sum2(ss, dummy, red);
+    rstd = rsqrtf(ss * inv_d + eps);
+  }
+  if (threadIdx.x == 0) { stats[2 * (size_t)blockIdx.x] = mean; stats[2 * (size_t)blockIdx.x + 1] = rstd; }
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < nchunks) {
+      const Chunk<T> g = load_chunk(gamma + (size_t)c * N);
+      Chunk<T> o;
+      if (beta != nullptr) {
+        const Chunk<T> b = load_chunk(beta + (size_t)c * N);
+#pragma unroll
+        for (int e = 0; e < N; ++e) o.set(e, (xs[j].get(e) - mean) * rstd * g.get(e) + b.get(e));
+      } else {
+#pragma unroll
+        for (int e = 0; e < N; ++e) o.set(e, (xs[j].get(e) - mean) * rstd * g.get(e));
+      }
+      store_chunk(y + base + (size_t)c * N, o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Norm backward.  With xhat = (x - mean) * rstd and dxhat = dy * gamma:
+//   LayerNorm: dx = rstd * (dxhat - mean_d(dxhat) - xhat * mean_d(dxhat * xhat))
+//   RMSNorm:   dx = rstd * (dxhat - xhat * mean_d(dxhat * xhat))
+//   dgamma = sum_rows dy * xhat,  dbeta = sum_rows dy.
+// dx_add (optional) is added to dx (the residual branch's cotangent).
+// A workgroup owns the rows {b, b + nblk, ...}; it keeps per-column partial sums of
+// dgamma/dbeta in registers and writes them to partial[b, :]; a second kernel adds the
+// nblk partials in ascending order into the fp32 gradient (no atomics).
+template <typename T, int MAXC>
+__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
+    const T* __restrict__ dy, const T* __restrict__ dx_add, T* __restrict__ dx,
+    float* __restrict__ partial_g, float* __restrict__ partial_b, int rows, int d, int norm) {
+  __shared__ float red[2 * kWaves];
+  constexpr int N = Chunk<T>::N;
+  const int nchunks = d / N;
+  const float inv_d = 1.f / (float)d;
+  float pg[MAXC][N], pb[MAXC][N];
+  Chunk<T> gs[MAXC];
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < nchunks) gs[j] = load_chunk(gamma + (size_t)c * N);
+#pragma unroll
+    for (int e = 0; e < N; ++e) { pg[j][e] = 0.f; pb[j][e] = 0.f; }
+  }
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    const size_t base = (size_t)r * d;
+    const float mean = stats[2 * (size_t)r], rstd = stats[2 * (size_t)r + 1];
+    Chunk<T> xs[MAXC], ds[MAXC];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+      const int c = threadIdx.x + j * kThreads;
+      if (c < nchunks) {
+        xs[j] = load_chunk(x + base + (size_t)c * N);
+        ds[j] = load_chunk(dy + base + (size_t)c * N);
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+          const float xh = (xs[j].get(e) - mean) * rstd;
+          const float dv = ds[j].get(e);
+          const float dxh = dv * gs[j].get(e);
+          s1 += dxh;
+          s2 += dxh * xh;
+          pg[j][e] += dv * xh;
+          pb[j][e] += dv;
+        }
+      }
+    }
+    block_sum2(s1, s2, red);
+    const float m1 = (norm == JPP_LAYERNORM) ? s1 * inv_d : 0.f;
+    const float m2 = s2 * inv_d;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+      const int c = threadIdx.x + j * kThreads;
+      if (c < nchunks) {
+        Chunk<T> o;
+        Chunk<T> add = xs[j];
+        if (dx_add != nullptr) add = load_chunk(dx_add + base + (size_t)c * N);
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+          const float xh = (xs[j].get(e) - mean) * rstd;
+          const float dxh = ds[j].get(e) * gs[j].get(e);
+          float v = rstd * (dxh - m1 - xh * m2);
+          if (dx_add != nullptr) v += add.get(e);
+          o.set(e, v);
+        }
+        store_chunk(dx + base + (size_t)c * N, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    if (c < nchunks) {
+      const size_t o = (size_t)blockIdx.x * d + (size_t)c * N;
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        partial_g[o + e] = pg[j][e];
+        if (partial_b != nullptr) partial_b[o + e] = pb[j][e];
+      }
+    }
+  }
+}
+
+// g[col] += sum_{b ascending} partial[b, col]
+__global__ __launch_bounds__(kThreads) void colreduce_finish_kernel(const float* __restrict__ partial,
+                                                                    int nblk, int n, float* __restrict__ g) {
+  const int col = blockIdx.x * kThreads + threadIdx.x;
+  if (col >= n) return;
+  float acc = 0.f;
+  for (int b = 0; b < nblk; ++b) acc += partial[(size_t)b * n + col];
+  g[col] += acc;
+}
+
+// partial[b, col] = sum over rows {b, b + nblk, ...} of dy[r, col]
+template <typename T>
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __restrict__ dy, int ld, int rows,
+                                                                  int n, float* __restrict__ partial) {
+  constexpr int N = Chunk<T>::N;
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c * N >= n) return;
+  float acc[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) acc[e] = 0.f;
+  for (int r = blockIdx.y; r < rows; r += gridDim.y) {
+    const Chunk<T> v = load_chunk(dy + (size_t)r * ld + (size_t)c * N);
+#pragma unroll
+    for (int e = 0; e < N; ++e) acc[e] += v.get(e);
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) partial[(size_t)blockIdx.y * n + (size_t)c * N + e] = acc[e];
+}
+
+// ---------------------------------------------------------------------------------------
+// Activations.  GeLU (erf form): a = h * Phi(h), Phi the standard normal CDF;
+// a' = Phi(h) + h * phi(h).  Tanh form: 0.5 h (1 + tanh(k0 (h + k1 h^3))).
+// SwiGLU on h = [gate | up]: a = silu(gate) * up, silu(t) = t * sigmoid(t),
+// silu'(t) = sigmoid(t) * (1 + t * (1 - sigmoid(t))).
+__device__ inline float gelu_erf(float h) { return 0.5f * h * (1.f + erff(h * 0.70710678118654752f)); }
+__device__ inline float gelu_erf_grad(float h) {
+  const float cdf = 0.5f * (1.f + erff(h * 0.70710678118654752f));
+  const float pdf = 0.3989422804014327f * __expf(-0.5f * h * h);
+  return cdf + h * pdf;
+}
+__device__ inline float gelu_tanh(float h) {
+  const float u = 0.7978845608028654f * (h + 0.044715f * h * h * h);
+  return 0.5f * h * (1.f + tanhf(u));
+}
+__device__ inline float gelu_tanh_grad(float h) {
+  const float u = 0.7978845608028654f * (h + 0.044715f * h * h * h);
+  const float th = tanhf(u);
+  const float du = 0.7978845608028654f * (1.f + 3.f * 0.044715f * h * h);
+  return 0.5f * (1.f + th) + 0.5f * h * (1.f - th * th) * du;
+}
+__device__ inline float sigmoidf(float t) { return 1.f / (1.f + __expf(-t)); }
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void act_fwd_kernel(const T* __restrict__ h, T* __restrict__ a,
+                                                           int rows, int f, int act) {
+  constexpr int N = Chunk<T>::N;
+  const int cpr = f / N;  // chunks per output row
+  const size_t total = (size_t)rows * cpr;
+  for (size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * kThreads) {
+    const size_t r = idx / cpr;
+    const int c = (int)(idx - r * cpr);
+    Chunk<T> o;
+    if (act == JPP_SWIGLU) {
+      const Chunk<T> g = load_chunk(h + r * 2 * f + (size_t)c * N);
+      const Chunk<T> u = load_chunk(h + r * 2 * f + f + (size_t)c * N);
+#pragma unroll
+      for (int e = 0; e < N; ++e) { const float t = g.get(e); o.set(e, t * sigmoidf(t) * u.get(e)); }
+    } else {
+      const Chunk<T> v = load_chunk(h + r * f + (size_t)c * N);
+      if (act == JPP_GELU) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) o.set(e, gelu_erf(v.get(e)));
+      } else {
+#pragma unroll
+        for (int e = 0; e < N; ++e) o.set(e, gelu_tanh(v.get(e)));
+      }
+    }
+    store_chunk(a + r * f + (size_t)c * N, o);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void act_bwd_kernel(const T* __restrict__ h, const T* __restrict__ da,
+                                                           T* __restrict__ dh, int rows, int f, int act) {
+  constexpr int N = Chunk<T>::N;
+  const int cpr = f / N;
+  const size_t total = (size_t)rows * cpr;
+  for (size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * kThreads) {
+    const size_t r = idx / cpr;
+    const int c = (int)(idx - r * cpr);
+    const Chunk<T> d = load_chunk(da + r * f + (size_t)c * N);
+    if (act == JPP_SWIGLU) {
+      const Chunk<T> g = load_chunk(h + r * 2 * f + (size_t)c * N);
+      const Chunk<T> u = load_chunk(h + r * 2 * f + f + (size_t)c * N);
+      Chunk<T> og, ou;
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        const float t = g.get(e), sg = sigmoidf(t), dv = d.get(e);
+        og.set(e, dv * u.get(e) * sg * (1.f + t * (1.f - sg)));
+        ou.set(e, dv * t * sg);
+      }
+      store_chunk(dh + r * 2 * f + (size_t)c * N, og);
+      store_chunk(dh + r * 2 * f + f + (size_t)c * N, ou);
+    } else {
+      const Chunk<T> v = load_chunk(h + r * f + (size_t)c * N);
+      Chunk<T> o;
+      if (act == JPP_GELU) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) o.set(e, d.get(e) * gelu_erf_grad(v.get(e)));
+      } else {
+#pragma unroll
+        for (int e = 0; e < N; ++e) o.set(e, d.get(e) * gelu_tanh_grad(v.get(e)));
+      }
+      store_chunk(dh + r * f + (size_t)c * N, o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// RoPE.  Element j < hd/2 of a head is paired with element j + hd/2; the pair at sequence
+// position p is rotated by angle(p, j) = p * theta^(-2j/hd).  The table holds
+// (cos, sin) as fp32, computed in double precision.  The inverse rotation is the backward.
+__global__ void rope_table_kernel(float* __restrict__ table, int seq, int hd, double theta) {
+  const int half = hd / 2;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= seq * half) return;
+  const int p = idx / half, j = idx - p * half;
+  const double inv = pow(theta, -2.0 * (double)j / (double)hd);
+  const double ang = (double)p * inv;
+  table[2 * (size_t)idx] = (float)cos(ang);
+  table[2 * (size_t)idx + 1] = (float)sin(ang);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void rope_kernel(T* __restrict__ qkv, const float* __restrict__ table,
+                                                        int tokens, int seq, int heads, int hd, int ld,
+                                                        float sign) {
+  constexpr int N = Chunk<T>::N;
+  const int half = hd / 2;
+  const int cph = half / N;  // chunk pairs per head
+  const size_t total = (size_t)tokens * heads * cph;
+  for (size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * kThreads) {
+    const int c = (int)(idx % cph);
+    const size_t th = idx / cph;
+    const int head = (int)(th % heads);
+    const size_t tok = th / heads;
+    const int pos = (int)(tok % seq);
+    T* p = qkv + tok * ld + (size_t)head * hd + (size_t)c * N;
+    Chunk<T> a = load_chunk(p), b = load_chunk(p + half);
+    Chunk<T> oa, ob;
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      const size_t ti = 2 * ((size_t)pos * half + (size_t)c * N + e);
+      const float cs = table[ti], sn = sign * table[ti + 1];
+      const float av = a.get(e), bv = b.get(e);
+      oa.set(e, av * cs - bv * sn);
+      ob.set(e, av * sn + bv * cs);
+    }
+    store_chunk(p, oa);
+    store_chunk(p + half, ob);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Mean-token cross-entropy from fp32 logits.  Per row r: lse = log sum_v exp(z_v);
+// row_loss[r] = lse - z[target]; dz = (exp(z - lse) - onehot(target)) / rows.
+// One workgroup per row; the row is read three times (max, sum, gradient), the last two
+// mostly from L2.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void cross_entropy_kernel(const float* __restrict__ z,
+                                                                 const int32_t* __restrict__ targets,
+                                                                 T* __restrict__ dz, float* __restrict__ row_loss,
+                                                                 int rows, int vocab) {
+  __shared__ float red[kWaves];
+  const size_t base = (size_t)blockIdx.x * vocab;
+  float m = -INFINITY;
+  for (int v = threadIdx.x; v < vocab; v += kThreads) m = fmaxf(m, z[base + v]);
+  m = block_max<kWaves>(m, red);
+  float s = 0.f;
+  for (int v = threadIdx.x; v < vocab; v += kThreads) s += __expf(z[base + v] - m);
+  s = block_sum<kWaves>(s, red);
+  const float lse = m + __logf(s);
+  const int tgt = targets[blockIdx.x];
+  // An id outside [0, vocab) cannot be indexed: its row reports NaN instead of reading out of bounds.
+  const bool tgt_ok = (unsigned)tgt < (unsigned)vocab;
+  if (threadIdx.x == 0) row_loss[blockIdx.x] = tgt_ok ? lse - z[base + tgt] : NAN;
+  const float inv_rows = 1.f / (float)rows;
+  for (int v = threadIdx.x; v < vocab; v += kThreads) {
+    float p = __expf(z[base + v] - lse);
+    if (v == tgt) p -= 1.f;
+    dz[base + v] = from_f32<T>(p * inv_rows);
+  }
+}
+
+// loss = (1/rows) * sum_r row_loss[r]; one workgroup, fixed order.
+__global__ __launch_bounds__(kThreads) void mean_rows_kernel(const float* __restrict__ row_loss, int rows,
+                                                             float* __restrict__ loss) {
+  __shared__ float red[kWaves];
+  float s = 0.f;
+  for (int r = threadIdx.x; r < rows; r += kThreads) s += row_loss[r];
+  s = block_sum<kWaves>(s, red);
+  if (threadIdx.x == 0) *loss = s / (float)rows;
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(u32x4* __restrict__ p, size_t n16) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (size_t)gridDim.x * kThreads)
+    p[i] = z;
+}
+
+inline int grid_for(size_t items) {
+  size_t g = (items + kThreads - 1) / kThreads;
+  const size_t cap = 256 * 16;  // 16 workgroups per CU
+  return (int)(g < 1 ? 1 : (g > cap ? cap : g));
+}
+
+template <typename T>
+int pick_maxc(int d) {
+  const int nchunks = d / Chunk<T>::N;
+  const int per = (nchunks + kThreads - 1) / kThreads;
+  return per <= 1 ? 1 : per <= 2 ? 2 : per <= 4 ? 4 : 8;
+}
+
+template <typename T>
+hipError_t norm_fwd_t(int norm, int rows, int d, float eps, const void* x, const void* gamma,
+                      const void* beta, void* y, float* stats, hipStream_t s) {
+  const T* xp = (const T*)x; const T* gp = (const T*)gamma; const T* bp = (const T*)beta; T* yp = (T*)y;
+  switch (pick_maxc<T>(d)) {
+    case 1: norm_fwd_kernel<T, 1><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
+    case 2: norm_fwd_kernel<T, 2><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
+    case 4: norm_fwd_kernel<T, 4><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
+    default: norm_fwd_kernel<T, 8><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
+  }
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamma, const float* stats,
+                      const void* dy, const void* dx_add, void* dx, float* g_gamma, float* g_beta,
+                      float* partial, hipStream_t s) {
+  const int nblk = colreduce_blocks(rows);
+  float* pg = partial;
+  float* pb = (norm == JPP_LAYERNORM && g_beta) ? partial + (size_t)nblk * d : nullptr;
+  const T* xp = (const T*)x; const T* gp = (const T*)gamma; const T* dyp = (const T*)dy;
+  const T* ap = (const T*)dx_add; T* dxp = (T*)dx;
+  switch (pick_maxc<T>(d)) {
+    case 1: norm_bwd_kernel<T, 1><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    case 2: norm_bwd_kernel<T, 2><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    case 4: norm_bwd_kernel<T, 4><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    default: norm_bwd_kernel<T, 8><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int fin = (d + kThreads - 1) / kThreads;
+  colreduce_finish_kernel<<<fin, kThreads, 0, s>>>(pg, nblk, d, g_gamma);
+  if (pb) colreduce_finish_kernel<<<fin, kThreads, 0, s>>>(pb, nblk, d, g_beta);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool norm_shape_ok(int dtype, int d) {
+  const int n = dtype == JPP_BF16 ? 8 : 4;
+  return d > 0 && d % n == 0 && d / n <= kThreads * kNormMaxChunksPerThread;
+}
+
+int colreduce_blocks(int rows) { return rows < 256 ? rows : 256; }
+
+hipError_t launch_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x, const void* gamma,
+                           const void* beta, void* y, float* stats, hipStream_t s) {
+  if (norm == JPP_RMSNORM) beta = nullptr;
+  return dtype == JPP_BF16 ? norm_fwd_t<bf16>(norm, rows, d, eps, x, gamma, beta, y, stats, s)
+                           : norm_fwd_t<float>(norm, rows, d, eps, x, gamma, beta, y, stats, s);
+}
+
+hipError_t launch_norm_bwd(int dtype, int norm, int rows, int d, const void* x, const void* gamma,
+                           const float* stats, const void* dy, const void* dx_add, void* dx, float* g_gamma,
+                           float* g_beta, float* partial, hipStream_t s) {
+  return dtype == JPP_BF16
+             ? norm_bwd_t<bf16>(norm, rows, d, x, gamma, stats, dy, dx_add, dx, g_gamma, g_beta, partial, s)
+             : norm_bwd_t<float>(norm, rows, d, x, gamma, stats, dy, dx_add, dx, g_gamma, g_beta, partial, s);
+}
+
+hipError_t launch_bias_grad(int dtype, int rows, int n, const void* dy, int ld, float* g, float* partial,
+                            hipStream_t s) {
+  const int nblk = colreduce_blocks(rows);
+  const int N = dtype == JPP_BF16 ? 8 : 4;
+  const int chunks = n / N;
+  dim3 grid((chunks + kThreads - 1) / kThreads, nblk);
+  if (dtype == JPP_BF16)
+    colsum_partial_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)dy, ld, rows, n, partial);
+  else
+    colsum_partial_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, ld, rows, n, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  colreduce_finish_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(partial, nblk, n, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_act_fwd(int dtype, int act, int rows, int f, const void* h, void* a, hipStream_t s) {
+  const int N = dtype == JPP_BF16 ? 8 : 4;
+  const int grid = grid_for((size_t)rows * (f / N));
+  if (dtype == JPP_BF16)
+    act_fwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)h, (bf16*)a, rows, f, act);
+  else
+    act_fwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)h, (float*)a, rows, f, act);
+  return hipGetLastError();
+}
+
+hipError_t launch_act_bwd(int dtype, int act, int rows, int f, const void* h, const void* da, void* dh,
+                          hipStream_t s) {
+  const int N = dtype == JPP_BF16 ? 8 : 4;
+  const int grid = grid_for((size_t)rows * (f / N));
+  if (dtype == JPP_BF16)
+    act_bwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)h, (const bf16*)da, (bf16*)dh, rows, f, act);
+  else
+    act_bwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)h, (const float*)da, (float*)dh, rows, f, act);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(float* table, int seq, int hd, float theta, hipStream_t s) {
+  const int n = seq * (hd / 2);
+  rope_table_kernel<<<(n + 255) / 256, 256, 0, s>>>(table, seq, hd, (double)theta);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope(int dtype, int mb, int seq, int Hq, int Hkv, int hd, void* qkv, const float* table,
+                       bool inverse, hipStream_t s) {
+  const int N = dtype == JPP_BF16 ? 8 : 4;
+  const int heads = Hq + Hkv;  // q heads followed by k heads are contiguous in the fused tensor
+  const int ld = (Hq + 2 * Hkv) * hd;
+  const int tokens = mb * seq;
+  const int grid = grid_for((size_t)tokens * heads * (hd / 2 / N));
+  const float sign = inverse ? -1.f : 1.f;
+  if (dtype == JPP_BF16)
+    rope_kernel<bf16><<<grid, kThreads, 0, s>>>((bf16*)qkv, table, tokens, seq, heads, hd, ld, sign);
+  else
+    rope_kernel<float><<<grid, kThreads, 0, s>>>((float*)qkv, table, tokens, seq, heads, hd, ld, sign);
+  return hipGetLastError();
+}
+
+hipError_t launch_cross_entropy(int dtype, int rows, int vocab, const float* z, const int32_t* targets,
+                                void* dz, float* row_loss, float* loss, hipStream_t s) {
+  if (dtype == JPP_BF16)
+    cross_entropy_kernel<bf16><<<rows, kThreads, 0, s>>>(z, targets, (bf16*)dz, row_loss, rows, vocab);
+  else
+    cross_entropy_kernel<float><<<rows, kThreads, 0, s>>>(z, targets, (float*)dz, row_loss, rows, vocab);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  mean_rows_kernel<<<1, kThreads, 0, s>>>(row_loss, rows, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;  // callers pass 16-byte multiples (arena regions are 256-byte aligned)
+  if (n16 == 0) return hipSuccess;
+  fill_zero_kernel<<<grid_for(n16), kThreads, 0, s>>>((u32x4*)p, n16);
+  return hipGetLastError();
+}
+
+}  // namespace jpp

@@ -1,0 +1,753 @@
+// The stage executor: one actor of an MPMD pipeline on one GPU.
+//
+// What the paper fixes (and this file implements):
+//  * Section 4.2: the actor receives a list of Task(i, ty, stage) and runs it in order;
+//    sends are issued asynchronously right after the producing task, receives are
+//    asynchronous and act as a prefetch overlapped with compute.  Here a "send"/"receive" is
+//    a device-local copy between the caller's boundary buffers and the stage's own buffers,
+//    issued on a side stream and ordered with events.
+//  * Section 4.3: buffers are deleted after their last use; a buffer that was sent is
+//    released if its send has completed, otherwise it is parked in a pending-deletion queue
+//    that every later deletion sweeps.  Here: the send staging buffers.
+//  * Section 4.4: all task dispatches of a step are fused into one call; there is no host
+//    round trip (no stream/event synchronisation) between tasks.
+//  * Section 3.1: gradients start at zero and every backward adds its microbatch's
+//    gradients (no 1/M); losses are collected per microbatch.
+//  * Section 2.2.1: the activations of a forward are kept until its backward on the same
+//    actor (the "stash"); the number alive at once depends on the schedule.
+// The layer mathematics is not defined by the paper; see include/jpp.h.
+#include <algorithm>
+#include <deque>
+#include <vector>
+
+#include "internal.h"
+
+namespace jpp {
+
+static thread_local std::string g_last_error;
+
+jpp_status fail(jpp_status code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+jpp_status fail_hip(hipError_t e, const char* what) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return JPP_EDEVICE;
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kTxBuffers = 3;   // send staging ring
+constexpr int kCotBuffers = 2;  // cotangent receive ring
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct ParamInfo { std::string name; int64_t shape[2]; size_t offset; };
+
+struct Dims {
+  int T, d, nq, nkv, nqkv, f, f1, hd, Hq, Hkv, seq, mb, vocab, L;
+  size_t esz;
+};
+
+// Element offsets (in bytes from the slot base) of one layer's stash.
+struct LayerStash {
+  size_t x, n1, qkv, O, x1, n2, h, a, stats1, stats2, lse, bytes;
+};
+struct HeadStash { size_t yL, nf, statsf, dz, bytes; };
+
+struct Event {
+  hipEvent_t ev = nullptr;
+  bool recorded = false;
+};
+
+struct Slot {
+  char* base = nullptr;
+  Event freed;  // recorded on the compute stream when the backward that used the slot is done
+  Event rx;     // recorded on the side stream when the received input is in place
+  bool rx_issued = false;
+};
+
+struct TxBuf {
+  char* p = nullptr;
+  Event produced;  // compute stream: contents written
+  Event sent;      // side stream: copied to the outbox
+};
+
+struct CotBuf {
+  char* p = nullptr;
+  Event freed;  // compute stream: consumer done
+  Event rx;     // side stream: cotangent in place
+};
+
+}  // namespace
+
+}  // namespace jpp
+
+using namespace jpp;
+
+struct jpp_stage {
+  jpp_layer_config cfg;
+  int M = 0, max_in_flight = 0;
+  Dims dm{};
+  std::vector<ParamInfo> pinfo;
+  size_t pcount = 0;
+  // per-layer parameter offsets (elements) by role; -1 if absent
+  struct LayerOff { long ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2; };
+  std::vector<LayerOff> loff;
+  long lnf_g = -1, lnf_b = -1, w_head = -1;
+
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  std::vector<char*> params;   // per vstage
+  std::vector<float*> grads;   // per vstage
+  float* rope_table = nullptr;
+  float* losses = nullptr;     // [V*M]
+  LayerStash ls{};
+  HeadStash hs{};
+  size_t slot_bytes = 0;
+  std::vector<Slot> slots;
+  std::vector<TxBuf> tx;
+  std::vector<CotBuf> cot;
+  // workspace
+  char *dbuf[2] = {nullptr, nullptr}, *da = nullptr, *dh = nullptr, *dn = nullptr, *dx1 = nullptr, *dO = nullptr,
+       *dqkv = nullptr;
+  float *delta = nullptr, *partial = nullptr, *z = nullptr, *row_loss = nullptr;
+
+  // boundary
+  std::vector<const void*> inbox_x, inbox_cot;
+  std::vector<void*> outbox_y, outbox_dx;
+  std::vector<const int32_t*> targets;
+  bool bound = false;
+  std::vector<bool> params_set;
+
+  // run state
+  hipStream_t cs = nullptr, ss = nullptr;
+  Event end_compute, end_side;
+  int peak_in_flight = 0, pending_peak = 0, prefetched = 0, host_syncs = 0;
+  std::vector<int> free_slots;
+  std::vector<int> tx_free;
+  std::deque<int> tx_pending;
+};
+
+namespace jpp {
+namespace {
+
+bool config_ok(const jpp_layer_config* c, int M, int max_in_flight, std::string& why) {
+  if (!c) { why = "null config"; return false; }
+  if (c->dtype != JPP_F32 && c->dtype != JPP_BF16) { why = "dtype must be JPP_F32 or JPP_BF16"; return false; }
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1 ||
+      c->d_ffn < 1 || c->seq_len < 1 || c->microbatch < 1) { why = "sizes must be positive"; return false; }
+  if (c->n_q_heads % c->n_kv_heads != 0) { why = "n_q_heads must be a multiple of n_kv_heads"; return false; }
+  if (c->norm != JPP_LAYERNORM && c->norm != JPP_RMSNORM) { why = "bad norm"; return false; }
+  if (c->act < JPP_GELU || c->act > JPP_SWIGLU) { why = "bad act"; return false; }
+  if (c->n_virtual < 1 || c->n_virtual > JPP_MAX_VIRTUAL) { why = "n_virtual out of range"; return false; }
+  for (int a = 0; a < c->n_virtual; ++a)
+    for (int b = a + 1; b < c->n_virtual; ++b)
+      if (c->stage_ids[a] == c->stage_ids[b]) { why = "duplicate stage id"; return false; }
+  if (M < 1 || max_in_flight < 1) { why = "n_microbatches and max_in_flight must be positive"; return false; }
+  if (c->loss_head && c->vocab < 1) { why = "loss_head needs vocab"; return false; }
+  const int chunk = c->dtype == JPP_BF16 ? 8 : 4;
+  if (c->head_dim % chunk != 0 || c->head_dim > 256) { why = "head_dim must be a multiple of the 16-byte chunk and <= 256"; return false; }
+  if (c->rope && (c->head_dim / 2) % chunk != 0) { why = "rope needs head_dim/2 to be a multiple of the 16-byte chunk"; return false; }
+  if (!norm_shape_ok(c->dtype, c->d_model)) { why = "d_model unsupported by the norm kernels"; return false; }
+  if (c->d_ffn % chunk != 0) { why = "d_ffn must be a multiple of the 16-byte chunk"; return false; }
+  if (c->dtype == JPP_BF16) {
+    const long T = (long)c->seq_len * c->microbatch;
+    if (T % 8 != 0 || c->d_model % 8 != 0 || (c->loss_head && c->vocab % 8 != 0)) {
+      why = "bf16 mode needs tokens, d_model and vocab to be multiples of 8";
+      return false;
+    }
+  }
+  if (c->rope_theta <= 0.f && c->rope) { why = "rope_theta must be positive"; return false; }
+  return true;
+}
+
+Dims dims_of(const jpp_layer_config& c) {
+  Dims m;
+  m.seq = c.seq_len; m.mb = c.microbatch; m.T = c.seq_len * c.microbatch;
+  m.d = c.d_model; m.hd = c.head_dim; m.Hq = c.n_q_heads; m.Hkv = c.n_kv_heads;
+  m.nq = c.n_q_heads * c.head_dim; m.nkv = c.n_kv_heads * c.head_dim; m.nqkv = m.nq + 2 * m.nkv;
+  m.f = c.d_ffn; m.f1 = c.act == JPP_SWIGLU ? 2 * c.d_ffn : c.d_ffn;
+  m.vocab = c.vocab; m.L = c.n_layers;
+  m.esz = c.dtype == JPP_BF16 ? 2 : 4;
+  return m;
+}
+
+void build_param_table(jpp_stage& st) {
+  const jpp_layer_config& c = st.cfg;
+  const Dims& m = st.dm;
+  size_t off = 0;
+  auto add = [&](const std::string& name, int64_t r, int64_t cdim) -> long {
+    // every tensor starts on a 16-byte boundary of the storage type and of fp32
+    off = (off + 7) / 8 * 8;
+    ParamInfo p{name, {r, cdim}, off};
+    st.pinfo.push_back(p);
+    const long o = (long)off;
+    off += (size_t)r * (cdim ? cdim : 1);
+    return o;
+  };
+  const bool ln = c.norm == JPP_LAYERNORM;
+  st.loff.resize(m.L);
+  for (int l = 0; l < m.L; ++l) {
+    auto& o = st.loff[l];
+    const std::string pre = "layer" + std::to_string(l) + ".";
+    o.ln1_g = add(pre + "ln1_g", m.d, 0);
+    o.ln1_b = ln ? add(pre + "ln1_b", m.d, 0) : -1;
+    o.wqkv = add(pre + "wqkv", m.nqkv, m.d);
+    o.bqkv = c.use_bias ? add(pre + "bqkv", m.nqkv, 0) : -1;
+    o.wo = add(pre + "wo", m.d, m.nq);
+    o.bo = c.use_bias ? add(pre + "bo", m.d, 0) : -1;
+    o.ln2_g = add(pre + "ln2_g", m.d, 0);
+    o.ln2_b = ln ? add(pre + "ln2_b", m.d, 0) : -1;
+    o.w1 = add(pre + "w1", m.f1, m.d);
+    o.b1 = c.use_bias ? add(pre + "b1", m.f1, 0) : -1;
+    o.w2 = add(pre + "w2", m.d, m.f);
+    o.b2 = c.use_bias ? add(pre + "b2", m.d, 0) : -1;
+  }
+  if (c.loss_head) {
+    st.lnf_g = add("head.lnf_g", m.d, 0);
+    st.lnf_b = ln ? add("head.lnf_b", m.d, 0) : -1;
+    st.w_head = add("head.w_head", m.vocab, m.d);
+  }
+  st.pcount = (off + 7) / 8 * 8;
+}
+
+// Lays the arena out; with base == nullptr only the size is computed.
+size_t carve(jpp_stage& st, char* base) {
+  const jpp_layer_config& c = st.cfg;
+  const Dims& m = st.dm;
+  const int V = c.n_virtual;
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> char* {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return p;
+  };
+  const size_t T = m.T, e = m.esz;
+  st.params.resize(V); st.grads.resize(V);
+  for (int v = 0; v < V; ++v) st.params[v] = take(st.pcount * e);
+  for (int v = 0; v < V; ++v) st.grads[v] = (float*)take(st.pcount * 4);
+  st.rope_table = c.rope ? (float*)take((size_t)m.seq * (m.hd / 2) * 2 * 4) : nullptr;
+  st.losses = (float*)take((size_t)V * st.M * 4);
+
+  // stash layout inside a slot
+  {
+    size_t o = 0;
+    auto sub = [&](size_t bytes) { size_t r = o; o += align_up(bytes); return r; };
+    st.ls.x = sub(T * m.d * e); st.ls.n1 = sub(T * m.d * e); st.ls.qkv = sub(T * m.nqkv * e);
+    st.ls.O = sub(T * m.nq * e); st.ls.x1 = sub(T * m.d * e); st.ls.n2 = sub(T * m.d * e);
+    st.ls.h = sub(T * m.f1 * e); st.ls.a = sub(T * m.f * e);
+    st.ls.stats1 = sub(2 * T * 4); st.ls.stats2 = sub(2 * T * 4);
+    st.ls.lse = sub((size_t)m.mb * m.Hq * m.seq * 4);
+    st.ls.bytes = o;
+    o = 0;
+    if (c.loss_head) {
+      st.hs.yL = sub(T * m.d * e); st.hs.nf = sub(T * m.d * e); st.hs.statsf = sub(2 * T * 4);
+      st.hs.dz = sub(T * m.vocab * e);
+    }
+    st.hs.bytes = o;
+    st.slot_bytes = st.ls.bytes * m.L + st.hs.bytes;
+  }
+  st.slots.resize(st.max_in_flight);
+  for (auto& s : st.slots) s.base = take(st.slot_bytes);
+  st.tx.resize(kTxBuffers);
+  for (auto& t : st.tx) t.p = take(T * m.d * e);
+  st.cot.resize(kCotBuffers);
+  for (auto& t : st.cot) t.p = take(T * m.d * e);
+  st.dbuf[0] = take(T * m.d * e); st.dbuf[1] = take(T * m.d * e);
+  st.da = take(T * m.f * e); st.dh = take(T * m.f1 * e); st.dn = take(T * m.d * e); st.dx1 = take(T * m.d * e);
+  st.dO = take(T * m.nq * e); st.dqkv = take(T * m.nqkv * e);
+  st.delta = (float*)take((size_t)m.mb * m.Hq * m.seq * 4);
+  const size_t widest = std::max<size_t>({(size_t)m.d, (size_t)m.f1, (size_t)m.nqkv});
+  st.partial = (float*)take(2 * (size_t)colreduce_blocks(m.T) * widest * 4);
+  if (c.loss_head) {
+    st.z = (float*)take(T * m.vocab * 4);
+    st.row_loss = (float*)take(T * 4);
+  }
+  return off;
+}
+
+hipError_t ev_create(Event& e) { return hipEventCreateWithFlags(&e.ev, hipEventDisableTiming); }
+void ev_destroy(Event& e) { if (e.ev) (void)hipEventDestroy(e.ev); e.ev = nullptr; }
+
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t _e = (expr);                             \
+    if (_e != hipSuccess) return fail_hip(_e, #expr);   \
+  } while (0)
+
+hipError_t gemm(const jpp_stage& st, hipStream_t s, int M, int N, int K, const void* A, int lda, bool aks,
+                const void* B, int ldb, bool bks, void* C, int ldc, int mode, const void* bias,
+                const void* residual) {
+  GemmDesc g{M, N, K, A, lda, aks, B, ldb, bks, C, ldc, mode, bias, residual};
+  return st.cfg.dtype == JPP_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+}
+
+hipError_t attention_fwd(const jpp_stage& st, hipStream_t s, const AttnDesc& a) {
+  if (st.cfg.dtype == JPP_BF16 && attention_mfma_supported(a)) return launch_attention_fwd_mfma(a, s);
+  return launch_attention_fwd_generic(st.cfg.dtype, a, s);
+}
+hipError_t attention_bwd(const jpp_stage& st, hipStream_t s, const AttnDesc& a) {
+  if (st.cfg.dtype == JPP_BF16 && attention_mfma_supported(a)) return launch_attention_bwd_mfma(a, s);
+  return launch_attention_bwd_generic(st.cfg.dtype, a, s);
+}
+
+#define K_TRY(expr)                       \
+  do {                                    \
+    hipError_t _e = (expr);               \
+    if (_e != hipSuccess) return _e;      \
+  } while (0)
+
+const void* pptr(const jpp_stage& st, int v, long off) {
+  return off < 0 ? nullptr : (const void*)(st.params[v] + (size_t)off * st.dm.esz);
+}
+float* gptr(const jpp_stage& st, int v, long off) { return off < 0 ? nullptr : st.grads[v] + off; }
+
+// Forward of all layers (and the loss head) of local stage v for microbatch i, reading the
+// input from the slot and writing the output to `y_out` (ignored for a loss-head stage).
+hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out) {
+  const Dims& m = st.dm;
+  const jpp_layer_config& c = st.cfg;
+  hipStream_t s = st.cs;
+  const int dt = c.dtype;
+  for (int l = 0; l < m.L; ++l) {
+    char* b = slot.base + (size_t)l * st.ls.bytes;
+    const auto& o = st.loff[l];
+    char* x = b + st.ls.x;
+    char* y = (l + 1 < m.L) ? slot.base + (size_t)(l + 1) * st.ls.bytes + st.ls.x
+                            : (c.loss_head ? slot.base + (size_t)m.L * st.ls.bytes + st.hs.yL : y_out);
+    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, x, pptr(st, v, o.ln1_g), pptr(st, v, o.ln1_b),
+                          b + st.ls.n1, (float*)(b + st.ls.stats1), s));
+    K_TRY(gemm(st, s, m.T, m.nqkv, m.d, b + st.ls.n1, m.d, false, pptr(st, v, o.wqkv), m.d, false, b + st.ls.qkv,
+               m.nqkv, OUT_STORE, pptr(st, v, o.bqkv), nullptr));
+    if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, st.rope_table, false, s));
+    AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
+               nullptr, nullptr, nullptr};
+    K_TRY(attention_fwd(st, s, a));
+    K_TRY(gemm(st, s, m.T, m.d, m.nq, b + st.ls.O, m.nq, false, pptr(st, v, o.wo), m.nq, false, b + st.ls.x1, m.d,
+               OUT_STORE, pptr(st, v, o.bo), x));
+    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, b + st.ls.x1, pptr(st, v, o.ln2_g),
+                          pptr(st, v, o.ln2_b), b + st.ls.n2, (float*)(b + st.ls.stats2), s));
+    K_TRY(gemm(st, s, m.T, m.f1, m.d, b + st.ls.n2, m.d, false, pptr(st, v, o.w1), m.d, false, b + st.ls.h, m.f1,
+               OUT_STORE, pptr(st, v, o.b1), nullptr));
+    K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, b + st.ls.h, b + st.ls.a, s));
+    K_TRY(gemm(st, s, m.T, m.d, m.f, b + st.ls.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
+               pptr(st, v, o.b2), b + st.ls.x1));
+  }
+  if (c.loss_head) {
+    char* hb = slot.base + (size_t)m.L * st.ls.bytes;
+    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, hb + st.hs.yL, pptr(st, v, st.lnf_g),
+                          pptr(st, v, st.lnf_b), hb + st.hs.nf, (float*)(hb + st.hs.statsf), s));
+    K_TRY(gemm(st, s, m.T, m.vocab, m.d, hb + st.hs.nf, m.d, false, pptr(st, v, st.w_head), m.d, false, st.z,
+               m.vocab, OUT_STORE_F32, nullptr, nullptr));
+    K_TRY(launch_cross_entropy(dt, m.T, m.vocab, st.z, st.targets[(size_t)v * st.M + i], hb + st.hs.dz,
+                               st.row_loss, st.losses + (size_t)v * st.M + i, s));
+  }
+  return hipSuccess;
+}
+
+// Backward of local stage v: reads the output cotangent from `dy_in` (ignored for a
+// loss-head stage), adds this microbatch's parameter gradients to the fp32 buffers and
+// writes the input cotangent to `dx_out`.
+hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in, char* dx_out) {
+  const Dims& m = st.dm;
+  const jpp_layer_config& c = st.cfg;
+  hipStream_t s = st.cs;
+  const int dt = c.dtype;
+  int cur = 0;
+  const char* dy = dy_in;
+  if (c.loss_head) {
+    char* hb = slot.base + (size_t)m.L * st.ls.bytes;
+    K_TRY(gemm(st, s, m.vocab, m.d, m.T, hb + st.hs.dz, m.vocab, true, hb + st.hs.nf, m.d, true,
+               gptr(st, v, st.w_head), m.d, OUT_ACC_F32, nullptr, nullptr));
+    K_TRY(gemm(st, s, m.T, m.d, m.vocab, hb + st.hs.dz, m.vocab, false, pptr(st, v, st.w_head), m.d, true, st.dn,
+               m.d, OUT_STORE, nullptr, nullptr));
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, hb + st.hs.yL, pptr(st, v, st.lnf_g), (float*)(hb + st.hs.statsf),
+                          st.dn, nullptr, st.dbuf[cur], gptr(st, v, st.lnf_g), gptr(st, v, st.lnf_b), st.partial,
+                          s));
+    dy = st.dbuf[cur];
+    cur ^= 1;
+  }
+  for (int l = m.L - 1; l >= 0; --l) {
+    char* b = slot.base + (size_t)l * st.ls.bytes;
+    const auto& o = st.loff[l];
+    char* dx = (l == 0) ? dx_out : st.dbuf[cur];
+    // FFN down projection
+    if (o.b2 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dy, m.d, gptr(st, v, o.b2), st.partial, s));
+    K_TRY(gemm(st, s, m.d, m.f, m.T, dy, m.d, true, b + st.ls.a, m.f, true, gptr(st, v, o.w2), m.f, OUT_ACC_F32,
+               nullptr, nullptr));
+    K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, st.da, m.f, OUT_STORE, nullptr,
+               nullptr));
+    K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, b + st.ls.h, st.da, st.dh, s));
+    // FFN up projection
+    if (o.b1 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.f1, st.dh, m.f1, gptr(st, v, o.b1), st.partial, s));
+    K_TRY(gemm(st, s, m.f1, m.d, m.T, st.dh, m.f1, true, b + st.ls.n2, m.d, true, gptr(st, v, o.w1), m.d,
+               OUT_ACC_F32, nullptr, nullptr));
+    K_TRY(gemm(st, s, m.T, m.d, m.f1, st.dh, m.f1, false, pptr(st, v, o.w1), m.d, true, st.dn, m.d, OUT_STORE,
+               nullptr, nullptr));
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, b + st.ls.x1, pptr(st, v, o.ln2_g), (float*)(b + st.ls.stats2),
+                          st.dn, dy, st.dx1, gptr(st, v, o.ln2_g), gptr(st, v, o.ln2_b), st.partial, s));
+    // attention output projection
+    if (o.bo >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, st.dx1, m.d, gptr(st, v, o.bo), st.partial, s));
+    K_TRY(gemm(st, s, m.d, m.nq, m.T, st.dx1, m.d, true, b + st.ls.O, m.nq, true, gptr(st, v, o.wo), m.nq,
+               OUT_ACC_F32, nullptr, nullptr));
+    K_TRY(gemm(st, s, m.T, m.nq, m.d, st.dx1, m.d, false, pptr(st, v, o.wo), m.nq, true, st.dO, m.nq, OUT_STORE,
+               nullptr, nullptr));
+    AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
+               st.dO, st.dqkv, st.delta};
+    K_TRY(attention_bwd(st, s, a));
+    if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, st.dqkv, st.rope_table, true, s));
+    // QKV projection
+    if (o.bqkv >= 0) K_TRY(launch_bias_grad(dt, m.T, m.nqkv, st.dqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
+    K_TRY(gemm(st, s, m.nqkv, m.d, m.T, st.dqkv, m.nqkv, true, b + st.ls.n1, m.d, true, gptr(st, v, o.wqkv), m.d,
+               OUT_ACC_F32, nullptr, nullptr));
+    K_TRY(gemm(st, s, m.T, m.d, m.nqkv, st.dqkv, m.nqkv, false, pptr(st, v, o.wqkv), m.d, true, st.dn, m.d,
+               OUT_STORE, nullptr, nullptr));
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, b + st.ls.x, pptr(st, v, o.ln1_g), (float*)(b + st.ls.stats1),
+                          st.dn, st.dx1, dx, gptr(st, v, o.ln1_g), gptr(st, v, o.ln1_b), st.partial, s));
+    dy = dx;
+    cur ^= 1;
+  }
+  return hipSuccess;
+}
+
+int local_stage(const jpp_layer_config& c, int global) {
+  for (int v = 0; v < c.n_virtual; ++v)
+    if (c.stage_ids[v] == global) return v;
+  return -1;
+}
+
+// Section 4.3: sweep the pending-deletion queue; buffers whose send has completed go back to
+// the free list.  hipEventQuery does not block.
+void sweep_pending(jpp_stage& st) {
+  for (size_t k = 0; k < st.tx_pending.size();) {
+    const int b = st.tx_pending[k];
+    if (hipEventQuery(st.tx[b].sent.ev) == hipSuccess) {
+      st.tx_free.push_back(b);
+      st.tx_pending.erase(st.tx_pending.begin() + k);
+    } else {
+      ++k;
+    }
+  }
+  (void)hipGetLastError();  // hipErrorNotReady from the query is not an error
+}
+
+// A staging buffer for the next send.  If none is free the oldest pending one is reused and
+// the compute stream is made to wait (on the device) for its send.
+hipError_t acquire_tx(jpp_stage& st, int& out) {
+  sweep_pending(st);
+  if (!st.tx_free.empty()) {
+    out = st.tx_free.back();
+    st.tx_free.pop_back();
+    return hipSuccess;
+  }
+  out = st.tx_pending.front();
+  st.tx_pending.pop_front();
+  return hipStreamWaitEvent(st.cs, st.tx[out].sent.ev, 0);
+}
+
+// Send: copy on the side stream once the compute stream has produced the buffer, then the
+// "deletion" of the staging buffer (Section 4.3).
+hipError_t send_and_delete(jpp_stage& st, int b, void* outbox, size_t bytes) {
+  TxBuf& t = st.tx[b];
+  K_TRY(hipEventRecord(t.produced.ev, st.cs));
+  K_TRY(hipStreamWaitEvent(st.ss, t.produced.ev, 0));
+  K_TRY(hipMemcpyAsync(outbox, t.p, bytes, hipMemcpyDeviceToDevice, st.ss));
+  K_TRY(hipEventRecord(t.sent.ev, st.ss));
+  t.sent.recorded = true;
+  sweep_pending(st);
+  if (hipEventQuery(t.sent.ev) == hipSuccess) {
+    st.tx_free.push_back(b);
+  } else {
+    (void)hipGetLastError();
+    st.tx_pending.push_back(b);
+    st.pending_peak = std::max(st.pending_peak, (int)st.tx_pending.size());
+  }
+  return hipSuccess;
+}
+
+// Receive of a forward input into a stash slot (side stream).
+hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes) {
+  if (slot.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, slot.freed.ev, 0));
+  K_TRY(hipMemcpyAsync(slot.base + st.ls.x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
+  K_TRY(hipEventRecord(slot.rx.ev, st.ss));
+  slot.rx_issued = true;
+  return hipSuccess;
+}
+
+hipError_t issue_recv_cot(jpp_stage& st, CotBuf& cb, const void* src, size_t bytes) {
+  if (cb.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, cb.freed.ev, 0));
+  K_TRY(hipMemcpyAsync(cb.p, src, bytes, hipMemcpyDeviceToDevice, st.ss));
+  K_TRY(hipEventRecord(cb.rx.ev, st.ss));
+  return hipSuccess;
+}
+
+}  // namespace
+}  // namespace jpp
+
+extern "C" {
+
+const char* jpp_last_error(void) { return jpp::g_last_error.c_str(); }
+
+size_t jpp_stage_arena_bytes(const jpp_layer_config* cfg, int n_microbatches, int max_in_flight) {
+  std::string why;
+  if (!config_ok(cfg, n_microbatches, max_in_flight, why)) { fail(JPP_EINVAL, why); return 0; }
+  jpp_stage tmp;
+  tmp.cfg = *cfg; tmp.M = n_microbatches; tmp.max_in_flight = max_in_flight;
+  tmp.dm = dims_of(*cfg);
+  build_param_table(tmp);
+  return carve(tmp, nullptr);
+}
+
+jpp_status jpp_stage_create(const jpp_layer_config* cfg, int n_microbatches, int max_in_flight, void* arena_dev,
+                            size_t arena_bytes, jpp_stage** out) {
+  if (!out) return fail(JPP_EINVAL, "null output pointer");
+  *out = nullptr;
+  std::string why;
+  if (!config_ok(cfg, n_microbatches, max_in_flight, why)) return fail(JPP_EINVAL, why);
+  if (!arena_dev || ((uintptr_t)arena_dev % kAlign) != 0) return fail(JPP_EINVAL, "arena must be 256-byte aligned");
+  jpp_stage* st = new jpp_stage;
+  st->cfg = *cfg; st->M = n_microbatches; st->max_in_flight = max_in_flight;
+  st->dm = dims_of(*cfg);
+  build_param_table(*st);
+  const size_t need = carve(*st, (char*)arena_dev);
+  if (need > arena_bytes) { delete st; return fail(JPP_EINVAL, "arena too small"); }
+  st->arena = (char*)arena_dev; st->arena_bytes = arena_bytes;
+  st->params_set.assign(cfg->n_virtual, false);
+  // the GEMM shapes this stage will launch must be supported
+  if (cfg->dtype == JPP_BF16) {
+    const Dims& m = st->dm;
+    const int dimsv[] = {m.T, m.d, m.nq, m.nqkv, m.f, m.f1};
+    for (int v : dimsv)
+      if (v % 8 != 0) { delete st; return fail(JPP_EINVAL, "bf16 mode needs every GEMM dimension to be a multiple of 8"); }
+  }
+  hipError_t e = hipSuccess;
+  auto mk = [&](Event& ev) { if (e == hipSuccess) e = ev_create(ev); };
+  for (auto& s : st->slots) { mk(s.freed); mk(s.rx); }
+  for (auto& t : st->tx) { mk(t.produced); mk(t.sent); }
+  for (auto& t : st->cot) { mk(t.freed); mk(t.rx); }
+  mk(st->end_compute); mk(st->end_side);
+  if (e == hipSuccess && cfg->rope) {
+    e = launch_rope_table(st->rope_table, cfg->seq_len, cfg->head_dim, cfg->rope_theta, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  }
+  if (e != hipSuccess) { jpp_stage_destroy(st); return fail_hip(e, "stage setup"); }
+  *out = st;
+  return JPP_OK;
+}
+
+void jpp_stage_destroy(jpp_stage* st) {
+  if (!st) return;
+  if (st->cs) (void)hipStreamSynchronize(st->cs);
+  if (st->ss) (void)hipStreamSynchronize(st->ss);
+  for (auto& s : st->slots) { ev_destroy(s.freed); ev_destroy(s.rx); }
+  for (auto& t : st->tx) { ev_destroy(t.produced); ev_destroy(t.sent); }
+  for (auto& t : st->cot) { ev_destroy(t.freed); ev_destroy(t.rx); }
+  ev_destroy(st->end_compute); ev_destroy(st->end_side);
+  delete st;
+}
+
+int jpp_stage_param_info(const jpp_stage* st, int idx, const char** name, int64_t shape[2], size_t* elem_offset) {
+  if (!st) { fail(JPP_EINVAL, "null stage"); return -JPP_EINVAL; }
+  if (idx < 0) return (int)st->pinfo.size();
+  if (idx >= (int)st->pinfo.size()) { fail(JPP_EINVAL, "parameter index out of range"); return -JPP_EINVAL; }
+  const ParamInfo& p = st->pinfo[idx];
+  if (name) *name = p.name.c_str();
+  if (shape) { shape[0] = p.shape[0]; shape[1] = p.shape[1]; }
+  if (elem_offset) *elem_offset = p.offset;
+  return JPP_OK;
+}
+
+size_t jpp_stage_param_count(const jpp_stage* st) { return st ? st->pcount : 0; }
+
+jpp_status jpp_stage_set_params(jpp_stage* st, int vstage, const void* src, int src_on_device) {
+  if (!st || !src) return fail(JPP_EINVAL, "null argument");
+  if (vstage < 0 || vstage >= st->cfg.n_virtual) return fail(JPP_EINVAL, "vstage out of range");
+  HIP_TRY(hipMemcpy(st->params[vstage], src, st->pcount * st->dm.esz,
+                    src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+  HIP_TRY(hipDeviceSynchronize());
+  st->params_set[vstage] = true;
+  return JPP_OK;
+}
+
+jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x, const void* const* inbox_cot,
+                                   void* const* outbox_y, void* const* outbox_dx,
+                                   const int32_t* const* targets) {
+  if (!st || !inbox_x || !outbox_dx) return fail(JPP_EINVAL, "inbox_x and outbox_dx are required");
+  const bool head = st->cfg.loss_head != 0;
+  if (!head && (!inbox_cot || !outbox_y)) return fail(JPP_EINVAL, "inbox_cot and outbox_y are required");
+  if (head && !targets) return fail(JPP_EINVAL, "targets are required for a loss_head stage");
+  const size_t n = (size_t)st->cfg.n_virtual * st->M;
+  for (size_t k = 0; k < n; ++k) {
+    if (!inbox_x[k] || !outbox_dx[k]) return fail(JPP_EINVAL, "null boundary buffer");
+    if (!head && (!inbox_cot[k] || !outbox_y[k])) return fail(JPP_EINVAL, "null boundary buffer");
+    if (head && !targets[k]) return fail(JPP_EINVAL, "null targets buffer");
+  }
+  st->inbox_x.assign(inbox_x, inbox_x + n);
+  st->outbox_dx.assign(outbox_dx, outbox_dx + n);
+  if (!head) {
+    st->inbox_cot.assign(inbox_cot, inbox_cot + n);
+    st->outbox_y.assign(outbox_y, outbox_y + n);
+  } else {
+    st->targets.assign(targets, targets + n);
+  }
+  st->bound = true;
+  return JPP_OK;
+}
+
+jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream) {
+  if (!st) return fail(JPP_EINVAL, "null stage");
+  hipStream_t s = (hipStream_t)stream;
+  for (int v = 0; v < st->cfg.n_virtual; ++v)
+    HIP_TRY(launch_fill_zero(st->grads[v], align_up(st->pcount * 4), s));
+  HIP_TRY(launch_fill_zero(st->losses, align_up((size_t)st->cfg.n_virtual * st->M * 4), s));
+  return JPP_OK;
+}
+
+jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream,
+                         void* side_stream) {
+  if (!st) return fail(JPP_EINVAL, "null stage");
+  if (!st->bound) return fail(JPP_ESTATE, "boundary buffers not bound");
+  for (bool b : st->params_set)
+    if (!b) return fail(JPP_ESTATE, "parameters not set for every virtual stage");
+  if (compute_stream == side_stream) return fail(JPP_EINVAL, "compute and side streams must differ");
+  std::string why;
+  int peak = 0;
+  int rc = validate_tasks(&st->cfg, st->M, tasks, n_tasks, &peak, why);
+  if (rc != JPP_OK) return fail((jpp_status)rc, why);
+  if (peak > st->max_in_flight)
+    return fail(JPP_ECAPACITY, "task list keeps " + std::to_string(peak) + " stashes alive, arena holds " +
+                                   std::to_string(st->max_in_flight));
+
+  const Dims& m = st->dm;
+  const size_t bbytes = (size_t)m.T * m.d * m.esz;
+  const bool head = st->cfg.loss_head != 0;
+  hipStream_t cs = (hipStream_t)compute_stream, ss = (hipStream_t)side_stream;
+  // order this run after the previous one on both streams (device-side waits only)
+  if (st->end_compute.recorded) {
+    HIP_TRY(hipStreamWaitEvent(cs, st->end_side.ev, 0));
+    HIP_TRY(hipStreamWaitEvent(ss, st->end_compute.ev, 0));
+    HIP_TRY(hipStreamWaitEvent(cs, st->end_compute.ev, 0));
+    HIP_TRY(hipStreamWaitEvent(ss, st->end_side.ev, 0));
+  }
+  st->cs = cs; st->ss = ss;
+  st->peak_in_flight = 0; st->pending_peak = 0; st->prefetched = 0; st->host_syncs = 0;
+  st->free_slots.clear();
+  for (int k = st->max_in_flight - 1; k >= 0; --k) st->free_slots.push_back(k);
+  for (auto& s : st->slots) s.rx_issued = false;
+  // staging buffers still pending from the previous run are ordered by the waits above
+  st->tx_free.clear(); st->tx_pending.clear();
+  for (int k = 0; k < kTxBuffers; ++k) st->tx_free.push_back(k);
+
+  const int V = st->cfg.n_virtual;
+  std::vector<int> slot_of((size_t)V * st->M, -1);   // stash slot of (v, i), assigned at receive time
+  std::vector<int> cot_of((size_t)V * st->M, -1);    // cotangent ring entry of (v, i)
+  int cot_next = 0;
+  int live = 0;
+
+  // Issues the receive of task k (Section 4.2: asynchronous, ahead of the consumer).
+  auto issue_recv = [&](int k, bool ahead) -> hipError_t {
+    const jpp_task& t = tasks[k];
+    const int v = local_stage(st->cfg, t.stage);
+    const size_t key = (size_t)v * st->M + t.i;
+    if (t.ty == JPP_FWD) {
+      if (slot_of[key] >= 0) return hipSuccess;  // already prefetched
+      if (st->free_slots.empty()) return hipErrorNotReady;  // caller retries when the task itself starts
+      const int sl = st->free_slots.back();
+      st->free_slots.pop_back();
+      slot_of[key] = sl;
+      if (ahead) ++st->prefetched;
+      return issue_recv_x(*st, st->slots[sl], st->inbox_x[key], bbytes);
+    }
+    if (head) return hipSuccess;  // a loss-head backward receives nothing
+    if (cot_of[key] >= 0) return hipSuccess;
+    const int cb = cot_next;
+    cot_next = (cot_next + 1) % kCotBuffers;
+    cot_of[key] = cb;
+    if (ahead) ++st->prefetched;
+    return issue_recv_cot(*st, st->cot[cb], st->inbox_cot[key], bbytes);
+  };
+
+  for (int k = 0; k < n_tasks; ++k) {
+    const jpp_task& t = tasks[k];
+    const int v = local_stage(st->cfg, t.stage);
+    const size_t key = (size_t)v * st->M + t.i;
+    // this task's own receive, if it was not prefetched
+    hipError_t e = issue_recv(k, false);
+    if (e != hipSuccess) return fail_hip(e, "receive");
+    // prefetch the next task's input while this task computes
+    if (k + 1 < n_tasks) {
+      // a cotangent ring entry may only be reused once its consumer is enqueued: with two
+      // entries the next backward's receive can always go ahead of the current task
+      e = issue_recv(k + 1, true);
+      if (e != hipSuccess && e != hipErrorNotReady) return fail_hip(e, "prefetch");
+    }
+    if (t.ty == JPP_FWD) {
+      Slot& slot = st->slots[slot_of[key]];
+      ++live;
+      st->peak_in_flight = std::max(st->peak_in_flight, live);
+      HIP_TRY(hipStreamWaitEvent(cs, slot.rx.ev, 0));
+      int txb = -1;
+      if (!head) HIP_TRY(acquire_tx(*st, txb));
+      e = enqueue_forward(*st, v, t.i, slot, head ? nullptr : st->tx[txb].p);
+      if (e != hipSuccess) return fail_hip(e, "forward kernels");
+      if (!head) HIP_TRY(send_and_delete(*st, txb, st->outbox_y[key], bbytes));
+    } else {
+      Slot& slot = st->slots[slot_of[key]];
+      const char* dy = nullptr;
+      if (!head) {
+        CotBuf& cb = st->cot[cot_of[key]];
+        HIP_TRY(hipStreamWaitEvent(cs, cb.rx.ev, 0));
+        dy = cb.p;
+      }
+      int txb = -1;
+      HIP_TRY(acquire_tx(*st, txb));
+      e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p);
+      if (e != hipSuccess) return fail_hip(e, "backward kernels");
+      if (!head) {
+        CotBuf& cb = st->cot[cot_of[key]];
+        HIP_TRY(hipEventRecord(cb.freed.ev, cs));
+        cb.freed.recorded = true;
+      }
+      HIP_TRY(send_and_delete(*st, txb, st->outbox_dx[key], bbytes));
+      // the stash is dead: release the slot (stream order protects it on the compute stream;
+      // the event protects it against an early receive on the side stream)
+      HIP_TRY(hipEventRecord(slot.freed.ev, cs));
+      slot.freed.recorded = true;
+      st->free_slots.push_back(slot_of[key]);
+      slot_of[key] = -1;
+      --live;
+    }
+  }
+  HIP_TRY(hipEventRecord(st->end_compute.ev, cs));
+  HIP_TRY(hipEventRecord(st->end_side.ev, ss));
+  st->end_compute.recorded = true;
+  return JPP_OK;
+}
+
+jpp_status jpp_stage_grads(jpp_stage* st, int vstage, const float** grads_dev, size_t* n_elems) {
+  if (!st || !grads_dev) return fail(JPP_EINVAL, "null argument");
+  if (vstage < 0 || vstage >= st->cfg.n_virtual) return fail(JPP_EINVAL, "vstage out of range");
+  if (st->cs) HIP_TRY(hipStreamSynchronize(st->cs));
+  if (st->ss) HIP_TRY(hipStreamSynchronize(st->ss));
+  *grads_dev = st->grads[vstage];
+  if (n_elems) *n_elems = st->pcount;
+  return JPP_OK;
+}
+
+jpp_status jpp_stage_losses(jpp_stage* st, const float** loss_dev) {
+  if (!st || !loss_dev) return fail(JPP_EINVAL, "null argument");
+  if (!st->cfg.loss_head) return fail(JPP_ESTATE, "stage has no loss head");
+  if (st->cs) HIP_TRY(hipStreamSynchronize(st->cs));
+  if (st->ss) HIP_TRY(hipStreamSynchronize(st->ss));
+  *loss_dev = st->losses;
+  return JPP_OK;
+}
+
+int jpp_stage_peak_in_flight(const jpp_stage* st) { return st ? st->peak_in_flight : -1; }
+int jpp_stage_pending_peak(const jpp_stage* st) { return st ? st->pending_peak : -1; }
+int jpp_stage_prefetched(const jpp_stage* st) { return st ? st->prefetched : -1; }
+int jpp_stage_host_syncs(const jpp_stage* st) { return st ? st->host_syncs : -1; }
+
+}  // extern "C"

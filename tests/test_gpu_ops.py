@@ -1,0 +1,281 @@
+"""Op-level GPU parity through the C ABI: each kernel against the definition evaluated in
+float64 on the same (already rounded) inputs.  These also run at the full benchmark shapes,
+where the oracle cannot run end to end: there, sampled output entries are checked one by one.
+"""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import stage_oracle as so
+from paper_2412_14374_amd import binding as B
+from paper_2412_14374_amd import inputs as inp
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def rel_l2(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(dtype).contiguous()
+
+
+def host(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+GEMM_SHAPES = [
+    # M, N, K  (multiples of 8; tails against the 256/128 tiles and the 64-wide k step)
+    (8, 8, 8), (136, 72, 200), (256, 256, 64), (264, 520, 328), (512, 384, 1000), (1032, 776, 72),
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("aks,bks", [(0, 0), (0, 1), (1, 1), (1, 0)])
+def test_gemm_bf16_all_layouts_and_epilogues(M, N, K, aks, bks):
+    rng = np.random.default_rng(M * 7 + N * 3 + K + aks * 2 + bks)
+    A = inp.round_to_dtype(rng.standard_normal((M, K)), inp.DT_BF16)
+    Bm = inp.round_to_dtype(rng.standard_normal((N, K)), inp.DT_BF16)
+    bias = inp.round_to_dtype(rng.standard_normal(N), inp.DT_BF16)
+    res = inp.round_to_dtype(rng.standard_normal((M, N)), inp.DT_BF16)
+    ref = A @ Bm.T
+    At = dev(A.T if aks else A, torch.bfloat16)
+    Bt = dev(Bm.T if bks else Bm, torch.bfloat16)
+    lda = M if aks else K
+    ldb = N if bks else K
+    bt, rt = dev(bias, torch.bfloat16), dev(res, torch.bfloat16)
+    # store bf16 with bias + residual
+    Cb = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.jpp_op_gemm(B.JPP_BF16, M, N, K, At.data_ptr(), lda, aks, Bt.data_ptr(), ldb, bks, Cb.data_ptr(), N,
+                  B.OUT_STORE, bt.data_ptr(), rt.data_ptr(), stream())
+    # store fp32, no epilogue terms
+    Cf = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    B.jpp_op_gemm(B.JPP_BF16, M, N, K, At.data_ptr(), lda, aks, Bt.data_ptr(), ldb, bks, Cf.data_ptr(), N,
+                  B.OUT_STORE_F32, None, None, stream())
+    # accumulate into fp32 twice
+    Ca = torch.ones((M, N), dtype=torch.float32, device=DEV)
+    for _ in range(2):
+        B.jpp_op_gemm(B.JPP_BF16, M, N, K, At.data_ptr(), lda, aks, Bt.data_ptr(), ldb, bks, Ca.data_ptr(), N,
+                      B.OUT_ACC_F32, None, None, stream())
+    torch.cuda.synchronize()
+    assert rel_l2(host(Cf), ref) < 1e-5                       # fp32 accumulate of exact bf16 products
+    assert np.abs(host(Cf) - ref).max() < 1e-3 * math.sqrt(K)
+    assert rel_l2(host(Ca), 1.0 + 2 * ref) < 1e-5
+    assert rel_l2(host(Cb), ref + bias[None, :] + res) < 4e-3  # one bf16 rounding of the result
+
+
+def test_gemm_bf16_padded_leading_dimensions_do_not_touch_neighbours():
+    """Sub-matrix views: ld > row length.  The cells outside C's view must stay untouched."""
+    rng = np.random.default_rng(0)
+    M, N, K = 72, 136, 200
+    Abig = inp.round_to_dtype(rng.standard_normal((M, K + 24)), inp.DT_BF16)
+    Bbig = inp.round_to_dtype(rng.standard_normal((K, N + 8)), inp.DT_BF16)     # k-strided operand
+    At, Bt = dev(Abig, torch.bfloat16), dev(Bbig, torch.bfloat16)
+    Cbig = torch.full((M, N + 16), -3.0, dtype=torch.float32, device=DEV)
+    B.jpp_op_gemm(B.JPP_BF16, M, N, K, At.data_ptr(), K + 24, 0, Bt.data_ptr(), N + 8, 1, Cbig.data_ptr(), N + 16,
+                  B.OUT_STORE_F32, None, None, stream())
+    torch.cuda.synchronize()
+    got = host(Cbig)
+    assert rel_l2(got[:, :N], Abig[:, :K] @ Bbig[:, :N]) < 1e-5
+    assert np.all(got[:, N:] == -3.0)
+
+
+def test_gemm_rejects_unsupported_shapes():
+    t = torch.zeros(64, 64, dtype=torch.bfloat16, device=DEV)
+    f = torch.zeros(64, 64, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.JppError) as e:
+        B.jpp_op_gemm(B.JPP_BF16, 12, 64, 64, t.data_ptr(), 64, 0, t.data_ptr(), 64, 0, f.data_ptr(), 64,
+                      B.OUT_STORE_F32, None, None, stream())
+    assert e.value.status == B.JPP_EINVAL
+    with pytest.raises(B.JppError):
+        B.jpp_op_gemm(B.JPP_BF16, 64, 64, 64, t.data_ptr(), 32, 0, t.data_ptr(), 64, 0, f.data_ptr(), 64,
+                      B.OUT_STORE_F32, None, None, stream())
+    with pytest.raises(B.JppError):
+        B.jpp_op_gemm(B.JPP_BF16, 64, 64, 64, None, 64, 0, t.data_ptr(), 64, 0, f.data_ptr(), 64,
+                      B.OUT_STORE_F32, None, None, stream())
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 3, 7), (130, 70, 33), (64, 64, 16)])
+@pytest.mark.parametrize("aks,bks", [(0, 0), (0, 1), (1, 1)])
+def test_gemm_f32(M, N, K, aks, bks):
+    rng = np.random.default_rng(1)
+    A = inp.round_to_dtype(rng.standard_normal((M, K)), inp.DT_F32)
+    Bm = inp.round_to_dtype(rng.standard_normal((N, K)), inp.DT_F32)
+    bias = inp.round_to_dtype(rng.standard_normal(N), inp.DT_F32)
+    At = dev(A.T if aks else A, torch.float32)
+    Bt = dev(Bm.T if bks else Bm, torch.float32)
+    Cc = torch.ones((M, N), dtype=torch.float32, device=DEV)
+    B.jpp_op_gemm(B.JPP_F32, M, N, K, At.data_ptr(), M if aks else K, aks, Bt.data_ptr(), N if bks else K, bks,
+                  Cc.data_ptr(), N, B.OUT_ACC_F32, dev(bias, torch.float32).data_ptr(), None, stream())
+    torch.cuda.synchronize()
+    assert rel_l2(host(Cc), 1.0 + A @ Bm.T + bias[None, :]) < 1e-6
+
+
+def attention_reference(spec, qkv, dout=None):
+    mb, seq, Hq, Hkv, hd = spec.microbatch, spec.seq_len, spec.n_q_heads, spec.n_kv_heads, spec.head_dim
+    nq, nkv = Hq * hd, Hkv * hd
+    q = qkv[:, :nq].reshape(mb, seq, Hq, hd)
+    k = qkv[:, nq:nq + nkv].reshape(mb, seq, Hkv, hd)
+    v = qkv[:, nq + nkv:].reshape(mb, seq, Hkv, hd)
+    O, P = so.attention_forward(spec, q, k, v)
+    if dout is None:
+        return O.reshape(mb * seq, nq), None
+    dq, dk, dv = so.attention_backward(spec, q, k, v, P, dout.reshape(mb, seq, Hq, hd))
+    dqkv = np.concatenate([dq.reshape(mb * seq, nq), dk.reshape(mb * seq, nkv), dv.reshape(mb * seq, nkv)], axis=1)
+    return O.reshape(mb * seq, nq), dqkv
+
+
+ATTN_CASES = [
+    # dtype, mb, seq, Hq, Hkv, hd
+    (inp.DT_F32, 2, 64, 4, 4, 32), (inp.DT_F32, 1, 37, 3, 1, 24), (inp.DT_BF16, 2, 200, 4, 2, 64),
+    (inp.DT_BF16, 2, 256, 4, 4, 128), (inp.DT_BF16, 1, 328, 8, 1, 128), (inp.DT_BF16, 1, 72, 2, 2, 128),
+    (inp.DT_BF16, 1, 1, 2, 1, 128),
+]
+
+
+@pytest.mark.parametrize("dtype,mb,seq,Hq,Hkv,hd", ATTN_CASES)
+def test_attention_forward_backward(dtype, mb, seq, Hq, Hkv, hd):
+    rng = np.random.default_rng(seq + hd)
+    spec = so.StageSpec(n_layers=1, d_model=Hq * hd, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=hd, d_ffn=8,
+                        seq_len=seq, microbatch=mb)
+    T, nqkv = mb * seq, (Hq + 2 * Hkv) * hd
+    qkv = inp.round_to_dtype(rng.standard_normal((T, nqkv)), dtype)
+    dout = inp.round_to_dtype(rng.standard_normal((T, Hq * hd)), dtype)
+    tdt = torch.bfloat16 if dtype == inp.DT_BF16 else torch.float32
+    tq, tdo = dev(qkv, tdt), dev(dout, tdt)
+    out = torch.zeros((T, Hq * hd), dtype=tdt, device=DEV)
+    lse = torch.zeros((mb, Hq, seq), dtype=torch.float32, device=DEV)
+    B.jpp_op_attention_fwd(dtype, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(), stream())
+    dqkv = torch.zeros((T, nqkv), dtype=tdt, device=DEV)
+    delta = torch.zeros((mb, Hq, seq), dtype=torch.float32, device=DEV)
+    B.jpp_op_attention_bwd(dtype, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                           tdo.data_ptr(), dqkv.data_ptr(), delta.data_ptr(), stream())
+    torch.cuda.synchronize()
+    O, dref = attention_reference(spec, qkv, dout)
+    tol = 1e-5 if dtype == inp.DT_F32 else 1e-2
+    assert rel_l2(host(out), O) < tol
+    # log-sum-exp of the scaled scores, from the definition
+    q = qkv[:, :Hq * hd].reshape(mb, seq, Hq, hd)
+    k = qkv[:, Hq * hd:(Hq + Hkv) * hd].reshape(mb, seq, Hkv, hd)
+    b, h, t = mb - 1, Hq - 1, seq - 1
+    s = (k[b, :t + 1, h // (Hq // Hkv)] @ q[b, t, h]) / math.sqrt(hd)
+    assert abs(host(lse)[b, h, t] - (s.max() + math.log(np.exp(s - s.max()).sum()))) < (1e-4 if dtype == inp.DT_F32 else 2e-2)
+    nq, nkv = Hq * hd, Hkv * hd
+    g = host(dqkv)
+    for name, sl in (("dq", slice(0, nq)), ("dk", slice(nq, nq + nkv)), ("dv", slice(nq + nkv, nqkv))):
+        if np.linalg.norm(dref[:, sl]) == 0.0:      # seq = 1: dS = 0 exactly, so dq = dk = 0
+            assert np.abs(g[:, sl]).max() < 1e-5, name
+            continue
+        assert rel_l2(g[:, sl], dref[:, sl]) < (1e-5 if dtype == inp.DT_F32 else 1.5e-2), name
+
+
+@pytest.mark.parametrize("dtype", [inp.DT_F32, inp.DT_BF16])
+@pytest.mark.parametrize("norm", [inp.NORM_LAYERNORM, inp.NORM_RMSNORM])
+@pytest.mark.parametrize("rows,d", [(5, 72), (300, 2048), (64, 12288)])
+def test_norm_forward_backward(dtype, norm, rows, d):
+    if dtype == inp.DT_F32 and d > 8192:
+        pytest.skip("fp32 rows are limited to 8192 columns")
+    rng = np.random.default_rng(rows + d)
+    spec = so.StageSpec(n_layers=1, d_model=d, n_q_heads=1, n_kv_heads=1, head_dim=8, d_ffn=8, seq_len=1,
+                        microbatch=1, norm=norm)
+    x = inp.round_to_dtype(rng.standard_normal((rows, d)) * 1.5 + 0.3, dtype)
+    g = inp.round_to_dtype(1 + 0.1 * rng.standard_normal(d), dtype)
+    b = inp.round_to_dtype(0.1 * rng.standard_normal(d), dtype)
+    dy = inp.round_to_dtype(rng.standard_normal((rows, d)), dtype)
+    add = inp.round_to_dtype(rng.standard_normal((rows, d)), dtype)
+    tdt = torch.bfloat16 if dtype == inp.DT_BF16 else torch.float32
+    tx, tg, tb, tdy, tadd = (dev(a, tdt) for a in (x, g, b, dy, add))
+    y = torch.zeros_like(tx)
+    stats = torch.zeros(2 * rows, dtype=torch.float32, device=DEV)
+    B.jpp_op_norm_fwd(dtype, norm, rows, d, 1e-5, tx.data_ptr(), tg.data_ptr(), tb.data_ptr(), y.data_ptr(),
+                      stats.data_ptr(), stream())
+    dx = torch.zeros_like(tx)
+    gg = torch.ones(d, dtype=torch.float32, device=DEV)
+    gb = torch.ones(d, dtype=torch.float32, device=DEV)
+    part = torch.zeros(B.jpp_op_colreduce_scratch(rows, d), dtype=torch.float32, device=DEV)
+    B.jpp_op_norm_bwd(dtype, norm, rows, d, tx.data_ptr(), tg.data_ptr(), stats.data_ptr(), tdy.data_ptr(),
+                      tadd.data_ptr(), dx.data_ptr(), gg.data_ptr(), gb.data_ptr(), part.data_ptr(), stream())
+    torch.cuda.synchronize()
+    yr, xhat, rstd = so.norm_forward(spec, x, g, b if norm == inp.NORM_LAYERNORM else 0.0)
+    dxr, dgr, dbr = so.norm_backward(spec, dy, xhat, rstd, g)
+    tol = 1e-5 if dtype == inp.DT_F32 else 6e-3
+    assert rel_l2(host(y), yr) < tol
+    assert rel_l2(host(dx), dxr + add) < tol
+    assert rel_l2(host(gg), 1 + dgr) < 1e-5
+    if norm == inp.NORM_LAYERNORM:
+        assert rel_l2(host(gb), 1 + dbr) < 1e-5
+    else:
+        assert np.all(host(gb) == 1.0)
+
+
+@pytest.mark.parametrize("dtype", [inp.DT_F32, inp.DT_BF16])
+@pytest.mark.parametrize("act", [inp.ACT_GELU, inp.ACT_GELU_TANH, inp.ACT_SWIGLU])
+def test_activation_forward_backward(dtype, act):
+    rows, f = 77, 520
+    rng = np.random.default_rng(act)
+    spec = so.StageSpec(n_layers=1, d_model=8, n_q_heads=1, n_kv_heads=1, head_dim=8, d_ffn=f, seq_len=1,
+                        microbatch=1, act=act)
+    f1 = 2 * f if act == inp.ACT_SWIGLU else f
+    h = inp.round_to_dtype(rng.standard_normal((rows, f1)) * 2, dtype)
+    da = inp.round_to_dtype(rng.standard_normal((rows, f)), dtype)
+    tdt = torch.bfloat16 if dtype == inp.DT_BF16 else torch.float32
+    th, tda = dev(h, tdt), dev(da, tdt)
+    a = torch.zeros((rows, f), dtype=tdt, device=DEV)
+    dh = torch.zeros((rows, f1), dtype=tdt, device=DEV)
+    B.jpp_op_act_fwd(dtype, act, rows, f, th.data_ptr(), a.data_ptr(), stream())
+    B.jpp_op_act_bwd(dtype, act, rows, f, th.data_ptr(), tda.data_ptr(), dh.data_ptr(), stream())
+    torch.cuda.synchronize()
+    tol = 2e-6 if dtype == inp.DT_F32 else 4e-3
+    assert rel_l2(host(a), so.act_forward(spec, h)) < tol
+    assert rel_l2(host(dh), so.act_backward(spec, h, da)) < tol
+
+
+# ------------------------------------------------------------------ full benchmark shapes
+
+FULL_GEMMS = [
+    # the GPT-3-shaped layer's GEMMs at T = 2048 tokens: (M, N, K, a_kstrided, b_kstrided, out_mode)
+    ("qkv fwd", 2048, 36864, 12288, 0, 0, B.OUT_STORE),
+    ("ffn-down dgrad", 2048, 49152, 12288, 0, 1, B.OUT_STORE),
+    ("ffn-up wgrad", 49152, 12288, 2048, 1, 1, B.OUT_ACC_F32),
+    ("lm-head fwd", 4096, 50304, 4096, 0, 0, B.OUT_STORE_F32),
+]
+
+
+@pytest.mark.parametrize("name,M,N,K,aks,bks,mode", FULL_GEMMS)
+def test_gemm_full_shape_sampled_entries(name, M, N, K, aks, bks, mode):
+    """At the benchmark's sizes the outputs are checked on sampled entries (random ones plus
+    the corners and tile edges), each against a float64 dot product of the kernel's inputs."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(M + N + K)
+    A = torch.randn((K, M) if aks else (M, K), generator=g, device=DEV).to(torch.bfloat16)
+    Bm = (torch.randn((K, N) if bks else (N, K), generator=g, device=DEV) * 0.02).to(torch.bfloat16)
+    if mode == B.OUT_STORE:
+        Cc = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    else:
+        Cc = torch.ones((M, N), dtype=torch.float32, device=DEV)
+    B.jpp_op_gemm(B.JPP_BF16, M, N, K, A.data_ptr(), M if aks else K, aks, Bm.data_ptr(), N if bks else K, bks,
+                  Cc.data_ptr(), N, mode, None, None, stream())
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    ms = np.concatenate([rng.integers(0, M, 4096), [0, 0, M - 1, M - 1, 255, 256, M - 256, M - 257]])
+    ns = np.concatenate([rng.integers(0, N, 4096), [0, N - 1, 0, N - 1, 255, 256, N - 256, N - 257]])
+    mi, ni = torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)
+    # the sampled operand rows are brought to the host; the reference is a float64 dot product there
+    a_rows = (A[:, mi].T if aks else A[mi, :]).float().cpu().numpy().astype(np.float64)
+    b_rows = (Bm[:, ni].T if bks else Bm[ni, :]).float().cpu().numpy().astype(np.float64)
+    ref = np.einsum("sk,sk->s", a_rows, b_rows)
+    got = Cc[mi, ni].double().cpu().numpy()
+    if mode == B.OUT_ACC_F32:
+        ref = ref + 1.0
+    tol = 4e-3 if mode == B.OUT_STORE else 1e-5
+    assert rel_l2(got, ref) < tol, name
+    assert np.all(np.isfinite(got))

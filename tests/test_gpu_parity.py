@@ -1,0 +1,254 @@
+"""GPU parity: the HIP stage executor against the fp64 CPU oracle, element by element, on
+the same seeded host arrays, through the C ABI.
+
+Tolerances (max over tensors of ||gpu - oracle||_2 / ||oracle||_2): 1e-5 for fp32 storage,
+2e-2 for bf16 storage with fp32 accumulation.  Accumulated gradients must be bit-identical
+across schedules that keep the per-stage backward order.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import stage_oracle as so
+from oracle import schedules as osch
+from paper_2412_14374_amd import binding as B
+from paper_2412_14374_amd import inputs as inp
+from paper_2412_14374_amd.harness import Stage
+
+pytestmark = pytest.mark.gpu
+
+TOL = {inp.DT_F32: 1e-5, inp.DT_BF16: 2e-2}
+
+
+def spec_of(w):
+    return so.StageSpec(n_layers=w.n_layers, d_model=w.d_model, n_q_heads=w.n_q_heads,
+                        n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, d_ffn=w.d_ffn,
+                        seq_len=w.seq_len, microbatch=w.microbatch, norm=w.norm, act=w.act,
+                        use_bias=bool(w.use_bias), rope=bool(w.rope), rope_theta=w.rope_theta,
+                        norm_eps=w.norm_eps, loss_head=bool(w.loss_head), vocab=w.vocab)
+
+
+def oracle_tasks(tasks):
+    return [(i, "fwd" if ty == B.JPP_FWD else "bwd", s) for (i, ty, s) in tasks]
+
+
+def rel_l2(a, b):
+    nb = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / nb if nb > 0 else np.linalg.norm(a)
+
+
+def compare(w, got, ref):
+    worst = ("", 0.0)
+    def upd(name, a, b):
+        nonlocal worst
+        assert a.shape == b.shape, name
+        assert np.all(np.isfinite(a)), name
+        e = rel_l2(a, b)
+        if e > worst[1]:
+            worst = (name, e)
+    for s in w.stage_ids:
+        for i in range(w.n_microbatches):
+            if w.loss_head:
+                upd(f"loss[{s}][{i}]", np.asarray(got["loss"][s][i]), np.asarray(ref["loss"][s][i]))
+            else:
+                upd(f"y[{s}][{i}]", got["y"][s][i], ref["y"][s][i])
+            upd(f"dx[{s}][{i}]", got["dx"][s][i], ref["dx"][s][i])
+        for li, lg in enumerate(ref["grads"][s]["layers"]):
+            for k, v in lg.items():
+                upd(f"G[{s}].layer{li}.{k}", got["grads"][s]["layers"][li][k], v)
+        if w.loss_head:
+            for k, v in ref["grads"][s]["head"].items():
+                upd(f"G[{s}].head.{k}", got["grads"][s]["head"][k], v)
+    return worst
+
+
+def run_both(w, perturb=True, seed=inp.SEED, tasks=None):
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec),
+                                               so.head_param_shapes(spec) if w.loss_head else None,
+                                               seed=seed, perturb=perturb)
+    st = Stage(w, tasks=tasks)
+    # the library's layout must be the oracle's layout
+    layer, head = st.layer_shapes()
+    assert layer == [(n, tuple(s)) for n, s in so.layer_param_shapes(spec)]
+    if w.loss_head:
+        assert head == [(n, tuple(s)) for n, s in so.head_param_shapes(spec)]
+    st.set_params_host(params)
+    st.bind(x, cot, tg)
+    st.zero_grads()
+    st.run()
+    got = st.results()
+    ref = so.run_task_list(spec, params, oracle_tasks(st.tasks), x, cot, tg)
+    assert B.jpp_stage_peak_in_flight(st.h) == ref["peak_live"]
+    return st, got, ref
+
+
+def test_c1_tiny_gpt_fp32_gpipe_matches_oracle():
+    w = inp.C1
+    st, got, ref = run_both(w, perturb=False)
+    name, err = compare(w, got, ref)
+    print("C1 worst", name, err)
+    assert err <= TOL[w.dtype], (name, err)
+    st.close()
+
+
+FP32_VARIANTS = {
+    "gpt-perturbed": dict(),
+    "llama": dict(n_q_heads=4, n_kv_heads=2, head_dim=32, norm=inp.NORM_RMSNORM, act=inp.ACT_SWIGLU,
+                  use_bias=0, rope=1, d_ffn=256, sched=inp.SCHED_1F1B, P=3, rank=1),
+    "head": dict(loss_head=1, vocab=1000, sched=inp.SCHED_1F1B, P=2, rank=1, seq_len=48),
+    "gelu-tanh-ragged": dict(act=inp.ACT_GELU_TANH, seq_len=37, microbatch=3, d_model=72, n_q_heads=3,
+                             n_kv_heads=3, head_dim=24, d_ffn=100),
+    "interleaved": dict(sched=inp.SCHED_INTERLEAVED, P=2, rank=1, V=2, n_layers=1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FP32_VARIANTS))
+def test_fp32_variants_match_oracle(name):
+    """Every code path of the executor in fp32 storage, where 1e-5 leaves no room for an
+    indexing or formula mistake."""
+    from dataclasses import replace
+    w = replace(inp.C1, name="fp32-" + name, **FP32_VARIANTS[name])
+    st, got, ref = run_both(w, perturb=True, seed=11)
+    worst, err = compare(w, got, ref)
+    print(name, "worst", worst, err)
+    assert err <= TOL[w.dtype], (worst, err)
+    st.close()
+
+
+TWINS = {
+    # same structure as the benchmark configurations, at sizes the oracle finishes in seconds;
+    # sizes chosen to span several GEMM tiles with ragged tails (e.g. 320 = 256 + 64)
+    "C2": inp.shrunk_twin(inp.C2, d_model=384, seq_len=160, d_ffn=1536, n_q_heads=3, n_microbatches=4),
+    "C3": inp.shrunk_twin(inp.C3, d_model=1024, seq_len=320, d_ffn=1408, n_q_heads=8, n_microbatches=4),
+    "C4": inp.shrunk_twin(inp.C4, d_model=512, seq_len=256, d_ffn=2048, n_q_heads=4, n_microbatches=8),
+    "C5": inp.shrunk_twin(inp.C5, d_model=256, seq_len=136, d_ffn=1024, n_q_heads=2, vocab=5000 + 24,
+                          n_microbatches=3),
+}
+
+
+@pytest.mark.parametrize("name", sorted(TWINS))
+def test_bf16_twins_match_oracle(name):
+    from dataclasses import replace
+    w = TWINS[name]
+    if name == "C4":
+        w = replace(w, P=2, rank=0)          # interleaved needs M % P == 0; 2 virtual stages kept
+    st, got, ref = run_both(w, perturb=True, seed=5)
+    worst, err = compare(w, got, ref)
+    print(name, "twin worst", worst, err)
+    assert err <= TOL[w.dtype], (worst, err)
+    st.close()
+
+
+def test_gradients_bit_identical_across_schedules_and_runs():
+    """Section 2.2.1: schedules only reorder tasks.  With the per-stage backward order kept,
+    the fp32 accumulation G <- G + g_i has one association, so GPipe, 1F1B at every rank and a
+    repeated run must give identical bits; y and dx likewise."""
+    from dataclasses import replace
+    w = replace(TWINS["C2"], n_layers=2)
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec), None, seed=3)
+    s0 = w.stage_ids[0]
+    M = w.n_microbatches
+    ref = None
+    lists = [B.jpp_schedule_make(inp.SCHED_GPIPE, 4, w.rank, 1, M)]
+    lists += [[(i, ty, s0) for (i, ty, _) in B.jpp_schedule_make(inp.SCHED_1F1B, 4, r, 1, M)] for r in range(4)]
+    lists.append(lists[0])
+    for tasks in lists:
+        tasks = [(i, ty, s0) for (i, ty, _) in tasks]
+        st = Stage(w, tasks=tasks)
+        st.set_params_host(params)
+        st.bind(x, cot, tg)
+        st.zero_grads()
+        st.run()
+        st.sync()
+        g = st.grads_tensor(0).cpu()
+        ys = torch.stack([t.cpu() for t in st.out_y])
+        dxs = torch.stack([t.cpu() for t in st.out_dx])
+        if ref is None:
+            ref = (g, ys, dxs)
+        else:
+            assert torch.equal(g.view(torch.int32), ref[0].view(torch.int32))
+            assert torch.equal(ys.view(torch.int16), ref[1].view(torch.int16))
+            assert torch.equal(dxs.view(torch.int16), ref[2].view(torch.int16))
+        st.close()
+    # a reversed backward order is a different association: equal to tolerance only
+    rev = [(i, B.JPP_FWD, s0) for i in range(M)] + [(i, B.JPP_BWD, s0) for i in reversed(range(M))]
+    st = Stage(w, tasks=rev)
+    st.set_params_host(params)
+    st.bind(x, cot, tg)
+    st.zero_grads()
+    st.run()
+    st.sync()
+    g = st.grads_tensor(0).cpu()
+    assert rel_l2(g.double().numpy(), ref[0].double().numpy()) < 1e-5
+    st.close()
+
+
+def test_second_run_without_zeroing_doubles_the_gradients():
+    """Section 3.1: each backward ADDS to the gradient buffers."""
+    w = inp.C1
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec), None)
+    st = Stage(w)
+    st.set_params_host(params)
+    st.bind(x, cot, tg)
+    st.zero_grads()
+    st.run()
+    g1 = st.grads_tensor(0).cpu().double()
+    st.run()
+    g2 = st.grads_tensor(0).cpu().double()
+    assert rel_l2(g2.numpy(), 2 * g1.numpy()) < 1e-6
+    st.close()
+
+
+def test_executor_bookkeeping_and_errors():
+    from dataclasses import replace
+    w = replace(inp.C1, sched=inp.SCHED_1F1B, P=4, rank=1, n_microbatches=6)
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec), None)
+    st = Stage(w)                               # max_in_flight = peak + 1
+    assert st.max_in_flight == 4
+    # run before parameters / boundary -> JPP_ESTATE
+    arr, n = B.tasks_array(st.tasks)
+    with pytest.raises(B.JppError) as e:
+        B.jpp_stage_run(st.h, arr, n, st.compute.cuda_stream, st.side.cuda_stream)
+    assert e.value.status == B.JPP_ESTATE
+    st.set_params_host(params)
+    st.bind(x, cot, tg)
+    st.zero_grads()
+    st.run()
+    st.sync()
+    assert B.jpp_stage_peak_in_flight(st.h) == 3            # min(P - rank, M)
+    assert B.jpp_stage_host_syncs(st.h) == 0
+    # every receive except the very first is issued ahead of its consumer when a slot is spare
+    assert B.jpp_stage_prefetched(st.h) == 2 * w.n_microbatches - 1
+    assert 0 <= B.jpp_stage_pending_peak(st.h) <= 3
+    # GPipe needs 6 live stashes, the arena holds 4 -> JPP_ECAPACITY, nothing launched
+    g = B.jpp_schedule_make(inp.SCHED_GPIPE, 4, 1, 1, 6)
+    arr, n = B.tasks_array(g)
+    with pytest.raises(B.JppError) as e:
+        B.jpp_stage_run(st.h, arr, n, st.compute.cuda_stream, st.side.cuda_stream)
+    assert e.value.status == B.JPP_ECAPACITY
+    # rule violation -> JPP_ESCHED
+    arr, n = B.tasks_array(st.tasks[:-1])
+    with pytest.raises(B.JppError) as e:
+        B.jpp_stage_run(st.h, arr, n, st.compute.cuda_stream, st.side.cuda_stream)
+    assert e.value.status == B.JPP_ESCHED
+    with pytest.raises(B.JppError) as e:
+        B.jpp_stage_run(st.h, arr, n, st.compute.cuda_stream, st.compute.cuda_stream)
+    assert e.value.status == B.JPP_EINVAL
+    st.close()
+    # exactly the peak: still correct, fewer prefetches
+    st2 = Stage(w, max_in_flight=3)
+    st2.set_params_host(params)
+    st2.bind(x, cot, tg)
+    st2.zero_grads()
+    st2.run()
+    got = st2.results()
+    ref = so.run_task_list(spec, params, oracle_tasks(st2.tasks), x, cot, tg)
+    worst, err = compare(w, got, ref)
+    assert err <= 1e-5, (worst, err)
+    assert B.jpp_stage_prefetched(st2.h) < 2 * w.n_microbatches - 1
+    st2.close()
