@@ -1,0 +1,189 @@
+"""Benchmark of the stage executor on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4]
+
+A step is one jpp_stage_zero_grads + one jpp_stage_run of the configuration's whole task list
+(all microbatches, all owned stages, forward and backward, gradient accumulation, boundary
+copies), with inputs resident in HBM.  Prints one JSON line (see the design doc for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops_per_microbatch(w):
+    """2*T*d_in*d_out per linear map x3 (forward, input grad, weight grad); causal attention at
+    half of the full score matrix (forward 2*mb*Hq*seq^2*hd, backward twice that); norms and
+    activations not counted; no recompute counted."""
+    T = w.tokens
+    nq, nkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
+    f1 = 2 * w.d_ffn if w.act == 2 else w.d_ffn
+    lin = w.d_model * (nq + 2 * nkv) + nq * w.d_model + w.d_model * f1 + w.d_ffn * w.d_model
+    per_layer = 3 * 2.0 * T * lin + 3 * 2.0 * w.microbatch * w.n_q_heads * w.seq_len ** 2 * w.head_dim
+    total = per_layer * w.n_layers
+    if w.loss_head:
+        total += 3 * 2.0 * T * w.d_model * w.vocab
+    return total * len(w.stage_ids)
+
+
+def wgrad_shapes(w):
+    """(M, N, K) of the weight-gradient GEMMs of one backward task, in launch order."""
+    T = w.tokens
+    nq, nkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
+    f1 = 2 * w.d_ffn if w.act == 2 else w.d_ffn
+    per_layer = [(w.d_model, w.d_ffn, T), (f1, w.d_model, T), (w.d_model, nq, T), (nq + 2 * nkv, w.d_model, T)]
+    out = per_layer * w.n_layers
+    if w.loss_head:
+        out = [(w.vocab, w.d_model, T)] + out
+    return out
+
+
+def time_dominant_kernel(w, torch, B, reps=3):
+    """Average launch duration of the dominant kernel -- the weight-gradient GEMM with the fused
+    fp32 accumulation, one template instantiation launched with the shapes above -- measured
+    with HIP events on the stream it is launched on."""
+    s = torch.cuda.Stream()
+    shapes = wgrad_shapes(w)
+    total_ms, total_flops, n = 0.0, 0.0, 0
+    with torch.cuda.stream(s):
+        for (M, N, K) in shapes:
+            A = torch.randn((K, M), device="cuda:0").to(torch.bfloat16)
+            Bm = torch.randn((K, N), device="cuda:0").to(torch.bfloat16)
+            C = torch.zeros((M, N), dtype=torch.float32, device="cuda:0")
+            args = (B.JPP_BF16, M, N, K, A.data_ptr(), M, 1, Bm.data_ptr(), N, 1, C.data_ptr(), N, B.OUT_ACC_F32,
+                    None, None, s.cuda_stream)
+            B.jpp_op_gemm(*args)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s)
+            for _ in range(reps):
+                B.jpp_op_gemm(*args)
+            e1.record(s)
+            s.synchronize()
+            total_ms += e0.elapsed_time(e1)
+            total_flops += reps * 2.0 * M * N * K
+            n += reps
+            del A, Bm, C
+    avg_ms = total_ms / n
+    return avg_ms, total_flops / n
+
+
+def cpu_baseline():
+    """The fp64 oracle, as it stands, on one microbatch (forward + backward) of one layer of a
+    shrunk twin of the GPT-3-shaped stage: d_model 1536, 12 heads of 128, FFN 6144, seq 1024."""
+    import numpy as np
+    from oracle import stage_oracle as so
+    from paper_2412_14374_amd import inputs as inp
+    w = inp.shrunk_twin(inp.C4, d_model=1536, seq_len=1024, d_ffn=6144, n_q_heads=12, n_microbatches=1)
+    spec = so.StageSpec(n_layers=1, d_model=w.d_model, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
+                        head_dim=w.head_dim, d_ffn=w.d_ffn, seq_len=w.seq_len, microbatch=w.microbatch)
+    rng = np.random.default_rng(0)
+    p = {k: rng.standard_normal(s) * 0.02 for k, s in so.layer_param_shapes(spec)}
+    x = rng.standard_normal((1, w.seq_len, w.d_model))
+    c = rng.standard_normal((1, w.seq_len, w.d_model))
+    t0 = time.perf_counter()
+    y, cache = so.layer_forward(spec, p, x)
+    so.layer_backward(spec, p, cache, c)
+    dt = time.perf_counter() - t0
+    flops = so.algorithmic_flops_per_microbatch(spec)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "seconds": dt, "microbatches_per_s_extrapolated_to_workload": None,
+            "sample": "fp64 numpy oracle, forward+backward of ONE microbatch of ONE layer of a shrunk twin "
+                      "(d_model 1536, 12 heads x 128, FFN 6144, seq 1024, GeLU, LayerNorm); "
+                      f"{flops / 1e9:.0f} algorithmic GFLOP"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs one pipeline stage on ONE GPU (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2412_14374_amd import binding as B
+    from paper_2412_14374_amd import inputs as inp
+    from paper_2412_14374_amd.harness import Stage
+
+    B.lib()                                     # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    w = inp.CONFIGS[a.config]
+    st = Stage(w)
+    st.set_params_random(seed=0)
+    st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM
+    for _ in range(a.warmup):
+        st.zero_grads()
+        st.run()
+    st.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        st.zero_grads()
+        st.run()
+    st.sync()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+    flops_step = algorithmic_flops_per_microbatch(w) * w.n_microbatches
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    mb_per_s = w.n_microbatches / (ms_per_step * 1e-3)
+    # sanity: the run produced finite gradients
+    g = st.grads_tensor(0)
+    finite = bool(torch.isfinite(g).all().item())
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+
+    out = {
+        "metric": "stage fwd+bwd TFLOP/s, % of bf16 MFMA peak, microbatches/s (1 GPU)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == inp.DT_BF16 else "f32", "data": "synthetic",
+        "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "microbatches_per_s": mb_per_s,
+        "grads_finite": finite,
+        "config": {"workload": w.name, "layers_per_stage": w.n_layers, "virtual_stages": w.V,
+                   "d_model": w.d_model, "heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_ffn": w.d_ffn,
+                   "seq_len": w.seq_len, "microbatch": w.microbatch, "n_microbatches": w.n_microbatches,
+                   "schedule": ["gpipe", "1f1b", "interleaved-1f1b"][w.sched], "P": w.P, "rank": w.rank,
+                   "algorithmic_tflop_per_microbatch": algorithmic_flops_per_microbatch(w) / 1e12},
+    }
+    if w.dtype == inp.DT_BF16:
+        avg_ms, flops_per_launch = time_dominant_kernel(w, torch, B)
+        ach = flops_per_launch / (avg_ms * 1e-3) / 1e12
+        out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel<..., k-strided A, k-strided B> "
+                           "(weight gradient with fused fp32 accumulate)",
+                           "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": ach / PEAK_BF16_TFLOPS, "avg_launch_ms": avg_ms,
+                           "flops_per_launch": flops_per_launch, "traffic": None}
+    if not a.no_cpu_baseline:
+        cb = cpu_baseline()
+        per_mb = algorithmic_flops_per_microbatch(w)
+        cb["microbatches_per_s_extrapolated_to_workload"] = cb["value"] * 1e12 / per_mb
+        out["cpu_baseline"] = cb
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

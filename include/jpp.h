@@ -187,6 +187,11 @@ jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, i
                        const void* B, int ldb, int b_kstrided, void* C, int ldc, int out_mode,
                        const void* bias, const void* residual, void* stream);
 
+/* Benchmarking knob: 0 (default) lets the library pick the bf16 GEMM tile configuration
+ * from the problem size; 1 = 256x256 tile with 4 waves, 2 = 256x256 with 8 waves,
+ * 3 = 128x128 with 4 waves.  Process-wide; results are identical for every value. */
+void jpp_set_gemm_variant(int variant);
+
 /* Causal self-attention over a fused qkv tensor [mb*seq, (Hq + 2*Hkv)*hd] (q heads, then
  * k heads, then v heads; query head h reads kv head h / (Hq/Hkv)).  out: [mb*seq, Hq*hd];
  * lse: fp32 [mb, Hq, seq] natural-log-sum-exp of the scaled scores. */

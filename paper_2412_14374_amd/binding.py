@@ -59,6 +59,7 @@ _SIGNATURES = {
     "jpp_stage_prefetched": (C.c_int, [C.c_void_p]),
     "jpp_stage_host_syncs": (C.c_int, [C.c_void_p]),
     "jpp_last_error": (C.c_char_p, []),
+    "jpp_set_gemm_variant": (None, [C.c_int]),
     "jpp_op_gemm": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
                               C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "jpp_op_attention_fwd": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 4),
@@ -234,6 +235,10 @@ def jpp_stage_prefetched(h):
 
 def jpp_stage_host_syncs(h):
     return lib().jpp_stage_host_syncs(h)
+
+
+def jpp_set_gemm_variant(v):
+    lib().jpp_set_gemm_variant(v)
 
 
 def jpp_op_gemm(dtype, M, N, K, A, lda, a_ks, B, ldb, b_ks, Cp, ldc, out_mode, bias, residual, stream):

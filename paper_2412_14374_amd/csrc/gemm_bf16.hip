@@ -11,19 +11,24 @@
 // the `grads += mugrads` of the paper's Section 3.1 fused into the producing GEMM: the
 // unrounded fp32 accumulator is added to the fp32 gradient.
 //
-// Design (one workgroup = one BM x BN tile of C, BK = 64):
+// Design (one workgroup = one BM x BN tile of C, BK = 64, two LDS stages):
 //  * LDS holds each operand tile as [rows][64 k] bf16, 128 bytes per row, with the 16-byte
 //    chunk index XOR-swizzled by ((row ^ row>>3) & 7): the 16-byte MFMA fragment reads
-//    (lanes = consecutive rows, same k chunk), the row-major staging writes (lanes =
-//    consecutive k chunks) and the transposing staging writes (lanes = rows 8 apart) all
-//    spread over all banks.
+//    (lanes = consecutive rows, same k chunk) and the transposing staging writes (lanes =
+//    rows 8 apart) both spread over all banks.
+//  * A k-contiguous operand goes HBM -> LDS directly (buffer_load ... lds): each wave
+//    instruction fills 1 KiB of LDS in lane order, and the swizzle is applied by choosing
+//    which global chunk each lane fetches.  No VGPRs and no ds_write are spent on it.
 //  * A k-strided operand is transposed on the way in: a thread loads an 8(k) x 8(row) block
 //    as eight 16-byte row segments, transposes it in registers with byte permutes and writes
 //    eight 16-byte k-runs.  The MFMA loop is identical for all four layout combinations.
-//  * Global loads are raw buffer loads: rows beyond the matrix read as zero through the
-//    hardware range check, the contiguous dimension is predicated, so M, N, K need only be
-//    multiples of 8.  Loads for tile k+1 are issued before the MFMAs of tile k and written
-//    to the other LDS buffer afterwards (one barrier per k tile).
+//  * Rows beyond the matrix read as zero through the buffer range check, the contiguous
+//    dimension is predicated, so M, N, K need only be multiples of 8.
+//  * MFMA fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued
+//    before the MFMAs of k-step kk.
+//  * Epilogue: accumulators go through LDS (free after the main loop) so that every global
+//    access is 8 or 16 bytes per lane on full rows; the fp32 gradient tile is read with
+//    16-byte loads issued before the staging.
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
 //    works on a contiguous band of tiles and shares operand panels in its own L2.
 #include "device_utils.h"
@@ -38,11 +43,14 @@ constexpr int kRowBytes = BK * 2;  // 128
 constexpr uint32_t kOOB = 0x7FFFFFFFu;
 constexpr uint32_t kMaxRecords = 0x7FFFFF00u;
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
 __device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  // 0x00020000: raw buffer, 32-bit data format field for gfx9 (DATA_FORMAT = 32)
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, long long bytes) {
+  const uint32_t n = bytes > (long long)kMaxRecords ? kMaxRecords : (bytes < 0 ? 0u : (uint32_t)bytes);
+  // 0x00020000: untyped raw buffer, 32-bit data format (gfx9 resource word 3)
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)n, 0x00020000);
 }
 
 struct Epilogue {
@@ -66,82 +74,75 @@ __device__ inline void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
   }
 }
 
-template <int R, int NT, bool KS, int PHASE>
-struct Loader {
-  // k-contiguous: R*8 chunks over NT threads.  k-strided: R units (8k x 8rows blocks), unit u
-  // handled by thread (u + PHASE) % NT when R <= NT.
-  static constexpr int kChunksPerThread = KS ? 8 : (R * 8 / NT);
-  static constexpr int kUnits = KS ? ((R + NT - 1) / NT) : 1;
-  static_assert(KS || (R * 8) % NT == 0, "tile rows x 8 must be a multiple of the thread count");
-  static_assert(!KS || R <= NT, "k-strided loader expects at most one unit per thread");
-  u32x4 regs[kChunksPerThread];
-  uint32_t goff[kChunksPerThread];  // tile-local byte offsets (k-contig) / row offsets (k-strided)
+// k-contiguous operand, HBM -> LDS without registers.  Wave w, step i fills LDS rows
+// [(i*NW + w)*8, +8): lane l lands on row (l>>3), physical chunk (l&7), and therefore
+// fetches the logical chunk (l&7) ^ swz(row).
+template <int R, int NT>
+struct DirectLoader {
+  static constexpr int NW = NT / 64;
+  static constexpr int kSteps = R * 8 / NT;
+  static_assert((R * 8) % NT == 0, "tile rows x 8 must be a multiple of the thread count");
+  int wave, lane;
+  __device__ inline void init(const Operand&, int) {
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    lane = threadIdx.x % 64;
+  }
+  __device__ inline void issue(const Operand& op, int r0, int k0, int K, char* tile) {
+    const bf16* base = op.p + (size_t)r0 * op.ld + k0;
+    const auto rs = make_rsrc(base, ((long long)(op.rows - r0) * op.ld - k0) * 2);
+#pragma unroll
+    for (int i = 0; i < kSteps; ++i) {
+      const int rowblk = i * NW + wave;
+      const int row = rowblk * 8 + (lane >> 3);
+      const int kc = (lane & 7) ^ swz(row);
+      const uint32_t off = (k0 + kc * 8 < K) ? (uint32_t)(row * op.ld + kc * 8) * 2u : kOOB;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + rowblk * 1024), 16, (int)off, 0, 0, 0);
+    }
+  }
+  __device__ inline void store(char*) {}
+};
+
+// k-strided operand: R units of 8(k) x 8(rows); unit u is handled by thread (u + PHASE) % NT.
+template <int R, int NT, int PHASE>
+struct TransposeLoader {
+  static_assert(R <= NT, "expects at most one unit per thread");
+  u32x4 regs[8];
+  uint32_t goff[8];
   bool active;
   int unit;
-
   __device__ inline void init(const Operand& op, int r0) {
-    const int tid = threadIdx.x;
-    if constexpr (!KS) {
-      active = true;
+    unit = (threadIdx.x + NT - PHASE) % NT;
+    active = unit < R;
+    const int rb = unit % (R / 8), kb = unit / (R / 8);
+    const bool col_ok = (r0 + rb * 8) < op.rows;
 #pragma unroll
-      for (int i = 0; i < kChunksPerThread; ++i) {
-        const int c = tid + NT * i;
-        const int row = c >> 3, kc = c & 7;
-        goff[i] = (uint32_t)(row * op.ld + kc * 8) * 2u;
-      }
-    } else {
-      unit = (tid + NT - PHASE) % NT;
-      active = unit < R;
+    for (int j = 0; j < 8; ++j)
+      goff[j] = (active && col_ok) ? (uint32_t)((kb * 8 + j) * op.ld + rb * 8) * 2u : kOOB;
+  }
+  __device__ inline void issue(const Operand& op, int r0, int k0, int K, char*) {
+    const bf16* base = op.p + (size_t)k0 * op.ld + r0;
+    const auto rs = make_rsrc(base, ((long long)(K - k0) * op.ld - r0) * 2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)goff[j], 0, 0);
+  }
+  __device__ inline void store(char* tile) {
+    if (active) {
+      u32x4 t[8];
+      transpose8x8(regs, t);
       const int rb = unit % (R / 8), kb = unit / (R / 8);
-      const bool col_ok = (r0 + rb * 8) < op.rows;
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        goff[j] = (active && col_ok) ? (uint32_t)((kb * 8 + j) * op.ld + rb * 8) * 2u : kOOB;
-    }
-  }
-
-  __device__ inline void issue(const Operand& op, int r0, int k0, int K) {
-    if constexpr (!KS) {
-      const bf16* base = op.p + (size_t)r0 * op.ld + k0;
-      const long long rem = ((long long)(op.rows - r0) * op.ld - k0) * 2;
-      const auto rs = make_rsrc(base, (uint32_t)(rem > (long long)kMaxRecords ? kMaxRecords : (rem < 0 ? 0 : rem)));
-#pragma unroll
-      for (int i = 0; i < kChunksPerThread; ++i) {
-        const int kc = (threadIdx.x + NT * i) & 7;
-        const uint32_t off = (k0 + kc * 8 < K) ? goff[i] : kOOB;
-        regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
-      }
-    } else {
-      const bf16* base = op.p + (size_t)k0 * op.ld + r0;
-      const long long rem = ((long long)(K - k0) * op.ld - r0) * 2;
-      const auto rs = make_rsrc(base, (uint32_t)(rem > (long long)kMaxRecords ? kMaxRecords : (rem < 0 ? 0 : rem)));
-#pragma unroll
-      for (int j = 0; j < 8; ++j) regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)goff[j], 0, 0);
-    }
-  }
-
-  __device__ inline void store(char* lds) {
-    if constexpr (!KS) {
-#pragma unroll
-      for (int i = 0; i < kChunksPerThread; ++i) {
-        const int c = threadIdx.x + NT * i;
-        const int row = c >> 3, kc = c & 7;
-        *reinterpret_cast<u32x4*>(lds + row * kRowBytes + ((kc ^ swz(row)) << 4)) = regs[i];
-      }
-    } else {
-      if (active) {
-        u32x4 t[8];
-        transpose8x8(regs, t);
-        const int rb = unit % (R / 8), kb = unit / (R / 8);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const int row = rb * 8 + r;
-          *reinterpret_cast<u32x4*>(lds + row * kRowBytes + ((kb ^ swz(row)) << 4)) = t[r];
-        }
+      for (int r = 0; r < 8; ++r) {
+        const int row = rb * 8 + r;
+        *reinterpret_cast<u32x4*>(tile + row * kRowBytes + ((kb ^ swz(row)) << 4)) = t[r];
       }
     }
   }
 };
+
+template <int R, int NT, bool KS, int PHASE>
+struct LoaderSel { typedef DirectLoader<R, NT> type; };
+template <int R, int NT, int PHASE>
+struct LoaderSel<R, NT, true, PHASE> { typedef TransposeLoader<R, NT, PHASE> type; };
 
 // Maps the linear workgroup id to a tile.  Ids are dealt round-robin to the 8 XCDs, so the
 // ids {x, x+8, x+16, ...} share one L2: give each XCD a contiguous range of tile numbers, and
@@ -154,7 +155,6 @@ __device__ inline void tile_of(int pid, int tiles_m, int tiles_n, int& tm, int& 
     const int per = (total + kXcd - 1) / kXcd;
     const int x = pid % kXcd, r = pid / kXcd;
     const int full = total % kXcd == 0 ? kXcd : total % kXcd;  // XCDs holding `per` tiles
-    // XCD x owns tiles [start_x, start_x + count_x): the first `full` XCDs get `per`, the rest per-1.
     const int start = x < full ? x * per : full * per + (x - full) * (per - 1);
     t = start + r;
   }
@@ -175,8 +175,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
   constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
+  constexpr int kStage = kABytes + kBBytes;
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  // buffer s: A at lds + s*(kABytes + kBBytes), B right after it
 
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   int tm, tn;
@@ -187,8 +187,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, half = lane >> 5;
 
-  Loader<BM, NT, AKS, 0> la;
-  Loader<BN, NT, BKS, NT / 2> lb;
+  typename LoaderSel<BM, NT, AKS, 0>::type la;
+  typename LoaderSel<BN, NT, BKS, NT / 2>::type lb;
   la.init(A, m0);
   lb.init(B, n0);
 
@@ -200,51 +200,56 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // fragment read offsets: row-dependent part is loop invariant
-  int a_row_off[MI], a_swz[MI], b_row_off[NI], b_swz[NI];
+  // fragment addresses: byte offset of (row, chunk = half) inside a tile; the k-step kk adds
+  // 2*kk to the chunk, i.e. XORs (2*kk) << 4 into the offset (swizzle and k-step commute).
+  int a_off[MI], b_off[NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int row = wm * TM + i * 32 + l32;
-    a_row_off[i] = row * kRowBytes;
-    a_swz[i] = swz(row);
+    a_off[i] = row * kRowBytes + ((half ^ swz(row)) << 4);
   }
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int row = wn * TN + j * 32 + l32;
-    b_row_off[j] = row * kRowBytes;
-    b_swz[j] = swz(row);
+    b_off[j] = kABytes + row * kRowBytes + ((half ^ swz(row)) << 4);
   }
 
   const int nk = (K + BK - 1) / BK;
-  la.issue(A, m0, 0, K);
-  lb.issue(B, n0, 0, K);
+  la.issue(A, m0, 0, K, lds);
+  lb.issue(B, n0, 0, K, lds + kABytes);
   la.store(lds);
   lb.store(lds + kABytes);
   __syncthreads();
 
+  bf16x8 af[2][MI], bfr[2][NI];
   for (int kt = 0; kt < nk; ++kt) {
-    char* cur = lds + (kt & 1) * (kABytes + kBBytes);
-    char* nxt = lds + ((kt + 1) & 1) * (kABytes + kBBytes);
+    char* cur = lds + (kt & 1) * kStage;
+    char* nxt = lds + ((kt + 1) & 1) * kStage;
     const bool more = kt + 1 < nk;
     if (more) {
-      la.issue(A, m0, (kt + 1) * BK, K);
-      lb.issue(B, n0, (kt + 1) * BK, K);
+      la.issue(A, m0, (kt + 1) * BK, K, nxt);
+      lb.issue(B, n0, (kt + 1) * BK, K, nxt + kABytes);
     }
 #pragma unroll
+    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(cur + a_off[i]);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(cur + b_off[j]);
+#pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MI], bfr[NI];
-      const int chunk = kk * 2 + half;
+      if (kk + 1 < BK / 16) {
+        const int x = ((kk + 1) * 2) << 4;
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(cur + a_row_off[i] + ((chunk ^ a_swz[i]) << 4));
+        for (int i = 0; i < MI; ++i)
+          af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(cur + (a_off[i] ^ x));
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(cur + kABytes + b_row_off[j] + ((chunk ^ b_swz[j]) << 4));
+        for (int j = 0; j < NI; ++j)
+          bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(cur + (b_off[j] ^ x));
+      }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
     }
     if (more) {
       la.store(nxt);
@@ -253,30 +258,65 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
     __syncthreads();
   }
 
-  // Epilogue.  Accumulator register r of lane (l32, half) is C[8*(r/4) + 4*half + r%4][l32]
-  // of its 32x32 block.
+  // ---- epilogue -------------------------------------------------------------------------
+  // Accumulator register r of lane (l32, half) is C[8*(r/4) + 4*half + r%4][l32] of its 32x32
+  // block.  Each wave stages one 32 x TN row block at a time in its private LDS region and
+  // reads it back row-major, 4 consecutive columns per lane.
+  constexpr int LDW = TN + 4;                 // padded row length in floats
+  constexpr int LPR = TN / 4;                 // lanes per row
+  constexpr int RPI = 64 / LPR;               // rows per wave instruction
+  constexpr int kSteps = 32 / RPI;
+  static_assert((size_t)NT / 64 * 32 * LDW * 4 <= 2 * (size_t)kStage, "epilogue staging must fit in LDS");
+  float* stage = reinterpret_cast<float*>(lds) + (size_t)wave * 32 * LDW;
+  const int erow = lane / LPR, ecol = (lane % LPR) * 4;
+  const int n = n0 + wn * TN + ecol;
+  const bool n_ok = n < N;
+  f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
+  if (ep.bias && n_ok) {
+    const bf16x4 b = *reinterpret_cast<const bf16x4*>(ep.bias + n);
 #pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int n = n0 + wn * TN + j * 32 + l32;
-    if (n >= N) continue;
-    const float bias = ep.bias ? (float)ep.bias[n] : 0.f;
+    for (int e = 0; e < 4; ++e) bias4[e] = (float)b[e];
+  }
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+  for (int i = 0; i < MI; ++i) {
+    const int mbase = m0 + wm * TM + i * 32;
+    f32x4 prev[kSteps];
+    if (ep.out_mode == OUT_ACC_F32) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (m >= M) continue;
-        const size_t idx = (size_t)m * ep.ldc + n;
-        float v = acc[i][j][r] + bias;
-        if (ep.residual) v += (float)ep.residual[idx];
-        if (ep.out_mode == OUT_STORE) {
-          reinterpret_cast<bf16*>(ep.C)[idx] = (bf16)v;
-        } else if (ep.out_mode == OUT_STORE_F32) {
-          reinterpret_cast<float*>(ep.C)[idx] = v;
-        } else {
-          float* c = reinterpret_cast<float*>(ep.C) + idx;
-          *c = *c + v;
-        }
+      for (int s = 0; s < kSteps; ++s) {
+        const int m = mbase + s * RPI + erow;
+        if (n_ok && m < M)
+          prev[s] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(ep.C) + (size_t)m * ep.ldc + n);
+      }
+    }
+    wave_lds_sync();  // the previous pass's reads are done before its region is rewritten
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage[(8 * (r >> 2) + 4 * half + (r & 3)) * LDW + j * 32 + l32] = acc[i][j][r];
+    wave_lds_sync();
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) {
+      const int m = mbase + s * RPI + erow;
+      if (!(n_ok && m < M)) continue;
+      f32x4 v = *reinterpret_cast<const f32x4*>(stage + (s * RPI + erow) * LDW + ecol);
+      const size_t idx = (size_t)m * ep.ldc + n;
+      v += bias4;
+      if (ep.residual) {
+        const bf16x4 rv = *reinterpret_cast<const bf16x4*>(ep.residual + idx);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+      }
+      if (ep.out_mode == OUT_STORE) {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+        *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(ep.C) + idx) = o;
+      } else if (ep.out_mode == OUT_STORE_F32) {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = v;
+      } else {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = prev[s] + v;
       }
     }
   }
@@ -310,6 +350,8 @@ hipError_t launch_layout(const GemmDesc& g, hipStream_t s) {
   return launch_cfg<BM, BN, WM, WN, true, false>(g, s);
 }
 
+int g_variant = 0;
+
 }  // namespace
 
 bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why) {
@@ -329,10 +371,19 @@ bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why) {
     why = "leading dimension smaller than the row length";
     return false;
   }
+  if (g.bias && ((uintptr_t)g.bias % 8) != 0) { why = "bias must be 8-byte aligned"; return false; }
   return true;
 }
 
+void set_gemm_variant(int v) { g_variant = v; }
+
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
+  switch (g_variant) {
+    case 1: return launch_layout<256, 256, 2, 2>(g, s);
+    case 2: return launch_layout<256, 256, 2, 4>(g, s);
+    case 3: return launch_layout<128, 128, 2, 2>(g, s);
+    default: break;
+  }
   // Large tiles when they still give every CU work; smaller ones otherwise.
   const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (big_tiles >= 192) return launch_layout<256, 256, 2, 2>(g, s);

@@ -33,6 +33,7 @@ struct GemmDesc {
 hipError_t launch_gemm_f32(const GemmDesc& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s);
 bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why);
+void set_gemm_variant(int v);  // 0 = automatic tile selection; 1..3 force a configuration (benchmarking)
 
 struct AttnDesc {
   int mb, seq, Hq, Hkv, hd;

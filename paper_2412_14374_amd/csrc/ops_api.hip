@@ -11,6 +11,8 @@ int chunk_of(int dtype) { return dtype == JPP_BF16 ? 8 : 4; }
 
 extern "C" {
 
+void jpp_set_gemm_variant(int variant) { set_gemm_variant(variant); }
+
 jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, int a_kstrided, const void* B,
                        int ldb, int b_kstrided, void* C, int ldc, int out_mode, const void* bias,
                        const void* residual, void* stream) {
