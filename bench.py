@@ -78,11 +78,12 @@ def time_dominant_kernel(w, torch, B, reps=3):
 
 def cpu_baseline():
     """The fp64 oracle, as it stands, on one microbatch (forward + backward) of one layer of a
-    shrunk twin of the GPT-3-shaped stage: d_model 1536, 12 heads of 128, FFN 6144, seq 1024."""
+    half-width twin of the GPT-3-shaped stage: d_model 6144, 48 heads of 128, FFN 24576, seq 2048
+    (about 5.7 algorithmic TFLOP, 10-30 s of host time)."""
     import numpy as np
     from oracle import stage_oracle as so
     from paper_2412_14374_amd import inputs as inp
-    w = inp.shrunk_twin(inp.C4, d_model=1536, seq_len=1024, d_ffn=6144, n_q_heads=12, n_microbatches=1)
+    w = inp.shrunk_twin(inp.C4, d_model=6144, seq_len=2048, d_ffn=24576, n_q_heads=48, n_microbatches=1)
     spec = so.StageSpec(n_layers=1, d_model=w.d_model, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                         head_dim=w.head_dim, d_ffn=w.d_ffn, seq_len=w.seq_len, microbatch=w.microbatch)
     rng = np.random.default_rng(0)
@@ -102,7 +103,7 @@ def cpu_baseline():
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "seconds": dt, "microbatches_per_s_extrapolated_to_workload": None,
             "sample": "fp64 numpy oracle, forward+backward of ONE microbatch of ONE layer of a shrunk twin "
-                      "(d_model 1536, 12 heads x 128, FFN 6144, seq 1024, GeLU, LayerNorm); "
+                      "(d_model 6144, 48 heads x 128, FFN 24576, seq 2048, GeLU, LayerNorm); "
                       f"{flops / 1e9:.0f} algorithmic GFLOP"}
 
 
