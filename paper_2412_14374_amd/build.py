@@ -18,7 +18,7 @@ SOURCES = ["schedule.cpp", "stage.hip", "ops_api.hip", "rowwise.hip", "gemm_f32.
            "attention_generic.hip", "attention_mfma.hip"]
 # -packed-fp32-ops is switched OFF for device code (packed fp32 forms have misbehaved on the
 # target machines); the host pass does not know the feature and says so, harmlessly.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -11,24 +11,33 @@
 // the `grads += mugrads` of the paper's Section 3.1 fused into the producing GEMM: the
 // unrounded fp32 accumulator is added to the fp32 gradient.
 //
-// Design (one workgroup = one BM x BN tile of C, BK = 64, two LDS stages):
-//  * LDS holds each operand tile as [rows][64 k] bf16, 128 bytes per row, with the 16-byte
-//    chunk index XOR-swizzled by ((row ^ row>>3) & 7): the 16-byte MFMA fragment reads
-//    (lanes = consecutive rows, same k chunk) and the transposing staging writes (lanes =
-//    rows 8 apart) both spread over all banks.
-//  * A k-contiguous operand goes HBM -> LDS directly (buffer_load ... lds): each wave
-//    instruction fills 1 KiB of LDS in lane order, and the swizzle is applied by choosing
-//    which global chunk each lane fetches.  No VGPRs and no ds_write are spent on it.
-//  * A k-strided operand is transposed on the way in: a thread loads an 8(k) x 8(row) block
-//    as eight 16-byte row segments, transposes it in registers with byte permutes and writes
-//    eight 16-byte k-runs.  The MFMA loop is identical for all four layout combinations.
+// Design (one workgroup = one BM x BN tile of C):
+//  * LDS is a ring of NS stages of BKT k-columns each and every stage is filled HBM -> LDS
+//    directly (buffer_load ... lds: no VGPRs, no ds_write).  The default is 256 x 256 x 64
+//    with two stages and eight waves: a 64-wide stage makes every row of a k-contiguous tile
+//    one full 128-byte cache line (32-wide stages fetch every line twice and lose more than
+//    their deeper prefetch gains), and 256 x 256 is the largest tile whose accumulators fit
+//    the register file -- measured on MI355X the CU-side fill rate (about 20-25 bytes per
+//    clock per CU from L2) is what bounds this kernel, so bytes per flop matter most.
+//  * Every wave instruction of such a load fills 1 KiB of LDS in lane order; bank-conflict
+//    freedom is obtained by XOR-swizzling WHICH global 16-byte chunk each lane fetches.
+//      k-contiguous tile: LDS [rows][BKT] bf16; fragment = one 16-byte read per lane.
+//      k-strided tile:    LDS [BKT][rows] bf16, as in memory; fragment = two
+//                         ds_read_b64_tr_b16 per lane (the CDNA4 transposing LDS read: lane i
+//                         of a 16-lane group receives element (i & 3) of the 8-byte rows
+//                         4j + (i >> 2), j = 0..3, that the group's lanes address).
+//    Both give lane (row = lane % 32, half = lane / 32) the 8 k-values 16*kk + 8*half + 0..7,
+//    so the MFMA loop is the same for all four layout combinations.
+//  * The loads are inline assembly and the cross-wave hand-over is an explicit
+//    "s_waitcnt vmcnt(loads still allowed in flight); s_barrier": the compiler's wait-count
+//    pass cannot tell the stages apart and would wait for every load in flight.
+//  * Loads and fragment reads are issued between groups of MFMAs (one 32-row block each), so
+//    that their issue slots hide behind the matrix pipe; fragments are double-buffered in
+//    registers and the last k-step of a stage is split around the barrier.
 //  * Rows beyond the matrix read as zero through the buffer range check, the contiguous
 //    dimension is predicated, so M, N, K need only be multiples of 8.
-//  * MFMA fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued
-//    before the MFMAs of k-step kk.
-//  * Epilogue: accumulators go through LDS (free after the main loop) so that every global
-//    access is 8 or 16 bytes per lane on full rows; the fp32 gradient tile is read with
-//    16-byte loads issued before the staging.
+//  * Epilogue: accumulators go through LDS so that every global access is 8 or 16 bytes per
+//    lane on full rows; the fp32 gradient tile is read with 16-byte loads issued first.
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
 //    works on a contiguous band of tiles and shares operand panels in its own L2.
 #include "device_utils.h"
@@ -38,19 +47,39 @@ namespace jpp {
 
 namespace {
 
-constexpr int BK = 64;
-constexpr int kRowBytes = BK * 2;  // 128
 constexpr uint32_t kOOB = 0x7FFFFFFFu;
 constexpr uint32_t kMaxRecords = 0x7FFFFF00u;
+constexpr int kMaxStages = 5;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_t;
 
-__device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, long long bytes) {
+// Raw buffer descriptor (base, stride 0, num_records = bytes, untyped 32-bit format).
+__device__ inline i32x4 make_rsrc(const void* p, long long bytes) {
   const uint32_t n = bytes > (long long)kMaxRecords ? kMaxRecords : (bytes < 0 ? 0u : (uint32_t)bytes);
-  // 0x00020000: untyped raw buffer, 32-bit data format (gfx9 resource word 3)
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)n, 0x00020000);
+  const unsigned long long a = (unsigned long long)p;
+  i32x4 r;
+  r[0] = (int)(uint32_t)a;
+  r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
+  r[2] = (int)n;
+  r[3] = 0x00020000;
+  return r;
+}
+
+// 16 bytes per lane, HBM -> LDS without passing through registers: the wave's 64 lanes fill
+// the 1 KiB at LDS byte address `lds_addr` in lane order; lanes whose byte offset `voff` is
+// outside the descriptor's range store zeros.  Issued as inline assembly on purpose: the
+// compiler's wait-count pass would otherwise make every later LDS read wait for ALL loads in
+// flight, which defeats a multi-stage ring; the waits are placed by hand below.
+__device__ inline void dma16(const i32x4& rsrc, uint32_t lds_addr, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rsrc)
+               : "memory", "m0");
+}
+__device__ inline uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(size_t)(__attribute__((address_space(3))) const char*)p;
 }
 
 struct Epilogue {
@@ -62,87 +91,87 @@ struct Operand {
   const bf16* p; int ld; int rows;  // rows = M (for A) or N (for B)
 };
 
-// Transposes an 8x8 block of bf16: in[j] holds 8 consecutive rows' elements at k = j; out[r]
-// holds 8 consecutive k at row r.
-__device__ inline void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int w = r >> 1;
-    const uint32_t sel = (r & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) out[r][p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
-  }
-}
+// ---- operand tiles -------------------------------------------------------------------------
+// R rows (m or n) x BKT k.  `issue` starts the HBM -> LDS copy of the tile whose first row is
+// r0 and first k is k0 (every thread issues kLoads loads, also for tiles past the end of K,
+// which then read as zero: the wait counts below rely on a fixed number per tile).
+// `frag` returns the MFMA operand of the 32-row block `blk` for k-step kk.
 
-// k-contiguous operand, HBM -> LDS without registers.  Wave w, step i fills LDS rows
-// [(i*NW + w)*8, +8): lane l lands on row (l>>3), physical chunk (l&7), and therefore
-// fetches the logical chunk (l&7) ^ swz(row).
-template <int R, int NT>
-struct DirectLoader {
-  static constexpr int NW = NT / 64;
-  static constexpr int kSteps = R * 8 / NT;
-  static_assert((R * 8) % NT == 0, "tile rows x 8 must be a multiple of the thread count");
-  int wave, lane;
-  __device__ inline void init(const Operand&, int) {
-    wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-    lane = threadIdx.x % 64;
-  }
-  __device__ inline void issue(const Operand& op, int r0, int k0, int K, char* tile) {
+template <int R, int BKT, int NT>
+struct KContigTile {
+  static constexpr int kRowBytes = BKT * 2;
+  static constexpr int CPR = BKT / 8;            // 16-byte chunks per row
+  static constexpr int RPL = 128 / kRowBytes;    // rows per 128-byte LDS line (1 or 2)
+  static constexpr int kRowsPerInstr = 64 / CPR;
+  static constexpr int kLoads = R * CPR / NT;
+  static constexpr int kBytes = R * kRowBytes;
+  static_assert((R * CPR) % NT == 0, "tile chunks must divide evenly over the threads");
+  __device__ static inline int swz(int row) { return (row / RPL) % CPR; }
+
+  // load i (0 .. kLoads-1) of the tile at (r0, k0) into the tile at LDS address `tile`
+  __device__ static inline void issue_one(const Operand& op, int r0, int k0, int K, uint32_t tile, int i) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
     const bf16* base = op.p + (size_t)r0 * op.ld + k0;
-    const auto rs = make_rsrc(base, ((long long)(op.rows - r0) * op.ld - k0) * 2);
-#pragma unroll
-    for (int i = 0; i < kSteps; ++i) {
-      const int rowblk = i * NW + wave;
-      const int row = rowblk * 8 + (lane >> 3);
-      const int kc = (lane & 7) ^ swz(row);
-      const uint32_t off = (k0 + kc * 8 < K) ? (uint32_t)(row * op.ld + kc * 8) * 2u : kOOB;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + rowblk * 1024), 16, (int)off, 0, 0, 0);
-    }
+    const i32x4 rs = make_rsrc(base, ((long long)(op.rows - r0) * op.ld - k0) * 2);
+    const int blk = i * (NT / 64) + wave;       // 1 KiB block of the tile
+    const int row = blk * kRowsPerInstr + lane / CPR;
+    const int kc = (lane % CPR) ^ swz(row);
+    const uint32_t off = (k0 + kc * 8 < K) ? (uint32_t)(row * op.ld + kc * 8) * 2u : kOOB;
+    dma16(rs, tile + blk * 1024, off);
   }
-  __device__ inline void store(char*) {}
+  // byte offset of the kk = 0 fragment of the 32-row block starting at `row0`
+  __device__ static inline int frag_base(int row0, int l32, int half) {
+    const int row = row0 + l32;
+    return row * kRowBytes + ((half ^ swz(row)) << 4);
+  }
+  __device__ static inline bf16x8 frag(const char* tile, int base, int kk) {
+    // chunk = 2*kk + half; the swizzle only touches the low bits that 2*kk leaves alone or
+    // flips consistently: (2kk + half) ^ s == ((half ^ s) ^ 2kk)
+    return *reinterpret_cast<const bf16x8*>(tile + (base ^ ((kk * 2) << 4)));
+  }
 };
 
-// k-strided operand: R units of 8(k) x 8(rows); unit u is handled by thread (u + PHASE) % NT.
-template <int R, int NT, int PHASE>
-struct TransposeLoader {
-  static_assert(R <= NT, "expects at most one unit per thread");
-  u32x4 regs[8];
-  uint32_t goff[8];
-  bool active;
-  int unit;
-  __device__ inline void init(const Operand& op, int r0) {
-    unit = (threadIdx.x + NT - PHASE) % NT;
-    active = unit < R;
-    const int rb = unit % (R / 8), kb = unit / (R / 8);
-    const bool col_ok = (r0 + rb * 8) < op.rows;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      goff[j] = (active && col_ok) ? (uint32_t)((kb * 8 + j) * op.ld + rb * 8) * 2u : kOOB;
-  }
-  __device__ inline void issue(const Operand& op, int r0, int k0, int K, char*) {
+template <int R, int BKT, int NT>
+struct KStridedTile {
+  static constexpr int kRowBytes = R * 2;        // one k-row of the tile
+  static constexpr int CPR = R / 8;
+  static constexpr int kRowsPerInstr = 64 / CPR;
+  static constexpr int kLoads = BKT * CPR / NT;
+  static constexpr int kBytes = BKT * kRowBytes;
+  static_assert((BKT * CPR) % NT == 0 && CPR <= 64, "tile chunks must divide evenly over the threads");
+
+  __device__ static inline void issue_one(const Operand& op, int r0, int k0, int K, uint32_t tile, int i) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
     const bf16* base = op.p + (size_t)k0 * op.ld + r0;
-    const auto rs = make_rsrc(base, ((long long)(K - k0) * op.ld - r0) * 2);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)goff[j], 0, 0);
+    const i32x4 rs = make_rsrc(base, ((long long)(K - k0) * op.ld - r0) * 2);
+    const int blk = i * (NT / 64) + wave;
+    const int k = blk * kRowsPerInstr + lane / CPR;
+    const int c = (lane % CPR) ^ ((k & 3) << 1);
+    const uint32_t off = (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
+    dma16(rs, tile + blk * 1024, off);
   }
-  __device__ inline void store(char* tile) {
-    if (active) {
-      u32x4 t[8];
-      transpose8x8(regs, t);
-      const int rb = unit % (R / 8), kb = unit / (R / 8);
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int row = rb * 8 + r;
-        *reinterpret_cast<u32x4*>(tile + row * kRowBytes + ((kb ^ swz(row)) << 4)) = t[r];
-      }
-    }
+  // Lane l of a 16-lane group addresses the 8-byte row (k = .. + (l>>2), rows 4*(l&3) .. +3)
+  // and receives k = .. + 0..3 for row (l & 15) of the group's 16 rows.
+  __device__ static inline int frag_base(int row0, int l32, int half) {
+    const int r = l32 & 15;
+    const int row = row0 + (l32 & 16) + 4 * (r & 3);
+    const int k = half * 8 + (r >> 2);
+    return k * kRowBytes + (((row >> 3) ^ ((k & 3) << 1)) << 4) + (row & 4) * 2;
+  }
+  __device__ static inline bf16x8 frag(const char* tile, int base, int kk) {
+    const char* p = tile + base + kk * 16 * kRowBytes;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(p + 4 * kRowBytes));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
   }
 };
 
-template <int R, int NT, bool KS, int PHASE>
-struct LoaderSel { typedef DirectLoader<R, NT> type; };
-template <int R, int NT, int PHASE>
-struct LoaderSel<R, NT, true, PHASE> { typedef TransposeLoader<R, NT, PHASE> type; };
+template <int R, int BKT, int NT, bool KS>
+struct TileSel { typedef KContigTile<R, BKT, NT> type; };
+template <int R, int BKT, int NT>
+struct TileSel<R, BKT, NT, true> { typedef KStridedTile<R, BKT, NT> type; };
 
 // Maps the linear workgroup id to a tile.  Ids are dealt round-robin to the 8 XCDs, so the
 // ids {x, x+8, x+16, ...} share one L2: give each XCD a contiguous range of tile numbers, and
@@ -168,15 +197,45 @@ __device__ inline void tile_of(int pid, int tiles_m, int tiles_n, int& tm, int& 
   tn = in_band / rows_in_band;
 }
 
-template <int BM, int BN, int WM, int WN, bool AKS, bool BKS>
+// "s_waitcnt vmcnt(N); s_barrier" with a compiler-level memory barrier and no fence: the
+// fence of __syncthreads() would wait for every outstanding load, which is exactly what the
+// multi-stage ring must not do.
+template <int N>
+__device__ inline void wait_loads_and_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, int K, Operand A, Operand B,
                                                                   Epilogue ep) {
   constexpr int NT = 64 * WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
-  constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
-  constexpr int kStage = kABytes + kBBytes;
-  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int KSTEPS = BKT / 16;
+  typedef typename TileSel<BM, BKT, NT, AKS>::type TA;
+  typedef typename TileSel<BN, BKT, NT, BKS>::type TB;
+  constexpr int kABytes = TA::kBytes;
+  constexpr int kStage = TA::kBytes + TB::kBytes;
+  constexpr int kLoadsPerStage = TA::kLoads + TB::kLoads;
+  static_assert(NS >= 2 && NS <= kMaxStages, "2..5 stages");
+  static_assert(MI % NI == 0 && MI % 2 == 0, "wave tile: rows a multiple of columns, at least 64 rows");
+
+  // One __shared__ array per stage (distinct objects: see the header comment).
+  __shared__ __attribute__((aligned(1024))) char stage0[kStage];
+  __shared__ __attribute__((aligned(1024))) char stage1[kStage];
+  __shared__ __attribute__((aligned(1024))) char stage2[NS > 2 ? kStage : 16];
+  __shared__ __attribute__((aligned(1024))) char stage3[NS > 3 ? kStage : 16];
+  __shared__ __attribute__((aligned(1024))) char stage4[NS > 4 ? kStage : 16];
+  auto stage = [&](int s) -> char* {
+    switch (s) {
+      case 0: return stage0;
+      case 1: return stage1;
+      case 2: return stage2;
+      case 3: return stage3;
+      default: return stage4;
+    }
+  };
 
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   int tm, tn;
@@ -187,11 +246,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, half = lane >> 5;
 
-  typename LoaderSel<BM, NT, AKS, 0>::type la;
-  typename LoaderSel<BN, NT, BKS, NT / 2>::type lb;
-  la.init(A, m0);
-  lb.init(B, n0);
-
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -200,63 +254,87 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // fragment addresses: byte offset of (row, chunk = half) inside a tile; the k-step kk adds
-  // 2*kk to the chunk, i.e. XORs (2*kk) << 4 into the offset (swizzle and k-step commute).
-  int a_off[MI], b_off[NI];
+  int a_base[MI], b_base[NI];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int row = wm * TM + i * 32 + l32;
-    a_off[i] = row * kRowBytes + ((half ^ swz(row)) << 4);
-  }
+  for (int i = 0; i < MI; ++i) a_base[i] = TA::frag_base(wm * TM + i * 32, l32, half);
 #pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int row = wn * TN + j * 32 + l32;
-    b_off[j] = kABytes + row * kRowBytes + ((half ^ swz(row)) << 4);
-  }
-
-  const int nk = (K + BK - 1) / BK;
-  la.issue(A, m0, 0, K, lds);
-  lb.issue(B, n0, 0, K, lds + kABytes);
-  la.store(lds);
-  lb.store(lds + kABytes);
-  __syncthreads();
+  for (int j = 0; j < NI; ++j) b_base[j] = kABytes + TB::frag_base(wn * TN + j * 32, l32, half);
 
   bf16x8 af[2][MI], bfr[2][NI];
-  for (int kt = 0; kt < nk; ++kt) {
-    char* cur = lds + (kt & 1) * kStage;
-    char* nxt = lds + ((kt + 1) & 1) * kStage;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      la.issue(A, m0, (kt + 1) * BK, K, nxt);
-      lb.issue(B, n0, (kt + 1) * BK, K, nxt + kABytes);
-    }
+  // one load of k-tile kt (A loads first, then B loads) into the stage at LDS address dst
+  auto issue_load = [&](int kt, uint32_t dst, int idx) {
+    if (idx < TA::kLoads) TA::issue_one(A, m0, kt * BKT, K, dst, idx);
+    else TB::issue_one(B, n0, kt * BKT, K, dst + kABytes, idx - TA::kLoads);
+  };
+  auto mfma_row = [&](int set, int i) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(cur + a_off[i]);
+    for (int j = 0; j < NI; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+  };
+  // the part of k-step kk's fragments that is fetched while MFMA row i runs
+  auto read_frag_part = [&](const char* tile, int kk, int set, int i) {
+    af[set][i] = TA::frag(tile, a_base[i], kk);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(cur + b_off[j]);
+    for (int j = 0; j < NI; ++j)
+      if (j * MI / NI == i && (j * MI) % NI == 0) bfr[set][j] = TB::frag(tile, b_base[j], kk);
+  };
+
+  // Ring: stage kt % NS holds k-tile kt.  One "group" = one 32-row block of MFMAs (NI of
+  // them); memory instructions are issued between groups so that they hide in the shadow of
+  // the matrix pipe: the loads of tile kt+NS-1 are spread over the first kSpread groups of
+  // iteration kt, and the fragment reads of k-step kk+1 over the groups of k-step kk.
+  constexpr int kGroups = KSTEPS * MI;
+  constexpr int kSpread = NS == 2 ? kGroups / 2 : kGroups;   // with 2 stages the tile is needed at the end
+  constexpr int LPG = (kLoadsPerStage + kSpread - 1) / kSpread;
+  // loads of the refill tile issued before the barrier of an iteration
+  constexpr int kGroupsBeforeBarrier = (KSTEPS - 1) * MI + MI / 2;
+  constexpr int kIssuedBeforeBarrier =
+      (kGroupsBeforeBarrier * LPG < kLoadsPerStage ? kGroupsBeforeBarrier * LPG : kLoadsPerStage);
+  constexpr int kWaitSteady = NS == 2 ? 0 : (NS - 3) * kLoadsPerStage + kIssuedBeforeBarrier;
+  static_assert(kWaitSteady < 64, "too many loads in flight for the 6-bit vmcnt");
+
+  const int nk = (K + BKT - 1) / BKT;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) {
-        const int x = ((kk + 1) * 2) << 4;
+  for (int s = 0; s < NS - 1; ++s)
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[(kk + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(cur + (a_off[i] ^ x));
+    for (int l = 0; l < kLoadsPerStage; ++l) issue_load(s, lds_addr_of(stage(s)), l);
+  wait_loads_and_barrier<(NS - 2) * kLoadsPerStage>();  // tile 0 has landed for every wave
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-          bfr[(kk + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(cur + (b_off[j] ^ x));
+  for (int i = 0; i < MI; ++i) read_frag_part(stage(0), 0, 0, i);
+
+  for (int kt0 = 0; kt0 < nk; kt0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int kt = kt0 + s;
+      if (kt < nk) {
+        const char* cur = stage(s);
+        const char* nxt = stage((s + 1) % NS);
+        const uint32_t refill = lds_addr_of(stage((s + NS - 1) % NS));  // held tile kt-1: free since the last barrier
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+#pragma unroll
+          for (int i = 0; i < MI; ++i) {
+            const int grp = kk * MI + i;
+            if (kk == KSTEPS - 1 && i == MI / 2) {
+              // tile kt+1 must have landed in every wave's share, and every wave must be done
+              // reading `cur` before the next iteration refills it
+              wait_loads_and_barrier<kWaitSteady>();
+#pragma unroll
+              for (int ii = 0; ii < MI; ++ii) read_frag_part(nxt, 0, 0, ii);
+            }
+#pragma unroll
+            for (int l = 0; l < LPG; ++l)
+              if (grp < kSpread && grp * LPG + l < kLoadsPerStage) issue_load(kt + NS - 1, refill, grp * LPG + l);
+            if (kk + 1 < KSTEPS) read_frag_part(cur, kk + 1, (kk + 1) & 1, i);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(kk & 1, i);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
       }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      la.store(nxt);
-      lb.store(nxt + kABytes);
-    }
-    __syncthreads();
   }
+  wait_loads_and_barrier<0>();  // nothing in flight, all operands consumed: LDS is free
 
   // ---- epilogue -------------------------------------------------------------------------
   // Accumulator register r of lane (l32, half) is C[8*(r/4) + 4*half + r%4][l32] of its 32x32
@@ -266,8 +344,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   constexpr int LPR = TN / 4;                 // lanes per row
   constexpr int RPI = 64 / LPR;               // rows per wave instruction
   constexpr int kSteps = 32 / RPI;
-  static_assert((size_t)NT / 64 * 32 * LDW * 4 <= 2 * (size_t)kStage, "epilogue staging must fit in LDS");
-  float* stage = reinterpret_cast<float*>(lds) + (size_t)wave * 32 * LDW;
+  constexpr int kRegion = 32 * LDW * 4;       // bytes per wave
+  constexpr int kWavesPerStage = kStage / kRegion;
+  static_assert(kWavesPerStage >= 1 && kWavesPerStage * NS >= NT / 64, "epilogue staging must fit in LDS");
+  float* stg = reinterpret_cast<float*>(stage(wave / kWavesPerStage) + (wave % kWavesPerStage) * kRegion);
   const int erow = lane / LPR, ecol = (lane % LPR) * 4;
   const int n = n0 + wn * TN + ecol;
   const bool n_ok = n < N;
@@ -294,13 +374,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        stage[(8 * (r >> 2) + 4 * half + (r & 3)) * LDW + j * 32 + l32] = acc[i][j][r];
+        stg[(8 * (r >> 2) + 4 * half + (r & 3)) * LDW + j * 32 + l32] = acc[i][j][r];
     wave_lds_sync();
 #pragma unroll
     for (int s = 0; s < kSteps; ++s) {
       const int m = mbase + s * RPI + erow;
       if (!(n_ok && m < M)) continue;
-      f32x4 v = *reinterpret_cast<const f32x4*>(stage + (s * RPI + erow) * LDW + ecol);
+      f32x4 v = *reinterpret_cast<const f32x4*>(stg + (s * RPI + erow) * LDW + ecol);
       const size_t idx = (size_t)m * ep.ldc + n;
       v += bias4;
       if (ep.residual) {
@@ -322,32 +402,23 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool AKS, bool BKS>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS>
 hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   constexpr int NT = 64 * WM * WN;
-  constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * kRowBytes;
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, AKS, BKS>;
-  static bool attr_set = false;  // per instantiation; the attribute is per function, set once
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   Operand A{(const bf16*)g.A, g.lda, g.M};
   Operand B{(const bf16*)g.B, g.ldb, g.N};
   Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual};
-  kern<<<tiles, NT, lds_bytes, s>>>(g.M, g.N, g.K, A, B, ep);
+  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS><<<tiles, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int BKT, int NS, int WM, int WN>
 hipError_t launch_layout(const GemmDesc& g, hipStream_t s) {
-  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, WM, WN, false, false>(g, s);
-  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, WM, WN, false, true>(g, s);
-  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, WM, WN, true, true>(g, s);
-  return launch_cfg<BM, BN, WM, WN, true, false>(g, s);
+  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, false>(g, s);
+  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, true>(g, s);
+  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, true, true>(g, s);
+  return launch_cfg<BM, BN, BKT, NS, WM, WN, true, false>(g, s);
 }
 
 int g_variant = 0;
@@ -379,15 +450,17 @@ void set_gemm_variant(int v) { g_variant = v; }
 
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
   switch (g_variant) {
-    case 1: return launch_layout<256, 256, 2, 2>(g, s);
-    case 2: return launch_layout<256, 256, 2, 4>(g, s);
-    case 3: return launch_layout<128, 128, 2, 2>(g, s);
+    case 1: return launch_layout<256, 256, 32, 4, 2, 2>(g, s);
+    case 2: return launch_layout<256, 256, 32, 5, 2, 2>(g, s);
+    case 3: return launch_layout<128, 128, 32, 4, 2, 2>(g, s);
+    case 4: return launch_layout<256, 256, 64, 2, 2, 2>(g, s);
+    case 5: return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
     default: break;
   }
   // Large tiles when they still give every CU work; smaller ones otherwise.
   const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  if (big_tiles >= 192) return launch_layout<256, 256, 2, 2>(g, s);
-  return launch_layout<128, 128, 2, 2>(g, s);
+  if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
+  return launch_layout<128, 128, 32, 4, 2, 2>(g, s);
 }
 
 }  // namespace jpp
