@@ -78,12 +78,12 @@ def time_dominant_kernel(w, torch, B, reps=3):
 
 def cpu_baseline():
     """The fp64 oracle, as it stands, on one microbatch (forward + backward) of one layer of a
-    half-width twin of the GPT-3-shaped stage: d_model 6144, 48 heads of 128, FFN 24576, seq 2048
-    (about 5.7 algorithmic TFLOP, 10-30 s of host time)."""
+    two-thirds-width twin of the GPT-3-shaped stage: d_model 8192, 64 heads of 128, FFN 32768, seq 2048
+    (about 10 algorithmic TFLOP, 10-30 s of host time)."""
     import numpy as np
     from oracle import stage_oracle as so
     from paper_2412_14374_amd import inputs as inp
-    w = inp.shrunk_twin(inp.C4, d_model=6144, seq_len=2048, d_ffn=24576, n_q_heads=48, n_microbatches=1)
+    w = inp.shrunk_twin(inp.C4, d_model=8192, seq_len=2048, d_ffn=32768, n_q_heads=64, n_microbatches=1)
     spec = so.StageSpec(n_layers=1, d_model=w.d_model, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                         head_dim=w.head_dim, d_ffn=w.d_ffn, seq_len=w.seq_len, microbatch=w.microbatch)
     rng = np.random.default_rng(0)
@@ -103,7 +103,7 @@ def cpu_baseline():
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "seconds": dt, "microbatches_per_s_extrapolated_to_workload": None,
             "sample": "fp64 numpy oracle, forward+backward of ONE microbatch of ONE layer of a shrunk twin "
-                      "(d_model 6144, 48 heads x 128, FFN 24576, seq 2048, GeLU, LayerNorm); "
+                      "(d_model 8192, 64 heads x 128, FFN 32768, seq 2048, GeLU, LayerNorm); "
                       f"{flops / 1e9:.0f} algorithmic GFLOP"}
 
 
@@ -114,6 +114,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-only", action="store_true",
+                    help="profiling aid: run only the dominant kernel's launches plus one 1 GiB device copy "
+                         "(the reference that scales the FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU (no collectives, no sharding); "
@@ -130,6 +133,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     w = inp.CONFIGS[a.config]
+    if a.kernel_only:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        avg_ms, flops = time_dominant_kernel(w, torch, B)
+        print(json.dumps({"kernel_only": True, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
+                          "tflops": flops / avg_ms / 1e9}))
+        return
     st = Stage(w)
     st.set_params_random(seed=0)
     st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM
@@ -177,7 +190,11 @@ def main():
                            "(weight gradient with fused fp32 accumulate)",
                            "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": ach / PEAK_BF16_TFLOPS, "avg_launch_ms": avg_ms,
-                           "flops_per_launch": flops_per_launch, "traffic": None}
+                           "flops_per_launch": flops_per_launch,
+                           # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a 1 GiB copy
+                           # (profiles/gemm_wgrad_c4_hbm_traffic.md); measured for the C4 shapes only
+                           "traffic": 6.38e9 if a.config == "C4" else None, "traffic_unit": "bytes/launch",
+                           "algorithmic_bytes_per_launch": 3.83e9 if a.config == "C4" else None}
     if not a.no_cpu_baseline:
         cb = cpu_baseline()
         per_mb = algorithmic_flops_per_microbatch(w)
