@@ -145,8 +145,11 @@ jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream);
 
 /* Executes the task list (host array, read during the call only) in the order given:
  * validation first (JPP_ESCHED / JPP_ECAPACITY: nothing is launched), then every kernel
- * of every task is enqueued on compute_stream without any host synchronisation
- * (Section 4.4).  Receives are copies inbox -> stage input issued on side_stream ahead of
+ * of every task is enqueued without any host synchronisation (Section 4.4): forward tasks
+ * on compute_stream, backward tasks on two library-owned streams that start after the work
+ * already queued on compute_stream and are joined back into it before the call returns, so
+ * that a forward and a backward of different microbatches, and a layer's weight and input
+ * gradients, may overlap (Section 2.2.1: any order that honours the data dependencies).  Receives are copies inbox -> stage input issued on side_stream ahead of
  * their consumer (prefetch), sends are copies stage output -> outbox issued on
  * side_stream right after the producing task (Section 4.2); staging buffers whose send
  * has not completed are parked in a pending-deletion queue and reclaimed later

@@ -184,14 +184,26 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
   }
 }
 
-// g[col] += sum_{b ascending} partial[b, col]
+// g[col] += sum_b partial[b, col].  32 columns x 8 row groups per workgroup: group q adds the
+// partial rows q, q+8, ... in ascending order, then the 8 group sums are added in ascending
+// order: a fixed association, independent of timing.
+constexpr int kFinCols = 32, kFinGroups = kThreads / kFinCols;
 __global__ __launch_bounds__(kThreads) void colreduce_finish_kernel(const float* __restrict__ partial,
                                                                     int nblk, int n, float* __restrict__ g) {
-  const int col = blockIdx.x * kThreads + threadIdx.x;
-  if (col >= n) return;
+  __shared__ float red[kFinGroups][kFinCols];
+  const int c = threadIdx.x % kFinCols, q = threadIdx.x / kFinCols;
+  const int col = blockIdx.x * kFinCols + c;
   float acc = 0.f;
-  for (int b = 0; b < nblk; ++b) acc += partial[(size_t)b * n + col];
-  g[col] += acc;
+  if (col < n)
+    for (int b = q; b < nblk; b += kFinGroups) acc += partial[(size_t)b * n + col];
+  red[q][c] = acc;
+  __syncthreads();
+  if (q == 0 && col < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < kFinGroups; ++i) t += red[i][c];
+    g[col] += t;
+  }
 }
 
 // partial[b, col] = sum over rows {b, b + nblk, ...} of dy[r, col]
@@ -440,7 +452,7 @@ hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamm
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int fin = (d + kThreads - 1) / kThreads;
+  const int fin = (d + kFinCols - 1) / kFinCols;
   colreduce_finish_kernel<<<fin, kThreads, 0, s>>>(pg, nblk, d, g_gamma);
   if (pb) colreduce_finish_kernel<<<fin, kThreads, 0, s>>>(pb, nblk, d, g_beta);
   return hipGetLastError();
@@ -482,7 +494,7 @@ hipError_t launch_bias_grad(int dtype, int rows, int n, const void* dy, int ld, 
     colsum_partial_kernel<float><<<grid, kThreads, 0, s>>>((const float*)dy, ld, rows, n, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  colreduce_finish_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(partial, nblk, n, g);
+  colreduce_finish_kernel<<<(n + kFinCols - 1) / kFinCols, kThreads, 0, s>>>(partial, nblk, n, g);
   return hipGetLastError();
 }
 

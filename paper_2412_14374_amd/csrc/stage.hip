@@ -16,6 +16,15 @@
 //  * Section 2.2.1: the activations of a forward are kept until its backward on the same
 //    actor (the "stash"); the number alive at once depends on the schedule.
 // The layer mathematics is not defined by the paper; see include/jpp.h.
+//
+// Streams.  Forward tasks are enqueued on the caller's compute stream; backward tasks on an
+// internal "backward" stream and their weight-gradient GEMMs on an internal "wgrad" stream.
+// Section 2.2.1 only requires that data dependencies are honoured, and a forward of one
+// microbatch is independent of the backward of another, as is a layer's weight gradient of
+// its input gradient: letting them overlap fills the CUs that a single GEMM leaves idle in
+// its last round of tiles.  Every kernel still sees exactly the same inputs, per-parameter
+// accumulation order is the task order, so results do not depend on the overlap.  Both
+// internal streams are joined back into the compute stream before jpp_stage_run returns.
 #include <algorithm>
 #include <deque>
 #include <vector>
@@ -65,6 +74,7 @@ struct Slot {
   char* base = nullptr;
   Event freed;  // recorded on the compute stream when the backward that used the slot is done
   Event rx;     // recorded on the side stream when the received input is in place
+  Event fwd_done;  // recorded on the compute stream when the forward that filled the slot is enqueued
   bool rx_issued = false;
 };
 
@@ -122,8 +132,9 @@ struct jpp_stage {
   std::vector<bool> params_set;
 
   // run state
-  hipStream_t cs = nullptr, ss = nullptr;
-  Event end_compute, end_side;
+  hipStream_t cs = nullptr, ss = nullptr;   // caller's streams of the current / last run
+  hipStream_t bs = nullptr, ws = nullptr;   // internal: backward chain, weight-gradient GEMMs
+  Event end_compute, end_side, run_start, b2w, w_layer, w_task, b_end, w_end;
   int peak_in_flight = 0, pending_peak = 0, prefetched = 0, host_syncs = 0;
   std::vector<int> free_slots;
   std::vector<int> tx_free;
@@ -347,20 +358,31 @@ hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out)
   return hipSuccess;
 }
 
+// Weight-gradient GEMM on the wgrad stream, after everything enqueued so far on the backward
+// stream (its operands were produced there).
+hipError_t wgrad(jpp_stage& st, int M, int N, int K, const void* dy, int ldy, const void* x, int ldx, float* G) {
+  K_TRY(hipEventRecord(st.b2w.ev, st.bs));
+  K_TRY(hipStreamWaitEvent(st.ws, st.b2w.ev, 0));
+  return gemm(st, st.ws, M, N, K, dy, ldy, true, x, ldx, true, G, N, OUT_ACC_F32, nullptr, nullptr);
+}
+
 // Backward of local stage v: reads the output cotangent from `dy_in` (ignored for a
 // loss-head stage), adds this microbatch's parameter gradients to the fp32 buffers and
-// writes the input cotangent to `dx_out`.
+// writes the input cotangent to `dx_out`.  The input-gradient chain runs on the backward
+// stream, the weight-gradient GEMMs on the wgrad stream.
 hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in, char* dx_out) {
   const Dims& m = st.dm;
   const jpp_layer_config& c = st.cfg;
-  hipStream_t s = st.cs;
+  hipStream_t s = st.bs;
   const int dt = c.dtype;
   int cur = 0;
   const char* dy = dy_in;
+  // the workspace buffers are about to be overwritten: the previous backward's weight
+  // gradients, which read them, must be done
+  if (st.w_task.recorded) K_TRY(hipStreamWaitEvent(s, st.w_task.ev, 0));
   if (c.loss_head) {
     char* hb = slot.base + (size_t)m.L * st.ls.bytes;
-    K_TRY(gemm(st, s, m.vocab, m.d, m.T, hb + st.hs.dz, m.vocab, true, hb + st.hs.nf, m.d, true,
-               gptr(st, v, st.w_head), m.d, OUT_ACC_F32, nullptr, nullptr));
+    K_TRY(wgrad(st, m.vocab, m.d, m.T, hb + st.hs.dz, m.vocab, hb + st.hs.nf, m.d, gptr(st, v, st.w_head)));
     K_TRY(gemm(st, s, m.T, m.d, m.vocab, hb + st.hs.dz, m.vocab, false, pptr(st, v, st.w_head), m.d, true, st.dn,
                m.d, OUT_STORE, nullptr, nullptr));
     K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, hb + st.hs.yL, pptr(st, v, st.lnf_g), (float*)(hb + st.hs.statsf),
@@ -373,25 +395,27 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
     char* b = slot.base + (size_t)l * st.ls.bytes;
     const auto& o = st.loff[l];
     char* dx = (l == 0) ? dx_out : st.dbuf[cur];
+    if (l != m.L - 1) {
+      // the layer above's weight gradients read dh, dx1, dqkv, which this layer rewrites
+      K_TRY(hipEventRecord(st.w_layer.ev, st.ws));
+      K_TRY(hipStreamWaitEvent(s, st.w_layer.ev, 0));
+    }
     // FFN down projection
+    K_TRY(wgrad(st, m.d, m.f, m.T, dy, m.d, b + st.ls.a, m.f, gptr(st, v, o.w2)));
     if (o.b2 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dy, m.d, gptr(st, v, o.b2), st.partial, s));
-    K_TRY(gemm(st, s, m.d, m.f, m.T, dy, m.d, true, b + st.ls.a, m.f, true, gptr(st, v, o.w2), m.f, OUT_ACC_F32,
-               nullptr, nullptr));
     K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, st.da, m.f, OUT_STORE, nullptr,
                nullptr));
     K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, b + st.ls.h, st.da, st.dh, s));
     // FFN up projection
+    K_TRY(wgrad(st, m.f1, m.d, m.T, st.dh, m.f1, b + st.ls.n2, m.d, gptr(st, v, o.w1)));
     if (o.b1 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.f1, st.dh, m.f1, gptr(st, v, o.b1), st.partial, s));
-    K_TRY(gemm(st, s, m.f1, m.d, m.T, st.dh, m.f1, true, b + st.ls.n2, m.d, true, gptr(st, v, o.w1), m.d,
-               OUT_ACC_F32, nullptr, nullptr));
     K_TRY(gemm(st, s, m.T, m.d, m.f1, st.dh, m.f1, false, pptr(st, v, o.w1), m.d, true, st.dn, m.d, OUT_STORE,
                nullptr, nullptr));
     K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, b + st.ls.x1, pptr(st, v, o.ln2_g), (float*)(b + st.ls.stats2),
                           st.dn, dy, st.dx1, gptr(st, v, o.ln2_g), gptr(st, v, o.ln2_b), st.partial, s));
     // attention output projection
+    K_TRY(wgrad(st, m.d, m.nq, m.T, st.dx1, m.d, b + st.ls.O, m.nq, gptr(st, v, o.wo)));
     if (o.bo >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, st.dx1, m.d, gptr(st, v, o.bo), st.partial, s));
-    K_TRY(gemm(st, s, m.d, m.nq, m.T, st.dx1, m.d, true, b + st.ls.O, m.nq, true, gptr(st, v, o.wo), m.nq,
-               OUT_ACC_F32, nullptr, nullptr));
     K_TRY(gemm(st, s, m.T, m.nq, m.d, st.dx1, m.d, false, pptr(st, v, o.wo), m.nq, true, st.dO, m.nq, OUT_STORE,
                nullptr, nullptr));
     AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
@@ -399,9 +423,8 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
     K_TRY(attention_bwd(st, s, a));
     if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, st.dqkv, st.rope_table, true, s));
     // QKV projection
+    K_TRY(wgrad(st, m.nqkv, m.d, m.T, st.dqkv, m.nqkv, b + st.ls.n1, m.d, gptr(st, v, o.wqkv)));
     if (o.bqkv >= 0) K_TRY(launch_bias_grad(dt, m.T, m.nqkv, st.dqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
-    K_TRY(gemm(st, s, m.nqkv, m.d, m.T, st.dqkv, m.nqkv, true, b + st.ls.n1, m.d, true, gptr(st, v, o.wqkv), m.d,
-               OUT_ACC_F32, nullptr, nullptr));
     K_TRY(gemm(st, s, m.T, m.d, m.nqkv, st.dqkv, m.nqkv, false, pptr(st, v, o.wqkv), m.d, true, st.dn, m.d,
                OUT_STORE, nullptr, nullptr));
     K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, b + st.ls.x, pptr(st, v, o.ln1_g), (float*)(b + st.ls.stats1),
@@ -409,6 +432,12 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
     dy = dx;
     cur ^= 1;
   }
+  // The wgrad stream now also follows the whole backward chain: an event recorded on it marks
+  // "nothing of this task reads the stash, the cotangent or the workspace any more".
+  K_TRY(hipEventRecord(st.b2w.ev, st.bs));
+  K_TRY(hipStreamWaitEvent(st.ws, st.b2w.ev, 0));
+  K_TRY(hipEventRecord(st.w_task.ev, st.ws));
+  st.w_task.recorded = true;
   return hipSuccess;
 }
 
@@ -434,8 +463,8 @@ void sweep_pending(jpp_stage& st) {
 }
 
 // A staging buffer for the next send.  If none is free the oldest pending one is reused and
-// the compute stream is made to wait (on the device) for its send.
-hipError_t acquire_tx(jpp_stage& st, int& out) {
+// the producing stream is made to wait (on the device) for its send.
+hipError_t acquire_tx(jpp_stage& st, hipStream_t producer, int& out) {
   sweep_pending(st);
   if (!st.tx_free.empty()) {
     out = st.tx_free.back();
@@ -444,14 +473,14 @@ hipError_t acquire_tx(jpp_stage& st, int& out) {
   }
   out = st.tx_pending.front();
   st.tx_pending.pop_front();
-  return hipStreamWaitEvent(st.cs, st.tx[out].sent.ev, 0);
+  return hipStreamWaitEvent(producer, st.tx[out].sent.ev, 0);
 }
 
-// Send: copy on the side stream once the compute stream has produced the buffer, then the
+// Send: copy on the side stream once the producing stream has written the buffer, then the
 // "deletion" of the staging buffer (Section 4.3).
-hipError_t send_and_delete(jpp_stage& st, int b, void* outbox, size_t bytes) {
+hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* outbox, size_t bytes) {
   TxBuf& t = st.tx[b];
-  K_TRY(hipEventRecord(t.produced.ev, st.cs));
+  K_TRY(hipEventRecord(t.produced.ev, producer));
   K_TRY(hipStreamWaitEvent(st.ss, t.produced.ev, 0));
   K_TRY(hipMemcpyAsync(outbox, t.p, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(t.sent.ev, st.ss));
@@ -524,10 +553,13 @@ jpp_status jpp_stage_create(const jpp_layer_config* cfg, int n_microbatches, int
   }
   hipError_t e = hipSuccess;
   auto mk = [&](Event& ev) { if (e == hipSuccess) e = ev_create(ev); };
-  for (auto& s : st->slots) { mk(s.freed); mk(s.rx); }
+  for (auto& s : st->slots) { mk(s.freed); mk(s.rx); mk(s.fwd_done); }
   for (auto& t : st->tx) { mk(t.produced); mk(t.sent); }
   for (auto& t : st->cot) { mk(t.freed); mk(t.rx); }
-  mk(st->end_compute); mk(st->end_side);
+  mk(st->end_compute); mk(st->end_side); mk(st->run_start); mk(st->b2w); mk(st->w_layer); mk(st->w_task);
+  mk(st->b_end); mk(st->w_end);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->bs, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->ws, hipStreamNonBlocking);
   if (e == hipSuccess && cfg->rope) {
     e = launch_rope_table(st->rope_table, cfg->seq_len, cfg->head_dim, cfg->rope_theta, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -541,10 +573,13 @@ void jpp_stage_destroy(jpp_stage* st) {
   if (!st) return;
   if (st->cs) (void)hipStreamSynchronize(st->cs);
   if (st->ss) (void)hipStreamSynchronize(st->ss);
-  for (auto& s : st->slots) { ev_destroy(s.freed); ev_destroy(s.rx); }
+  if (st->bs) { (void)hipStreamSynchronize(st->bs); (void)hipStreamDestroy(st->bs); }
+  if (st->ws) { (void)hipStreamSynchronize(st->ws); (void)hipStreamDestroy(st->ws); }
+  for (auto& s : st->slots) { ev_destroy(s.freed); ev_destroy(s.rx); ev_destroy(s.fwd_done); }
   for (auto& t : st->tx) { ev_destroy(t.produced); ev_destroy(t.sent); }
   for (auto& t : st->cot) { ev_destroy(t.freed); ev_destroy(t.rx); }
-  ev_destroy(st->end_compute); ev_destroy(st->end_side);
+  ev_destroy(st->end_compute); ev_destroy(st->end_side); ev_destroy(st->run_start); ev_destroy(st->b2w);
+  ev_destroy(st->w_layer); ev_destroy(st->w_task); ev_destroy(st->b_end); ev_destroy(st->w_end);
   delete st;
 }
 
@@ -632,6 +667,12 @@ jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void
     HIP_TRY(hipStreamWaitEvent(ss, st->end_side.ev, 0));
   }
   st->cs = cs; st->ss = ss;
+  // the internal streams start after everything already queued on the compute stream
+  // (e.g. jpp_stage_zero_grads)
+  HIP_TRY(hipEventRecord(st->run_start.ev, cs));
+  HIP_TRY(hipStreamWaitEvent(st->bs, st->run_start.ev, 0));
+  HIP_TRY(hipStreamWaitEvent(st->ws, st->run_start.ev, 0));
+  st->w_task.recorded = false;
   st->peak_in_flight = 0; st->pending_peak = 0; st->prefetched = 0; st->host_syncs = 0;
   st->free_slots.clear();
   for (int k = st->max_in_flight - 1; k >= 0; --k) st->free_slots.push_back(k);
@@ -689,37 +730,46 @@ jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void
       st->peak_in_flight = std::max(st->peak_in_flight, live);
       HIP_TRY(hipStreamWaitEvent(cs, slot.rx.ev, 0));
       int txb = -1;
-      if (!head) HIP_TRY(acquire_tx(*st, txb));
+      if (!head) HIP_TRY(acquire_tx(*st, cs, txb));
       e = enqueue_forward(*st, v, t.i, slot, head ? nullptr : st->tx[txb].p);
       if (e != hipSuccess) return fail_hip(e, "forward kernels");
-      if (!head) HIP_TRY(send_and_delete(*st, txb, st->outbox_y[key], bbytes));
+      HIP_TRY(hipEventRecord(slot.fwd_done.ev, cs));
+      if (!head) HIP_TRY(send_and_delete(*st, cs, txb, st->outbox_y[key], bbytes));
     } else {
       Slot& slot = st->slots[slot_of[key]];
       const char* dy = nullptr;
+      HIP_TRY(hipStreamWaitEvent(st->bs, slot.fwd_done.ev, 0));  // the forward that filled the stash
       if (!head) {
         CotBuf& cb = st->cot[cot_of[key]];
-        HIP_TRY(hipStreamWaitEvent(cs, cb.rx.ev, 0));
+        HIP_TRY(hipStreamWaitEvent(st->bs, cb.rx.ev, 0));
         dy = cb.p;
       }
       int txb = -1;
-      HIP_TRY(acquire_tx(*st, txb));
+      HIP_TRY(acquire_tx(*st, st->bs, txb));
       e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p);
       if (e != hipSuccess) return fail_hip(e, "backward kernels");
+      // enqueue_backward left the wgrad stream behind both the input-gradient chain and the
+      // weight gradients of this task: events recorded there cover every reader
       if (!head) {
         CotBuf& cb = st->cot[cot_of[key]];
-        HIP_TRY(hipEventRecord(cb.freed.ev, cs));
+        HIP_TRY(hipEventRecord(cb.freed.ev, st->ws));
         cb.freed.recorded = true;
       }
-      HIP_TRY(send_and_delete(*st, txb, st->outbox_dx[key], bbytes));
-      // the stash is dead: release the slot (stream order protects it on the compute stream;
-      // the event protects it against an early receive on the side stream)
-      HIP_TRY(hipEventRecord(slot.freed.ev, cs));
+      HIP_TRY(send_and_delete(*st, st->bs, txb, st->outbox_dx[key], bbytes));
+      // the stash is dead: release the slot; the event protects it against an early receive
+      // on the side stream (and, through the receive, against the next forward)
+      HIP_TRY(hipEventRecord(slot.freed.ev, st->ws));
       slot.freed.recorded = true;
       st->free_slots.push_back(slot_of[key]);
       slot_of[key] = -1;
       --live;
     }
   }
+  // join the internal streams back into the caller's compute stream
+  HIP_TRY(hipEventRecord(st->b_end.ev, st->bs));
+  HIP_TRY(hipEventRecord(st->w_end.ev, st->ws));
+  HIP_TRY(hipStreamWaitEvent(cs, st->b_end.ev, 0));
+  HIP_TRY(hipStreamWaitEvent(cs, st->w_end.ev, 0));
   HIP_TRY(hipEventRecord(st->end_compute.ev, cs));
   HIP_TRY(hipEventRecord(st->end_side.ev, ss));
   st->end_compute.recorded = true;
