@@ -69,6 +69,11 @@ __device__ inline i32x4 make_rsrc(const void* p, long long bytes) {
   return r;
 }
 
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc_v(const void* p, long long bytes) {
+  const uint32_t n = bytes > (long long)kMaxRecords ? kMaxRecords : (bytes < 0 ? 0u : (uint32_t)bytes);
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)n, 0x00020000);
+}
+
 // 16 bytes per lane, HBM -> LDS without passing through registers: the wave's 64 lanes fill
 // the 1 KiB at LDS byte address `lds_addr` in lane order; lanes whose byte offset `voff` is
 // outside the descriptor's range store zeros.  Issued as inline assembly on purpose: the
@@ -119,6 +124,21 @@ struct KContigTile {
     const uint32_t off = (k0 + kc * 8 < K) ? (uint32_t)(row * op.ld + kc * 8) * 2u : kOOB;
     dma16(rs, tile + blk * 1024, off);
   }
+  // Register-staged variant: chunk i*NT + tid of the tile; 8 consecutive lanes read one
+  // 128-byte row segment, the swizzle is applied when the chunk is written to LDS.
+  __device__ static inline u32x4 load_one(const Operand& op, int r0, int k0, int K, int i) {
+    const int cidx = i * NT + threadIdx.x;
+    const int row = cidx / CPR, c = cidx % CPR;
+    const bf16* base = op.p + (size_t)r0 * op.ld + k0;
+    const auto rs = make_rsrc_v(base, ((long long)(op.rows - r0) * op.ld - k0) * 2);
+    const uint32_t off = (k0 + c * 8 < K) ? (uint32_t)(row * op.ld + c * 8) * 2u : kOOB;
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+  }
+  __device__ static inline void store_one(char* tile, int i, const u32x4& v) {
+    const int cidx = i * NT + threadIdx.x;
+    const int row = cidx / CPR, c = cidx % CPR;
+    *reinterpret_cast<u32x4*>(tile + row * kRowBytes + ((c ^ swz(row)) << 4)) = v;
+  }
   // byte offset of the kk = 0 fragment of the 32-row block starting at `row0`
   __device__ static inline int frag_base(int row0, int l32, int half) {
     const int row = row0 + l32;
@@ -149,6 +169,19 @@ struct KStridedTile {
     const int c = (lane % CPR) ^ ((k & 3) << 1);
     const uint32_t off = (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
     dma16(rs, tile + blk * 1024, off);
+  }
+  __device__ static inline u32x4 load_one(const Operand& op, int r0, int k0, int K, int i) {
+    const int cidx = i * NT + threadIdx.x;
+    const int k = cidx / CPR, c = cidx % CPR;
+    const bf16* base = op.p + (size_t)k0 * op.ld + r0;
+    const auto rs = make_rsrc_v(base, ((long long)(K - k0) * op.ld - r0) * 2);
+    const uint32_t off = (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+  }
+  __device__ static inline void store_one(char* tile, int i, const u32x4& v) {
+    const int cidx = i * NT + threadIdx.x;
+    const int k = cidx / CPR, c = cidx % CPR;
+    *reinterpret_cast<u32x4*>(tile + k * kRowBytes + ((c ^ ((k & 3) << 1)) << 4)) = v;
   }
   // Lane l of a 16-lane group addresses the 8-byte row (k = .. + (l>>2), rows 4*(l&3) .. +3)
   // and receives k = .. + 0..3 for row (l & 15) of the group's 16 rows.
@@ -206,7 +239,7 @@ __device__ inline void wait_loads_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, int K, Operand A, Operand B,
                                                                   Epilogue ep) {
   constexpr int NT = 64 * WM * WN;
@@ -294,6 +327,69 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   static_assert(kWaitSteady < 64, "too many loads in flight for the 6-bit vmcnt");
 
   const int nk = (K + BKT - 1) / BKT;
+  if constexpr (VG) {
+    // Register-staged loads (two LDS stages): tile kt+2 travels in registers while tile kt is
+    // multiplied; at the start of iteration kt the registers (tile kt+1, loaded one iteration
+    // ago) are written to the free stage and immediately reloaded, one chunk per MFMA group.
+    static_assert(NS == 2, "register staging uses two LDS stages");
+    constexpr int L = kLoadsPerStage;
+    constexpr int kGroupsV = KSTEPS * MI;
+    constexpr int kBefore = (KSTEPS - 1) * MI + MI / 2;      // groups before the barrier
+    constexpr int PG = (L + kBefore - 1) / kBefore;           // chunks handled per group
+    u32x4 regs[L];
+    auto vload = [&](int kt, int idx) {
+      regs[idx] = idx < TA::kLoads ? TA::load_one(A, m0, kt * BKT, K, idx)
+                                   : TB::load_one(B, n0, kt * BKT, K, idx - TA::kLoads);
+    };
+    auto vstore = [&](char* dst, int idx) {
+      if (idx < TA::kLoads) TA::store_one(dst, idx, regs[idx]);
+      else TB::store_one(dst + kABytes, idx - TA::kLoads, regs[idx]);
+    };
+#pragma unroll
+    for (int l = 0; l < L; ++l) vload(0, l);
+#pragma unroll
+    for (int l = 0; l < L; ++l) vstore(stage(0), l);
+    __syncthreads();
+#pragma unroll
+    for (int l = 0; l < L; ++l) vload(1, l);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) read_frag_part(stage(0), 0, 0, i);
+    for (int kt0 = 0; kt0 < nk; kt0 += 2) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        const int kt = kt0 + s;
+        if (kt < nk) {
+          const char* cur = stage(s);
+          char* nxt = stage(s ^ 1);
+#pragma unroll
+          for (int kk = 0; kk < KSTEPS; ++kk) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+              const int grp = kk * MI + i;
+              if (kk == KSTEPS - 1 && i == MI / 2) {
+                __syncthreads();  // tile kt+1 is complete in `nxt`; nobody reads `cur` any more
+#pragma unroll
+                for (int ii = 0; ii < MI; ++ii) read_frag_part(nxt, 0, 0, ii);
+              }
+#pragma unroll
+              for (int l = 0; l < PG; ++l) {
+                const int idx = grp * PG + l;
+                if (grp < kBefore && idx < L) {
+                  vstore(nxt, idx);
+                  vload(kt + 2, idx);
+                }
+              }
+              if (kk + 1 < KSTEPS) read_frag_part(cur, kk + 1, (kk + 1) & 1, i);
+              __builtin_amdgcn_sched_barrier(0);
+              mfma_row(kk & 1, i);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+      }
+    }
+    (void)kGroupsV;
+  } else {
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
 #pragma unroll
@@ -333,6 +429,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
         }
       }
     }
+  }
   }
   wait_loads_and_barrier<0>();  // nothing in flight, all operands consumed: LDS is free
 
@@ -402,23 +499,23 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   }
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false>
 hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   constexpr int NT = 64 * WM * WN;
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   Operand A{(const bf16*)g.A, g.lda, g.M};
   Operand B{(const bf16*)g.B, g.ldb, g.N};
   Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual};
-  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS><<<tiles, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
+  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG><<<tiles, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool VG = false>
 hipError_t launch_layout(const GemmDesc& g, hipStream_t s) {
-  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, false>(g, s);
-  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, true>(g, s);
-  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, true, true>(g, s);
-  return launch_cfg<BM, BN, BKT, NS, WM, WN, true, false>(g, s);
+  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, false, VG>(g, s);
+  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, true, VG>(g, s);
+  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, true, true, VG>(g, s);
+  return launch_cfg<BM, BN, BKT, NS, WM, WN, true, false, VG>(g, s);
 }
 
 int g_variant = 0;
@@ -455,11 +552,13 @@ hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
     case 3: return launch_layout<128, 128, 32, 4, 2, 2>(g, s);
     case 4: return launch_layout<256, 256, 64, 2, 2, 2>(g, s);
     case 5: return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
+    case 6: return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
+    case 7: return launch_layout<256, 256, 64, 2, 2, 2, true>(g, s);
     default: break;
   }
   // Large tiles when they still give every CU work; smaller ones otherwise.
   const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
+  if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
   return launch_layout<128, 128, 32, 4, 2, 2>(g, s);
 }
 
