@@ -127,7 +127,7 @@ __device__ inline bf16x8 acc_frag(const f32x16& a, int s2) {
 
 // ---- forward -------------------------------------------------------------------------------
 // One workgroup: 128 queries of one (b, h); wave w owns queries [32w, 32w+32).  KV tiles of 64.
-__global__ __launch_bounds__(kThreads) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
+__global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
                                                                  bf16* __restrict__ out,
                                                                  float* __restrict__ lse, int seq, int Hq,
                                                                  int Hkv, long long total_bytes) {
@@ -386,7 +386,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
 // One workgroup: 128 queries of one (b, h); wave w owns queries [32w, 32w+32).  KV tiles of 64:
 //   S^T = K Q^T, dP^T = V dO^T (A = K / V row tiles from LDS, B = Q / dO fragments in registers)
 //   dS^T = P^T (dP^T - D);  dQ^T += K^T dS^T (A = transposed K tile)
-__global__ __launch_bounds__(kThreads) void attn_bwd_dq_mfma_kernel(
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
     const bf16* __restrict__ qkv, const bf16* __restrict__ dout, const float* __restrict__ lse,
     const float* __restrict__ delta, bf16* __restrict__ dqkv, int seq, int Hq, int Hkv, long long qkv_bytes) {
   __shared__ __attribute__((aligned(1024))) char lds[3 * kTileBytes];
