@@ -554,12 +554,13 @@ hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
     case 5: return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
     case 6: return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
     case 7: return launch_layout<256, 256, 64, 2, 2, 2, true>(g, s);
+    case 8: return launch_layout<128, 128, 64, 2, 2, 2, true>(g, s);
     default: break;
   }
   // Large tiles when they still give every CU work; smaller ones otherwise.
   const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
-  return launch_layout<128, 128, 32, 4, 2, 2>(g, s);
+  return launch_layout<128, 128, 64, 2, 2, 2, true>(g, s);
 }
 
 }  // namespace jpp

@@ -73,6 +73,45 @@ def test_gemm_bf16_all_layouts_and_epilogues(M, N, K, aks, bks):
     assert rel_l2(host(Cb), ref + bias[None, :] + res) < 4e-3  # one bf16 rounding of the result
 
 
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("aks,bks", [(0, 0), (0, 1), (1, 1), (1, 0)])
+def test_gemm_bf16_every_tile_configuration_gives_the_same_bits(variant, aks, bks):
+    """The automatic choice depends on the shape, so each configuration is forced in turn on
+    shapes with ragged tails in every dimension: all three output modes must match the
+    definition and agree bit for bit with the automatic choice (same k order per element)."""
+    rng = np.random.default_rng(100 + aks * 2 + bks)
+    for (M, N, K) in [(264, 520, 328), (776, 136, 72)]:
+        A = inp.round_to_dtype(rng.standard_normal((M, K)), inp.DT_BF16)
+        Bm = inp.round_to_dtype(rng.standard_normal((N, K)), inp.DT_BF16)
+        bias = inp.round_to_dtype(rng.standard_normal(N), inp.DT_BF16)
+        res = inp.round_to_dtype(rng.standard_normal((M, N)), inp.DT_BF16)
+        At = dev(A.T if aks else A, torch.bfloat16)
+        Bt = dev(Bm.T if bks else Bm, torch.bfloat16)
+        bt, rt = dev(bias, torch.bfloat16), dev(res, torch.bfloat16)
+        lda, ldb = (M if aks else K), (N if bks else K)
+        out = {}
+        try:
+            for v in (0, variant):
+                B.jpp_set_gemm_variant(v)
+                Cb = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+                Cf = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+                Ca = torch.ones((M, N), dtype=torch.float32, device=DEV)
+                a = (B.JPP_BF16, M, N, K, At.data_ptr(), lda, aks, Bt.data_ptr(), ldb, bks)
+                B.jpp_op_gemm(*a, Cb.data_ptr(), N, B.OUT_STORE, bt.data_ptr(), rt.data_ptr(), stream())
+                B.jpp_op_gemm(*a, Cf.data_ptr(), N, B.OUT_STORE_F32, None, None, stream())
+                B.jpp_op_gemm(*a, Ca.data_ptr(), N, B.OUT_ACC_F32, None, None, stream())
+                torch.cuda.synchronize()
+                out[v] = (Cb, Cf, Ca)
+        finally:
+            B.jpp_set_gemm_variant(0)
+        ref = A @ Bm.T
+        assert rel_l2(host(out[variant][1]), ref) < 1e-5
+        assert rel_l2(host(out[variant][2]), 1.0 + ref) < 1e-5
+        assert rel_l2(host(out[variant][0]), ref + bias[None, :] + res) < 4e-3
+        for got, auto in zip(out[variant], out[0]):
+            assert torch.equal(got, auto)
+
+
 def test_gemm_bf16_padded_leading_dimensions_do_not_touch_neighbours():
     """Sub-matrix views: ld > row length.  The cells outside C's view must stay untouched."""
     rng = np.random.default_rng(0)
