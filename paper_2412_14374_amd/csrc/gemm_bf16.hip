@@ -335,7 +335,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
     constexpr int L = kLoadsPerStage;
     constexpr int kGroupsV = KSTEPS * MI;
     constexpr int kBefore = (KSTEPS - 1) * MI + MI / 2;      // groups before the barrier
-    constexpr int PG = (L + kBefore - 1) / kBefore;           // chunks handled per group
     u32x4 regs[L];
     auto vload = [&](int kt, int idx) {
       regs[idx] = idx < TA::kLoads ? TA::load_one(A, m0, kt * BKT, K, idx)
@@ -372,9 +371,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
                 for (int ii = 0; ii < MI; ++ii) read_frag_part(nxt, 0, 0, ii);
               }
 #pragma unroll
-              for (int l = 0; l < PG; ++l) {
-                const int idx = grp * PG + l;
-                if (grp < kBefore && idx < L) {
+              for (int idx = 0; idx < L; ++idx) {
+                if (idx * kBefore / L == grp) {   // chunks spread evenly over the groups before the barrier
                   vstore(nxt, idx);
                   vload(kt + 2, idx);
                 }
