@@ -193,7 +193,7 @@ def main():
                            "flops_per_launch": flops_per_launch,
                            # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a 1 GiB copy
                            # (profiles/gemm_wgrad_c4_hbm_traffic.md); measured for the C4 shapes only
-                           "traffic": 6.38e9 if a.config == "C4" else None, "traffic_unit": "bytes/launch",
+                           "traffic": 6.65e9 if a.config == "C4" else None, "traffic_unit": "bytes/launch",
                            "algorithmic_bytes_per_launch": 3.83e9 if a.config == "C4" else None}
     if not a.no_cpu_baseline:
         cb = cpu_baseline()
