@@ -318,3 +318,47 @@ def test_gemm_full_shape_sampled_entries(name, M, N, K, aks, bks, mode):
     tol = 4e-3 if mode == B.OUT_STORE else 1e-5
     assert rel_l2(got, ref) < tol, name
     assert np.all(np.isfinite(got))
+
+
+FULL_ATTENTION = [
+    # name, mb, seq, Hq, Hkv, sampled kv heads (with their whole query groups)
+    ("C4 layer", 1, 2048, 96, 96, [0, 50, 95]),
+    ("C3 layer", 1, 4096, 64, 8, [5]),
+    ("C5 layer", 2, 2048, 32, 32, [31]),
+]
+
+
+@pytest.mark.parametrize("name,mb,seq,Hq,Hkv,kv_heads", FULL_ATTENTION)
+def test_attention_full_shape_sampled_heads(name, mb, seq, Hq, Hkv, kv_heads):
+    """The benchmark's attention shapes: the kernels run on every head; the float64 definition is
+    evaluated for a few kv heads together with all query heads that read them."""
+    hd, grp = 128, Hq // Hkv
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seq + Hq)
+    T, nq, nkv = mb * seq, Hq * hd, Hkv * hd
+    tq = torch.randn((T, nq + 2 * nkv), generator=g, device=DEV).to(torch.bfloat16)
+    tdo = torch.randn((T, nq), generator=g, device=DEV).to(torch.bfloat16)
+    out = torch.zeros((T, nq), dtype=torch.bfloat16, device=DEV)
+    lse = torch.zeros((mb, Hq, seq), dtype=torch.float32, device=DEV)
+    dqkv = torch.zeros_like(tq)
+    delta = torch.zeros((mb, Hq, seq), dtype=torch.float32, device=DEV)
+    B.jpp_op_attention_fwd(inp.DT_BF16, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(), stream())
+    B.jpp_op_attention_bwd(inp.DT_BF16, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                           tdo.data_ptr(), dqkv.data_ptr(), delta.data_ptr(), stream())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all()) and bool(torch.isfinite(dqkv.float()).all())
+    for kv in kv_heads:
+        qcols = slice(kv * grp * hd, (kv + 1) * grp * hd)
+        kcols = slice(nq + kv * hd, nq + (kv + 1) * hd)
+        vcols = slice(nq + nkv + kv * hd, nq + nkv + (kv + 1) * hd)
+        spec = so.StageSpec(n_layers=1, d_model=grp * hd, n_q_heads=grp, n_kv_heads=1, head_dim=hd, d_ffn=8,
+                            seq_len=seq, microbatch=mb)
+        q = host(tq[:, qcols]).reshape(mb, seq, grp, hd)
+        k = host(tq[:, kcols]).reshape(mb, seq, 1, hd)
+        v = host(tq[:, vcols]).reshape(mb, seq, 1, hd)
+        O, P = so.attention_forward(spec, q, k, v)
+        dq, dk, dv = so.attention_backward(spec, q, k, v, P, host(tdo[:, qcols]).reshape(mb, seq, grp, hd))
+        assert rel_l2(host(out[:, qcols]), O.reshape(T, grp * hd)) < 1e-2, (name, kv)
+        assert rel_l2(host(dqkv[:, qcols]), dq.reshape(T, grp * hd)) < 1e-2, (name, kv)
+        assert rel_l2(host(dqkv[:, kcols]), dk.reshape(T, hd)) < 1e-2, (name, kv)
+        assert rel_l2(host(dqkv[:, vcols]), dv.reshape(T, hd)) < 1e-2, (name, kv)

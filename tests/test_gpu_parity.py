@@ -186,6 +186,45 @@ def test_gradients_bit_identical_across_schedules_and_runs():
     st.close()
 
 
+def test_full_size_c4_stage_is_schedule_invariant_and_sums_over_microbatches():
+    """The benchmark's own configuration and launch path (GPT-3-shaped stage, two virtual
+    stages, bf16, kernels picked for these sizes) with 8 microbatches.  The oracle cannot run
+    at this size, so what holds at any size is checked: interleaved 1F1B and
+    all-forwards-then-all-backwards give identical bits (Section 2.2.1), and the gradient of
+    the last bias of a stage, whose cotangent is the incoming one unchanged, equals the plain
+    sum over microbatches and tokens of the inputs c_i (Section 3.1: sum, no 1/M)."""
+    from dataclasses import replace
+    w = replace(inp.C4, n_microbatches=8)
+    M = w.n_microbatches
+    inter = B.jpp_schedule_make(inp.SCHED_INTERLEAVED, w.P, w.rank, w.V, M)
+    flat = [(i, B.JPP_FWD, s) for s in w.stage_ids for i in range(M)]
+    flat += [(i, B.JPP_BWD, s) for s in reversed(w.stage_ids) for i in range(M)]
+    st = Stage(w, tasks=flat)
+    st.set_params_random(seed=5)
+    st.bind(seed=6)
+    outs = []
+    for tasks in (inter, flat):
+        st.zero_grads()
+        st.run(tasks)
+        st.sync()
+        outs.append(([st.grads_tensor(v).clone() for v in range(len(w.stage_ids))],
+                     [t.clone() for t in st.out_y], [t.clone() for t in st.out_dx]))
+        torch.cuda.synchronize()   # the copies run on torch's stream, the next run on the stage's
+    for a, b in zip(outs[0][0], outs[1][0]):
+        assert bool(torch.isfinite(a).all())
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    for k in (1, 2):
+        for a, b in zip(outs[0][k], outs[1][k]):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    off = {name: (o, int(np.prod(shp))) for name, shp, o in st.info}
+    o, n = off["layer0.b2"] if "layer0.b2" in off else off["b2"]
+    for v in range(len(w.stage_ids)):
+        cs = torch.stack([st.in_c[v * M + i].double().sum(dim=(0, 1)) for i in range(M)]).sum(dim=0).cpu().numpy()
+        got = outs[0][0][v][o:o + n].double().cpu().numpy()
+        assert rel_l2(got, cs) < 1e-5
+    st.close()
+
+
 def test_second_run_without_zeroing_doubles_the_gradients():
     """Section 3.1: each backward ADDS to the gradient buffers."""
     w = inp.C1
