@@ -35,6 +35,12 @@ def algorithmic_flops_per_microbatch(w):
     return total * len(w.stage_ids)
 
 
+def flops_full_attention(w):
+    """The count above with attention taken over the whole seq x seq score matrix."""
+    extra = 3 * 2.0 * w.microbatch * w.n_q_heads * w.seq_len ** 2 * w.head_dim * w.n_layers * len(w.stage_ids)
+    return algorithmic_flops_per_microbatch(w) + extra
+
+
 def wgrad_shapes(w):
     """(M, N, K) of the weight-gradient GEMMs of one backward task, in launch order."""
     T = w.tokens
@@ -151,14 +157,20 @@ def main():
         st.run()
     st.sync()
     torch.cuda.synchronize()
+    # per-step marks on the stage's compute stream (every run is joined back into it), recorded
+    # without waiting: the host keeps enqueueing while the GPU works
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    marks[0].record(st.compute)
+    for k in range(a.steps):
         st.zero_grads()
         st.run()
+        marks[k + 1].record(st.compute)
     st.sync()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(a.steps))
     flops_step = algorithmic_flops_per_microbatch(w) * w.n_microbatches
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     mb_per_s = w.n_microbatches / (ms_per_step * 1e-3)
@@ -176,6 +188,9 @@ def main():
         "dtype": "bf16" if w.dtype == inp.DT_BF16 else "f32", "data": "synthetic",
         "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "microbatches_per_s": mb_per_s,
+        "ms_per_step_min": per_step[0], "ms_per_step_median": per_step[len(per_step) // 2],
+        # the same time with attention counted over the full score matrix (no causal halving)
+        "value_full_attention_count": tflops * flops_full_attention(w) / algorithmic_flops_per_microbatch(w),
         "grads_finite": finite,
         "config": {"workload": w.name, "layers_per_stage": w.n_layers, "virtual_stages": w.V,
                    "d_model": w.d_model, "heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_ffn": w.d_ffn,
