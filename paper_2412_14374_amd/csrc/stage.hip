@@ -26,10 +26,8 @@
 // accumulation order is the task order, so results do not depend on the overlap.  Both
 // internal streams are joined back into the compute stream before jpp_stage_run returns.
 #include <algorithm>
-#include <deque>
-#include <vector>
 
-#include "internal.h"
+#include "stage_impl.h"
 
 namespace jpp {
 
@@ -44,102 +42,9 @@ jpp_status fail_hip(hipError_t e, const char* what) {
   return JPP_EDEVICE;
 }
 
-namespace {
-
-constexpr size_t kAlign = 256;
-constexpr int kTxBuffers = 3;   // send staging ring
-constexpr int kCotBuffers = 2;  // cotangent receive ring
-
-size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
-
-struct ParamInfo { std::string name; int64_t shape[2]; size_t offset; };
-
-struct Dims {
-  int T, d, nq, nkv, nqkv, f, f1, hd, Hq, Hkv, seq, mb, vocab, L;
-  size_t esz;
-};
-
-// Element offsets (in bytes from the slot base) of one layer's stash.
-struct LayerStash {
-  size_t x, n1, qkv, O, x1, n2, h, a, stats1, stats2, lse, bytes;
-};
-struct HeadStash { size_t yL, nf, statsf, dz, bytes; };
-
-struct Event {
-  hipEvent_t ev = nullptr;
-  bool recorded = false;
-};
-
-struct Slot {
-  char* base = nullptr;
-  Event freed;  // recorded on the compute stream when the backward that used the slot is done
-  Event rx;     // recorded on the side stream when the received input is in place
-  Event fwd_done;  // recorded on the compute stream when the forward that filled the slot is enqueued
-  bool rx_issued = false;
-};
-
-struct TxBuf {
-  char* p = nullptr;
-  Event produced;  // compute stream: contents written
-  Event sent;      // side stream: copied to the outbox
-};
-
-struct CotBuf {
-  char* p = nullptr;
-  Event freed;  // compute stream: consumer done
-  Event rx;     // side stream: cotangent in place
-};
-
-}  // namespace
-
 }  // namespace jpp
 
 using namespace jpp;
-
-struct jpp_stage {
-  jpp_layer_config cfg;
-  int M = 0, max_in_flight = 0;
-  Dims dm{};
-  std::vector<ParamInfo> pinfo;
-  size_t pcount = 0;
-  // per-layer parameter offsets (elements) by role; -1 if absent
-  struct LayerOff { long ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2; };
-  std::vector<LayerOff> loff;
-  long lnf_g = -1, lnf_b = -1, w_head = -1;
-
-  char* arena = nullptr;
-  size_t arena_bytes = 0;
-  std::vector<char*> params;   // per vstage
-  std::vector<float*> grads;   // per vstage
-  float* rope_table = nullptr;
-  float* losses = nullptr;     // [V*M]
-  LayerStash ls{};
-  HeadStash hs{};
-  size_t slot_bytes = 0;
-  std::vector<Slot> slots;
-  std::vector<TxBuf> tx;
-  std::vector<CotBuf> cot;
-  // workspace
-  char *dbuf[2] = {nullptr, nullptr}, *da = nullptr, *dh = nullptr, *dn = nullptr, *dx1 = nullptr, *dO = nullptr,
-       *dqkv = nullptr;
-  float *delta = nullptr, *partial = nullptr, *z = nullptr, *row_loss = nullptr;
-
-  // boundary
-  std::vector<const void*> inbox_x, inbox_cot;
-  std::vector<void*> outbox_y, outbox_dx;
-  std::vector<const int32_t*> targets;
-  bool bound = false;
-  std::vector<bool> params_set;
-
-  // run state
-  hipStream_t cs = nullptr, ss = nullptr;   // caller's streams of the current / last run
-  hipStream_t bs = nullptr, ws = nullptr;   // internal: backward chain, weight-gradient GEMMs
-  Event end_compute, end_side, run_start, b2w, w_layer, w_task, b_end, w_end;
-  int peak_in_flight = 0, pending_peak = 0, prefetched = 0, host_syncs = 0;
-  std::vector<int> free_slots;
-  std::vector<int> tx_free;
-  std::deque<int> tx_pending;
-};
 
 namespace jpp {
 namespace {
@@ -327,7 +232,7 @@ hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out)
     const auto& o = st.loff[l];
     char* x = b + st.ls.x;
     char* y = (l + 1 < m.L) ? slot.base + (size_t)(l + 1) * st.ls.bytes + st.ls.x
-                            : (c.loss_head ? slot.base + (size_t)m.L * st.ls.bytes + st.hs.yL : y_out);
+                            : (st.is_head(v) ? slot.base + (size_t)m.L * st.ls.bytes + st.hs.yL : y_out);
     K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, x, pptr(st, v, o.ln1_g), pptr(st, v, o.ln1_b),
                           b + st.ls.n1, (float*)(b + st.ls.stats1), s));
     K_TRY(gemm(st, s, m.T, m.nqkv, m.d, b + st.ls.n1, m.d, false, pptr(st, v, o.wqkv), m.d, false, b + st.ls.qkv,
@@ -346,7 +251,7 @@ hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out)
     K_TRY(gemm(st, s, m.T, m.d, m.f, b + st.ls.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
                pptr(st, v, o.b2), b + st.ls.x1));
   }
-  if (c.loss_head) {
+  if (st.is_head(v)) {
     char* hb = slot.base + (size_t)m.L * st.ls.bytes;
     K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, hb + st.hs.yL, pptr(st, v, st.lnf_g),
                           pptr(st, v, st.lnf_b), hb + st.hs.nf, (float*)(hb + st.hs.statsf), s));
@@ -380,7 +285,7 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
   // the workspace buffers are about to be overwritten: the previous backward's weight
   // gradients, which read them, must be done
   if (st.w_task.recorded) K_TRY(hipStreamWaitEvent(s, st.w_task.ev, 0));
-  if (c.loss_head) {
+  if (st.is_head(v)) {
     char* hb = slot.base + (size_t)m.L * st.ls.bytes;
     K_TRY(wgrad(st, m.vocab, m.d, m.T, hb + st.hs.dz, m.vocab, hb + st.hs.nf, m.d, gptr(st, v, st.w_head)));
     K_TRY(gemm(st, s, m.T, m.d, m.vocab, hb + st.hs.dz, m.vocab, false, pptr(st, v, st.w_head), m.d, true, st.dn,
@@ -441,12 +346,6 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
   return hipSuccess;
 }
 
-int local_stage(const jpp_layer_config& c, int global) {
-  for (int v = 0; v < c.n_virtual; ++v)
-    if (c.stage_ids[v] == global) return v;
-  return -1;
-}
-
 // Section 4.3: sweep the pending-deletion queue; buffers whose send has completed go back to
 // the free list.  hipEventQuery does not block.
 void sweep_pending(jpp_stage& st) {
@@ -478,12 +377,14 @@ hipError_t acquire_tx(jpp_stage& st, hipStream_t producer, int& out) {
 
 // Send: copy on the side stream once the producing stream has written the buffer, then the
 // "deletion" of the staging buffer (Section 4.3).
-hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* outbox, size_t bytes) {
+hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* outbox, size_t bytes,
+                           hipEvent_t signal) {
   TxBuf& t = st.tx[b];
   K_TRY(hipEventRecord(t.produced.ev, producer));
   K_TRY(hipStreamWaitEvent(st.ss, t.produced.ev, 0));
   K_TRY(hipMemcpyAsync(outbox, t.p, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(t.sent.ev, st.ss));
+  if (signal) K_TRY(hipEventRecord(signal, st.ss));  // the receiving actor waits for this one
   t.sent.recorded = true;
   sweep_pending(st);
   if (hipEventQuery(t.sent.ev) == hipSuccess) {
@@ -497,7 +398,8 @@ hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* out
 }
 
 // Receive of a forward input into a stash slot (side stream).
-hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes) {
+hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes, hipEvent_t produced) {
+  if (produced) K_TRY(hipStreamWaitEvent(st.ss, produced, 0));  // the sending actor's copy
   if (slot.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, slot.freed.ev, 0));
   K_TRY(hipMemcpyAsync(slot.base + st.ls.x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(slot.rx.ev, st.ss));
@@ -505,7 +407,8 @@ hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes
   return hipSuccess;
 }
 
-hipError_t issue_recv_cot(jpp_stage& st, CotBuf& cb, const void* src, size_t bytes) {
+hipError_t issue_recv_cot(jpp_stage& st, CotBuf& cb, const void* src, size_t bytes, hipEvent_t produced) {
+  if (produced) K_TRY(hipStreamWaitEvent(st.ss, produced, 0));
   if (cb.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, cb.freed.ev, 0));
   K_TRY(hipMemcpyAsync(cb.p, src, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(cb.rx.ev, st.ss));
@@ -610,22 +513,30 @@ jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x, co
                                    void* const* outbox_y, void* const* outbox_dx,
                                    const int32_t* const* targets) {
   if (!st || !inbox_x || !outbox_dx) return fail(JPP_EINVAL, "inbox_x and outbox_dx are required");
-  const bool head = st->cfg.loss_head != 0;
-  if (!head && (!inbox_cot || !outbox_y)) return fail(JPP_EINVAL, "inbox_cot and outbox_y are required");
-  if (head && !targets) return fail(JPP_EINVAL, "targets are required for a loss_head stage");
-  const size_t n = (size_t)st->cfg.n_virtual * st->M;
+  const int V = st->cfg.n_virtual;
+  const bool any_head = st->cfg.loss_head != 0;
+  const bool any_body = !any_head || V > 1;   // the head sits on the last virtual stage only
+  if (any_body && (!inbox_cot || !outbox_y)) return fail(JPP_EINVAL, "inbox_cot and outbox_y are required");
+  if (any_head && !targets) return fail(JPP_EINVAL, "targets are required for a loss_head stage");
+  const size_t n = (size_t)V * st->M;
   for (size_t k = 0; k < n; ++k) {
+    const bool head = st->is_head((int)(k / st->M));
     if (!inbox_x[k] || !outbox_dx[k]) return fail(JPP_EINVAL, "null boundary buffer");
     if (!head && (!inbox_cot[k] || !outbox_y[k])) return fail(JPP_EINVAL, "null boundary buffer");
     if (head && !targets[k]) return fail(JPP_EINVAL, "null targets buffer");
   }
   st->inbox_x.assign(inbox_x, inbox_x + n);
   st->outbox_dx.assign(outbox_dx, outbox_dx + n);
-  if (!head) {
-    st->inbox_cot.assign(inbox_cot, inbox_cot + n);
-    st->outbox_y.assign(outbox_y, outbox_y + n);
-  } else {
-    st->targets.assign(targets, targets + n);
+  st->inbox_cot.assign(n, nullptr);
+  st->outbox_y.assign(n, nullptr);
+  st->targets.assign(n, nullptr);
+  for (size_t k = 0; k < n; ++k) {
+    if (st->is_head((int)(k / st->M))) {
+      st->targets[k] = targets[k];
+    } else {
+      st->inbox_cot[k] = inbox_cot[k];
+      st->outbox_y[k] = outbox_y[k];
+    }
   }
   st->bound = true;
   return JPP_OK;
@@ -640,9 +551,19 @@ jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream) {
   return JPP_OK;
 }
 
-jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream,
-                         void* side_stream) {
+}  // extern "C"
+
+namespace jpp {
+
+int local_stage(const jpp_layer_config& c, int global) {
+  for (int v = 0; v < c.n_virtual; ++v)
+    if (c.stage_ids[v] == global) return v;
+  return -1;
+}
+
+jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream, void* side_stream) {
   if (!st) return fail(JPP_EINVAL, "null stage");
+  if (st->running) return fail(JPP_ESTATE, "a run is already being enqueued on this stage");
   if (!st->bound) return fail(JPP_ESTATE, "boundary buffers not bound");
   for (bool b : st->params_set)
     if (!b) return fail(JPP_ESTATE, "parameters not set for every virtual stage");
@@ -655,9 +576,6 @@ jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void
     return fail(JPP_ECAPACITY, "task list keeps " + std::to_string(peak) + " stashes alive, arena holds " +
                                    std::to_string(st->max_in_flight));
 
-  const Dims& m = st->dm;
-  const size_t bbytes = (size_t)m.T * m.d * m.esz;
-  const bool head = st->cfg.loss_head != 0;
   hipStream_t cs = (hipStream_t)compute_stream, ss = (hipStream_t)side_stream;
   // order this run after the previous one on both streams (device-side waits only)
   if (st->end_compute.recorded) {
@@ -681,99 +599,147 @@ jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void
   st->tx_free.clear(); st->tx_pending.clear();
   for (int k = 0; k < kTxBuffers; ++k) st->tx_free.push_back(k);
 
-  const int V = st->cfg.n_virtual;
-  std::vector<int> slot_of((size_t)V * st->M, -1);   // stash slot of (v, i), assigned at receive time
-  std::vector<int> cot_of((size_t)V * st->M, -1);    // cotangent ring entry of (v, i)
-  int cot_next = 0;
-  int live = 0;
+  const size_t keys = (size_t)st->cfg.n_virtual * st->M;
+  st->run_tasks.assign(tasks, tasks + n_tasks);
+  st->run_next = 0;
+  st->slot_of.assign(keys, -1);   // stash slot of (v, i), assigned at receive time
+  st->cot_of.assign(keys, -1);    // cotangent ring entry of (v, i)
+  st->cot_next = 0;
+  st->live = 0;
+  st->running = true;
+  return JPP_OK;
+}
 
-  // Issues the receive of task k (Section 4.2: asynchronous, ahead of the consumer).
-  auto issue_recv = [&](int k, bool ahead) -> hipError_t {
-    const jpp_task& t = tasks[k];
-    const int v = local_stage(st->cfg, t.stage);
-    const size_t key = (size_t)v * st->M + t.i;
-    if (t.ty == JPP_FWD) {
-      if (slot_of[key] >= 0) return hipSuccess;  // already prefetched
-      if (st->free_slots.empty()) return hipErrorNotReady;  // caller retries when the task itself starts
-      const int sl = st->free_slots.back();
-      st->free_slots.pop_back();
-      slot_of[key] = sl;
-      if (ahead) ++st->prefetched;
-      return issue_recv_x(*st, st->slots[sl], st->inbox_x[key], bbytes);
-    }
-    if (head) return hipSuccess;  // a loss-head backward receives nothing
-    if (cot_of[key] >= 0) return hipSuccess;
-    const int cb = cot_next;
-    cot_next = (cot_next + 1) % kCotBuffers;
-    cot_of[key] = cb;
+namespace {
+
+// Issues the receive of task k (Section 4.2: asynchronous, ahead of the consumer).  `ahead`
+// = issued before the task itself starts (a prefetch): skipped, without error, when no stash
+// slot is free or when the producing actor has not enqueued its send yet.
+hipError_t issue_recv(jpp_stage* st, int k, bool ahead) {
+  const jpp_task& t = st->run_tasks[k];
+  const int v = local_stage(st->cfg, t.stage);
+  const size_t key = (size_t)v * st->M + t.i;
+  const size_t bbytes = (size_t)st->dm.T * st->dm.d * st->dm.esz;
+  if (t.ty == JPP_FWD) {
+    if (st->slot_of[key] >= 0) return hipSuccess;  // already prefetched
+    if (!st->avail_x.empty() && !st->avail_x[key]) return hipErrorNotReady;
+    if (st->free_slots.empty()) return hipErrorNotReady;  // retried when the task itself starts
+    const int sl = st->free_slots.back();
+    st->free_slots.pop_back();
+    st->slot_of[key] = sl;
     if (ahead) ++st->prefetched;
-    return issue_recv_cot(*st, st->cot[cb], st->inbox_cot[key], bbytes);
-  };
-
-  for (int k = 0; k < n_tasks; ++k) {
-    const jpp_task& t = tasks[k];
-    const int v = local_stage(st->cfg, t.stage);
-    const size_t key = (size_t)v * st->M + t.i;
-    // this task's own receive, if it was not prefetched
-    hipError_t e = issue_recv(k, false);
-    if (e != hipSuccess) return fail_hip(e, "receive");
-    // prefetch the next task's input while this task computes
-    if (k + 1 < n_tasks) {
-      // a cotangent ring entry may only be reused once its consumer is enqueued: with two
-      // entries the next backward's receive can always go ahead of the current task
-      e = issue_recv(k + 1, true);
-      if (e != hipSuccess && e != hipErrorNotReady) return fail_hip(e, "prefetch");
-    }
-    if (t.ty == JPP_FWD) {
-      Slot& slot = st->slots[slot_of[key]];
-      ++live;
-      st->peak_in_flight = std::max(st->peak_in_flight, live);
-      HIP_TRY(hipStreamWaitEvent(cs, slot.rx.ev, 0));
-      int txb = -1;
-      if (!head) HIP_TRY(acquire_tx(*st, cs, txb));
-      e = enqueue_forward(*st, v, t.i, slot, head ? nullptr : st->tx[txb].p);
-      if (e != hipSuccess) return fail_hip(e, "forward kernels");
-      HIP_TRY(hipEventRecord(slot.fwd_done.ev, cs));
-      if (!head) HIP_TRY(send_and_delete(*st, cs, txb, st->outbox_y[key], bbytes));
-    } else {
-      Slot& slot = st->slots[slot_of[key]];
-      const char* dy = nullptr;
-      HIP_TRY(hipStreamWaitEvent(st->bs, slot.fwd_done.ev, 0));  // the forward that filled the stash
-      if (!head) {
-        CotBuf& cb = st->cot[cot_of[key]];
-        HIP_TRY(hipStreamWaitEvent(st->bs, cb.rx.ev, 0));
-        dy = cb.p;
-      }
-      int txb = -1;
-      HIP_TRY(acquire_tx(*st, st->bs, txb));
-      e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p);
-      if (e != hipSuccess) return fail_hip(e, "backward kernels");
-      // enqueue_backward left the wgrad stream behind both the input-gradient chain and the
-      // weight gradients of this task: events recorded there cover every reader
-      if (!head) {
-        CotBuf& cb = st->cot[cot_of[key]];
-        HIP_TRY(hipEventRecord(cb.freed.ev, st->ws));
-        cb.freed.recorded = true;
-      }
-      HIP_TRY(send_and_delete(*st, st->bs, txb, st->outbox_dx[key], bbytes));
-      // the stash is dead: release the slot; the event protects it against an early receive
-      // on the side stream (and, through the receive, against the next forward)
-      HIP_TRY(hipEventRecord(slot.freed.ev, st->ws));
-      slot.freed.recorded = true;
-      st->free_slots.push_back(slot_of[key]);
-      slot_of[key] = -1;
-      --live;
-    }
+    return issue_recv_x(*st, st->slots[sl], st->inbox_x[key], bbytes,
+                        st->wait_x.empty() ? nullptr : st->wait_x[key]);
   }
+  if (st->is_head(v)) return hipSuccess;  // a loss-head backward receives nothing
+  if (st->cot_of[key] >= 0) return hipSuccess;
+  if (!st->avail_cot.empty() && !st->avail_cot[key]) return hipErrorNotReady;
+  const int cb = st->cot_next;
+  st->cot_next = (st->cot_next + 1) % kCotBuffers;
+  st->cot_of[key] = cb;
+  if (ahead) ++st->prefetched;
+  return issue_recv_cot(*st, st->cot[cb], st->inbox_cot[key], bbytes,
+                        st->wait_cot.empty() ? nullptr : st->wait_cot[key]);
+}
+
+}  // namespace
+
+jpp_status run_step(jpp_stage* st) {
+  if (!st || !st->running) return fail(JPP_ESTATE, "run_step outside a run");
+  const int n_tasks = (int)st->run_tasks.size();
+  const int k = st->run_next;
+  if (k >= n_tasks) return fail(JPP_ESTATE, "no task left");
+  const Dims& m = st->dm;
+  const size_t bbytes = (size_t)m.T * m.d * m.esz;
+  hipStream_t cs = st->cs;
+  const jpp_task& t = st->run_tasks[k];
+  const int v = local_stage(st->cfg, t.stage);
+  const size_t key = (size_t)v * st->M + t.i;
+  const bool head = st->is_head(v);
+  // this task's own receive, if it was not prefetched
+  hipError_t e = issue_recv(st, k, false);
+  if (e != hipSuccess) return fail_hip(e, "receive");
+  // prefetch the next task's input while this task computes
+  if (k + 1 < n_tasks) {
+    // a cotangent ring entry may only be reused once its consumer is enqueued: with two
+    // entries the next backward's receive can always go ahead of the current task
+    e = issue_recv(st, k + 1, true);
+    if (e != hipSuccess && e != hipErrorNotReady) return fail_hip(e, "prefetch");
+  }
+  if (t.ty == JPP_FWD) {
+    Slot& slot = st->slots[st->slot_of[key]];
+    ++st->live;
+    st->peak_in_flight = std::max(st->peak_in_flight, st->live);
+    HIP_TRY(hipStreamWaitEvent(cs, slot.rx.ev, 0));
+    int txb = -1;
+    if (!head) HIP_TRY(acquire_tx(*st, cs, txb));
+    e = enqueue_forward(*st, v, t.i, slot, head ? nullptr : st->tx[txb].p);
+    if (e != hipSuccess) return fail_hip(e, "forward kernels");
+    HIP_TRY(hipEventRecord(slot.fwd_done.ev, cs));
+    if (!head)
+      HIP_TRY(send_and_delete(*st, cs, txb, st->outbox_y[key], bbytes,
+                              st->signal_y.empty() ? nullptr : st->signal_y[key]));
+  } else {
+    Slot& slot = st->slots[st->slot_of[key]];
+    const char* dy = nullptr;
+    HIP_TRY(hipStreamWaitEvent(st->bs, slot.fwd_done.ev, 0));  // the forward that filled the stash
+    if (!head) {
+      CotBuf& cb = st->cot[st->cot_of[key]];
+      HIP_TRY(hipStreamWaitEvent(st->bs, cb.rx.ev, 0));
+      dy = cb.p;
+    }
+    int txb = -1;
+    HIP_TRY(acquire_tx(*st, st->bs, txb));
+    e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p);
+    if (e != hipSuccess) return fail_hip(e, "backward kernels");
+    // enqueue_backward left the wgrad stream behind both the input-gradient chain and the
+    // weight gradients of this task: events recorded there cover every reader
+    if (!head) {
+      CotBuf& cb = st->cot[st->cot_of[key]];
+      HIP_TRY(hipEventRecord(cb.freed.ev, st->ws));
+      cb.freed.recorded = true;
+    }
+    HIP_TRY(send_and_delete(*st, st->bs, txb, st->outbox_dx[key], bbytes,
+                            st->signal_dx.empty() ? nullptr : st->signal_dx[key]));
+    // the stash is dead: release the slot; the event protects it against an early receive
+    // on the side stream (and, through the receive, against the next forward)
+    HIP_TRY(hipEventRecord(slot.freed.ev, st->ws));
+    slot.freed.recorded = true;
+    st->free_slots.push_back(st->slot_of[key]);
+    st->slot_of[key] = -1;
+    --st->live;
+  }
+  st->run_next = k + 1;
+  return JPP_OK;
+}
+
+jpp_status run_end(jpp_stage* st) {
+  if (!st || !st->running) return fail(JPP_ESTATE, "run_end outside a run");
+  st->running = false;
   // join the internal streams back into the caller's compute stream
   HIP_TRY(hipEventRecord(st->b_end.ev, st->bs));
   HIP_TRY(hipEventRecord(st->w_end.ev, st->ws));
-  HIP_TRY(hipStreamWaitEvent(cs, st->b_end.ev, 0));
-  HIP_TRY(hipStreamWaitEvent(cs, st->w_end.ev, 0));
-  HIP_TRY(hipEventRecord(st->end_compute.ev, cs));
-  HIP_TRY(hipEventRecord(st->end_side.ev, ss));
+  HIP_TRY(hipStreamWaitEvent(st->cs, st->b_end.ev, 0));
+  HIP_TRY(hipStreamWaitEvent(st->cs, st->w_end.ev, 0));
+  HIP_TRY(hipEventRecord(st->end_compute.ev, st->cs));
+  HIP_TRY(hipEventRecord(st->end_side.ev, st->ss));
   st->end_compute.recorded = true;
   return JPP_OK;
+}
+
+}  // namespace jpp
+
+extern "C" {
+
+jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream,
+                         void* side_stream) {
+  jpp_status rc = run_begin(st, tasks, n_tasks, compute_stream, side_stream);
+  if (rc != JPP_OK) return rc;
+  for (int k = 0; k < n_tasks; ++k) {
+    rc = run_step(st);
+    if (rc != JPP_OK) { st->running = false; return rc; }
+  }
+  return run_end(st);
 }
 
 jpp_status jpp_stage_grads(jpp_stage* st, int vstage, const float** grads_dev, size_t* n_elems) {

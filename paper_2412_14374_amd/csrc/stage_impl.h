@@ -1,0 +1,135 @@
+// State of one stage executor (one actor), shared by the executor and the multi-actor
+// pipeline driver.  Not part of the C interface.
+#pragma once
+
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+namespace jpp {
+
+constexpr size_t kAlign = 256;
+constexpr int kTxBuffers = 3;   // send staging ring
+constexpr int kCotBuffers = 2;  // cotangent receive ring
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct ParamInfo { std::string name; int64_t shape[2]; size_t offset; };
+
+struct Dims {
+  int T, d, nq, nkv, nqkv, f, f1, hd, Hq, Hkv, seq, mb, vocab, L;
+  size_t esz;
+};
+
+// Element offsets (in bytes from the slot base) of one layer's stash.
+struct LayerStash {
+  size_t x, n1, qkv, O, x1, n2, h, a, stats1, stats2, lse, bytes;
+};
+struct HeadStash { size_t yL, nf, statsf, dz, bytes; };
+
+struct Event {
+  hipEvent_t ev = nullptr;
+  bool recorded = false;
+};
+
+struct Slot {
+  char* base = nullptr;
+  Event freed;  // recorded on the compute stream when the backward that used the slot is done
+  Event rx;     // recorded on the side stream when the received input is in place
+  Event fwd_done;  // recorded on the compute stream when the forward that filled the slot is enqueued
+  bool rx_issued = false;
+};
+
+struct TxBuf {
+  char* p = nullptr;
+  Event produced;  // compute stream: contents written
+  Event sent;      // side stream: copied to the outbox
+};
+
+struct CotBuf {
+  char* p = nullptr;
+  Event freed;  // compute stream: consumer done
+  Event rx;     // side stream: cotangent in place
+};
+
+}  // namespace jpp
+
+struct jpp_stage {
+  typedef jpp::Dims Dims; typedef jpp::ParamInfo ParamInfo; typedef jpp::LayerStash LayerStash;
+  typedef jpp::HeadStash HeadStash; typedef jpp::Event Event; typedef jpp::Slot Slot;
+  typedef jpp::TxBuf TxBuf; typedef jpp::CotBuf CotBuf;
+  jpp_layer_config cfg;
+  int M = 0, max_in_flight = 0;
+  Dims dm{};
+  std::vector<ParamInfo> pinfo;
+  size_t pcount = 0;
+  // per-layer parameter offsets (elements) by role; -1 if absent
+  struct LayerOff { long ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2; };
+  std::vector<LayerOff> loff;
+  long lnf_g = -1, lnf_b = -1, w_head = -1;
+
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  std::vector<char*> params;   // per vstage
+  std::vector<float*> grads;   // per vstage
+  float* rope_table = nullptr;
+  float* losses = nullptr;     // [V*M]
+  LayerStash ls{};
+  HeadStash hs{};
+  size_t slot_bytes = 0;
+  std::vector<Slot> slots;
+  std::vector<TxBuf> tx;
+  std::vector<CotBuf> cot;
+  // workspace
+  char *dbuf[2] = {nullptr, nullptr}, *da = nullptr, *dh = nullptr, *dn = nullptr, *dx1 = nullptr, *dO = nullptr,
+       *dqkv = nullptr;
+  float *delta = nullptr, *partial = nullptr, *z = nullptr, *row_loss = nullptr;
+
+  // boundary
+  std::vector<const void*> inbox_x, inbox_cot;
+  std::vector<void*> outbox_y, outbox_dx;
+  std::vector<const int32_t*> targets;
+  bool bound = false;
+  std::vector<bool> params_set;
+
+  // run state
+  hipStream_t cs = nullptr, ss = nullptr;   // caller's streams of the current / last run
+  hipStream_t bs = nullptr, ws = nullptr;   // internal: backward chain, weight-gradient GEMMs
+  Event end_compute, end_side, run_start, b2w, w_layer, w_task, b_end, w_end;
+  int peak_in_flight = 0, pending_peak = 0, prefetched = 0, host_syncs = 0;
+  std::vector<int> free_slots;
+  std::vector<int> tx_free;
+  std::deque<int> tx_pending;
+  // the task list being enqueued (between run_begin and run_end)
+  std::vector<jpp_task> run_tasks;
+  int run_next = 0;                 // index of the next task to enqueue
+  std::vector<int> slot_of, cot_of; // stash slot / cotangent ring entry of (v, i); -1 = none
+  int cot_next = 0, live = 0;
+  bool running = false;
+
+  // Hand-offs to other actors on the same device, set by a pipeline (empty otherwise); all
+  // indexed v * M + i.  A receive waits (on the side stream) for wait_*[key] before it copies;
+  // a send records signal_*[key] after its copy.  avail_*[key] says that the producer of the
+  // input has been enqueued, i.e. that wait_*[key] has been recorded: only then may the
+  // receive be issued (a wait on an event that is not yet recorded does not wait).
+  std::vector<hipEvent_t> wait_x, wait_cot, signal_y, signal_dx;
+  std::vector<char> avail_x, avail_cot;
+
+  // The loss head, if configured, belongs to the actor's last virtual stage.
+  bool is_head(int v) const { return cfg.loss_head != 0 && v == cfg.n_virtual - 1; }
+};
+
+namespace jpp {
+
+int local_stage(const jpp_layer_config& c, int global);
+// jpp_stage_run in three parts, so that a pipeline can interleave the task lists of several
+// actors: run_begin validates and prepares (no kernel is launched on failure), run_step
+// enqueues the next task (its receive, kernels and send) and run_end joins the streams.
+jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream, void* side_stream);
+jpp_status run_step(jpp_stage* st);
+jpp_status run_end(jpp_stage* st);
+
+}  // namespace jpp
+
