@@ -146,3 +146,27 @@ def draw_stage_inputs(w, layer_shapes, head_shapes=None, seed=SEED, perturb=Fals
         targets = [rng.integers(0, w.vocab, size=(w.microbatch, w.seq_len)).astype(np.int32)
                    for _ in range(M)]
     return params, x, cot, targets
+
+
+def draw_pipeline_inputs(w, n_stages, layer_shapes, head_shapes=None, seed=SEED, perturb=False):
+    """Draw what a whole pipeline of `n_stages` stages needs, in a fixed order: per stage the
+    parameters (layer by layer; the head on the last stage if w.loss_head), then the inputs
+    x_0..x_{M-1} of stage 0, then either the targets (loss head) or the cotangents
+    c_0..c_{M-1} of the last stage's output.  Returns (params_by_stage, x0, cot_last, targets)
+    with float64 arrays already rounded to the storage type."""
+    rng = np.random.default_rng(seed)
+    M = w.n_microbatches
+    shp = (w.microbatch, w.seq_len, w.d_model)
+    params = {}
+    for s in range(n_stages):
+        p = {"layers": [draw_params(layer_shapes, rng, w, perturb) for _ in range(w.n_layers)]}
+        if w.loss_head and s == n_stages - 1:
+            p["head"] = draw_params(head_shapes, rng, w, perturb)
+        params[s] = p
+    x0 = [round_to_dtype(rng.standard_normal(shp), w.dtype) for _ in range(M)]
+    cot_last, targets = None, None
+    if w.loss_head:
+        targets = [rng.integers(0, w.vocab, size=(w.microbatch, w.seq_len)).astype(np.int32) for _ in range(M)]
+    else:
+        cot_last = [round_to_dtype(rng.standard_normal(shp) * w.cot_std, w.dtype) for _ in range(M)]
+    return params, x0, cot_last, targets
