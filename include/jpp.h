@@ -59,7 +59,10 @@ typedef struct { int32_t i; int32_t ty; int32_t stage; } jpp_task;
  *     GeLU:   y = x1 + gelu(n2 W1^T + b1) W2^T + b2
  *     SwiGLU: [g|u] = n2 W1^T (W1 is [2*d_ffn, d_model], gate rows first); y = x1 + (silu(g)*u) W2^T
  * optionally followed (loss_head) by a final norm, an untied LM head [vocab, d_model]
- * and the mean-token cross-entropy, whose backward is seeded with dloss = 1. */
+ * and the mean-token cross-entropy, whose backward is seeded with dloss = 1.  With several
+ * virtual stages the head belongs to the LAST one (local index n_virtual-1) only; the head's
+ * parameter slots exist in every virtual stage's buffer and stay unused (zero gradient)
+ * in the others. */
 typedef struct {
   int32_t dtype;      /* JPP_F32: everything fp32.  JPP_BF16: bf16 storage, fp32 accumulate   */
   int32_t n_layers;   /* decoder layers per (virtual) stage                                   */
@@ -132,10 +135,11 @@ jpp_status jpp_stage_set_params(jpp_stage* st, int vstage, const void* src, int 
 /* Boundary buffers, caller-owned, all device pointers to [microbatch, seq_len, d_model]
  * tensors of the storage dtype; each host array has n_virtual * M entries indexed
  * [vstage * M + i].  inbox_x[i]: activation received for FWD(i); inbox_cot[i]: cotangent
- * received for BWD(i) (ignored / may be NULL for a loss_head stage); outbox_y[i]: output
- * sent after FWD(i) (NULL array allowed for a loss_head stage); outbox_dx[i]: input
- * cotangent sent after BWD(i).  targets[i] (loss_head only): device int32
- * [microbatch, seq_len] token ids in [0, vocab).  The host arrays are copied. */
+ * received for BWD(i) and outbox_y[i]: output sent after FWD(i) (entries of the virtual
+ * stage that carries the loss head are ignored; the arrays may be NULL when that is the only
+ * one); outbox_dx[i]: input cotangent sent after BWD(i).  targets[i] (loss_head only, read
+ * for the head's virtual stage): device int32 [microbatch, seq_len] token ids in [0, vocab).
+ * The host arrays are copied. */
 jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x,
                                    const void* const* inbox_cot, void* const* outbox_y,
                                    void* const* outbox_dx, const int32_t* const* targets);
@@ -164,8 +168,9 @@ jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void
  * offsets as the parameters).  Valid until zero_grads / destroy. */
 jpp_status jpp_stage_grads(jpp_stage* st, int vstage, const float** grads_dev, size_t* n_elems);
 
-/* loss_head stages: borrowed device pointer to the fp32 loss vector [M] (Section 3.1:
- * losses are collected per microbatch, not averaged over microbatches). Synchronises. */
+/* loss_head stages: borrowed device pointer to the fp32 loss vector [n_virtual * M], entry
+ * [vstage * M + i]; only the head's virtual stage (the last) is written (Section 3.1: losses
+ * are collected per microbatch, not averaged over microbatches). Synchronises. */
 jpp_status jpp_stage_losses(jpp_stage* st, const float** loss_dev);
 
 /* Introspection of the last run (host bookkeeping, used by tests). */
@@ -175,6 +180,48 @@ int jpp_stage_prefetched(const jpp_stage* st);       /* receives issued ahead of
 int jpp_stage_host_syncs(const jpp_stage* st);       /* host-side waits inside the last run (0) */
 
 const char* jpp_last_error(void);
+
+/* ---- several actors on one device (Sections 4.2 and 4.4) ----------------------------
+ * A pipeline of P actors; actor r is a jpp_stage created by the caller whose stage_ids are
+ * {r, P + r, 2P + r, ...} (circular placement), all with the same n_microbatches, dtype and
+ * boundary shape; only actor P-1 may have loss_head = 1 (the last global stage then ends in
+ * the loss).  The pipeline owns the boundary buffers between consecutive stages (in the
+ * caller's arena) and wires them into the actors with jpp_stage_bind_boundary: stage s sends
+ * y to stage s+1 and dx to stage s-1 right after the producing task, the receiver copies it
+ * in ahead of its consumer when it can.  Parameters are set on the actors directly;
+ * gradients and losses are read from them (jpp_stage_grads, jpp_stage_losses of actor P-1).
+ * Destroy the pipeline before its actors. */
+typedef struct jpp_pipeline jpp_pipeline;
+
+/* Bytes of device memory for the boundary buffers: 2 * (P * n_virtual - 1) * M tensors. */
+size_t jpp_pipeline_arena_bytes(const jpp_layer_config* cfg, int n_actors, int n_microbatches);
+
+/* arena_dev: device pointer, 256-byte aligned, caller-owned, at least arena_bytes (may be
+ * NULL when there is a single stage).  JPP_EINVAL if the actors do not fit together. */
+jpp_status jpp_pipeline_create(jpp_stage* const* actors, int n_actors, void* arena_dev, size_t arena_bytes,
+                               jpp_pipeline** out);
+void jpp_pipeline_destroy(jpp_pipeline* p);
+
+/* Outer boundary, device pointers, M entries each: x_in[i] input of stage 0, dx_out[i] its
+ * cotangent; with a loss head targets[i] (int32 [microbatch, seq_len]); without one cot_in[i]
+ * (cotangent of the last stage's output) and y_out[i] (that output). */
+jpp_status jpp_pipeline_bind(jpp_pipeline* p, const void* const* x_in, void* const* dx_out,
+                             const int32_t* const* targets, const void* const* cot_in, void* const* y_out);
+
+/* One training step of the whole pipeline: task_lists[r] / n_tasks[r] is actor r's list,
+ * compute_streams[r] / side_streams[r] its two streams (all distinct, default priority).
+ * Every list is validated as in jpp_stage_run, then the lists are merged in a topological
+ * order of the task graph (Section 4.2): round after round each actor enqueues its next task
+ * if the task producing its operand (FWD(i, s-1) for FWD(i, s); BWD(i, s+1) for BWD(i, s)) is
+ * already enqueued.  If no actor can move the lists wait for each other in a cycle:
+ * JPP_ESCHED, with the blocked tasks in jpp_last_error(), and nothing has been launched.
+ * Asynchronous, no host synchronisation; gradients accumulate as in jpp_stage_run (call
+ * jpp_stage_zero_grads on every actor's compute stream first). */
+jpp_status jpp_pipeline_run(jpp_pipeline* p, const jpp_task* const* task_lists, const int* n_tasks,
+                            void* const* compute_streams, void* const* side_streams);
+
+/* Waits for everything the last jpp_pipeline_run enqueued. */
+jpp_status jpp_pipeline_sync(jpp_pipeline* p);
 
 /* ---- single operations (the kernels the executor is made of) ------------------------
  * Exposed for op-level parity at shapes the CPU oracle cannot run end to end, and for

@@ -54,6 +54,14 @@ _SIGNATURES = {
     "jpp_stage_run": (C.c_int, [C.c_void_p, C.POINTER(jpp_task), C.c_int, C.c_void_p, C.c_void_p]),
     "jpp_stage_grads": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
     "jpp_stage_losses": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p)]),
+    "jpp_pipeline_arena_bytes": (C.c_size_t, [C.POINTER(jpp_layer_config), C.c_int, C.c_int]),
+    "jpp_pipeline_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_size_t,
+                                      C.POINTER(C.c_void_p)]),
+    "jpp_pipeline_destroy": (None, [C.c_void_p]),
+    "jpp_pipeline_bind": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_void_p)] * 5),
+    "jpp_pipeline_run": (C.c_int, [C.c_void_p, C.POINTER(C.POINTER(jpp_task)), C.POINTER(C.c_int),
+                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
+    "jpp_pipeline_sync": (C.c_int, [C.c_void_p]),
     "jpp_stage_peak_in_flight": (C.c_int, [C.c_void_p]),
     "jpp_stage_pending_peak": (C.c_int, [C.c_void_p]),
     "jpp_stage_prefetched": (C.c_int, [C.c_void_p]),
@@ -219,6 +227,40 @@ def jpp_stage_losses(h):
     p = C.c_void_p()
     _check(lib().jpp_stage_losses(h, C.byref(p)))
     return p.value
+
+
+def jpp_pipeline_arena_bytes(cfg, n_actors, M):
+    return lib().jpp_pipeline_arena_bytes(C.byref(cfg), n_actors, M)
+
+
+def jpp_pipeline_create(actor_handles, arena_ptr, arena_bytes):
+    h = C.c_void_p()
+    arr = (C.c_void_p * len(actor_handles))(*[a.value if hasattr(a, "value") else a for a in actor_handles])
+    _check(lib().jpp_pipeline_create(arr, len(actor_handles), C.c_void_p(arena_ptr), arena_bytes, C.byref(h)))
+    return h
+
+
+def jpp_pipeline_destroy(h):
+    lib().jpp_pipeline_destroy(h)
+
+
+def jpp_pipeline_bind(h, x_in, dx_out, targets, cot_in, y_out):
+    """Each argument: list of M device addresses (ints) or None."""
+    _check(lib().jpp_pipeline_bind(h, _ptr_array(x_in), _ptr_array(dx_out), _ptr_array(targets),
+                                   _ptr_array(cot_in), _ptr_array(y_out)))
+
+
+def jpp_pipeline_run(h, task_lists, compute_streams, side_streams):
+    """task_lists: one list of (i, ty, stage) per actor; streams: raw stream handles (ints)."""
+    P = len(task_lists)
+    arrs = [tasks_array(t) for t in task_lists]
+    lists = (C.POINTER(jpp_task) * P)(*[C.cast(a, C.POINTER(jpp_task)) for a, _ in arrs])
+    counts = (C.c_int * P)(*[n for _, n in arrs])
+    _check(lib().jpp_pipeline_run(h, lists, counts, _ptr_array(compute_streams), _ptr_array(side_streams)))
+
+
+def jpp_pipeline_sync(h):
+    _check(lib().jpp_pipeline_sync(h))
 
 
 def jpp_stage_peak_in_flight(h):

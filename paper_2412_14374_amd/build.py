@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libjpp.so")
-SOURCES = ["schedule.cpp", "stage.hip", "ops_api.hip", "rowwise.hip", "gemm_f32.hip", "gemm_bf16.hip",
+SOURCES = ["schedule.cpp", "stage.hip", "pipeline.hip", "ops_api.hip", "rowwise.hip", "gemm_f32.hip", "gemm_bf16.hip",
            "attention_generic.hip", "attention_mfma.hip"]
 # -packed-fp32-ops is switched OFF for device code (packed fp32 forms have misbehaved on the
 # target machines); the host pass does not know the feature and says so, harmlessly.

@@ -74,6 +74,8 @@ class Stage:
         flat = np.zeros(self.pcount, dtype=np.float32)
         for name, shp, off in self.info:
             grp, key = name.split(".", 1)
+            if grp == "head" and "head" not in p:
+                continue            # a virtual stage without the head: its slots stay zero
             a = p["head"][key] if grp == "head" else p["layers"][int(grp[5:])][key]
             assert tuple(a.shape) == tuple(shp), (name, a.shape, shp)
             flat[off:off + a.size] = a.reshape(-1)
@@ -191,3 +193,78 @@ class Stage:
 
 def default_tasks(w):
     return B.jpp_schedule_make(w.sched, w.P, w.rank, w.V, w.n_microbatches)
+
+
+class Pipeline:
+    """P actors (Stage objects) of one pipeline on one device plus the pipeline's own boundary
+    buffers and outer inputs / outputs.  `w` describes one actor (P, V, layer shape);
+    w.loss_head says whether the last global stage ends in the loss."""
+
+    def __init__(self, w, task_lists, dev="cuda:0"):
+        from dataclasses import replace
+        self.w, self.dev = w, dev
+        self.P, self.V, self.M = w.P, w.V, w.n_microbatches
+        self.S = self.P * self.V
+        self.task_lists = [list(t) for t in task_lists]
+        self.actors = [Stage(replace(w, rank=r, loss_head=(w.loss_head if r == self.P - 1 else 0)),
+                             tasks=self.task_lists[r], dev=dev) for r in range(self.P)]
+        nbytes = B.jpp_pipeline_arena_bytes(self.actors[0].cfg, self.P, self.M)
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        base = (self.arena.data_ptr() + 255) // 256 * 256
+        self.h = B.jpp_pipeline_create([a.h for a in self.actors], base, nbytes)
+
+    def close(self):
+        if self.h is not None:
+            B.jpp_pipeline_destroy(self.h)
+            self.h = None
+        for a in self.actors:
+            a.close()
+
+    def set_params_host(self, params_by_stage):
+        for a in self.actors:
+            a.set_params_host(params_by_stage)
+
+    def bind(self, x0, cot_last=None, targets=None):
+        w, dt = self.w, torch_dtype(self.w)
+        shp = (w.microbatch, w.seq_len, w.d_model)
+        self.x_in = [to_device(x, w, self.dev) for x in x0]
+        self.dx_out = [torch.zeros(shp, dtype=dt, device=self.dev) for _ in range(self.M)]
+        self.tg = self.cot_in = self.y_out = None
+        if w.loss_head:
+            self.tg = [torch.from_numpy(np.ascontiguousarray(t, dtype=np.int32)).to(self.dev) for t in targets]
+        else:
+            self.cot_in = [to_device(c, w, self.dev) for c in cot_last]
+            self.y_out = [torch.zeros(shp, dtype=dt, device=self.dev) for _ in range(self.M)]
+        torch.cuda.synchronize()
+        ptrs = lambda ts: [t.data_ptr() for t in ts] if ts else None
+        B.jpp_pipeline_bind(self.h, ptrs(self.x_in), ptrs(self.dx_out), ptrs(self.tg), ptrs(self.cot_in),
+                            ptrs(self.y_out))
+
+    def zero_grads(self):
+        for a in self.actors:
+            a.zero_grads()
+
+    def run(self, task_lists=None):
+        B.jpp_pipeline_run(self.h, self.task_lists if task_lists is None else task_lists,
+                           [a.compute.cuda_stream for a in self.actors], [a.side.cuda_stream for a in self.actors])
+
+    def sync(self):
+        B.jpp_pipeline_sync(self.h)
+
+    def results(self):
+        """Host float64 results keyed like oracle.pipeline_oracle.run_pipeline's output."""
+        self.sync()
+        torch.cuda.synchronize()
+        out = {"grads": {}, "dx": [to_host(t) for t in self.dx_out]}
+        for r, a in enumerate(self.actors):
+            for v in range(self.V):
+                g = a.unpack_grads(a.grads_tensor(v).cpu().numpy().astype(np.float64))
+                if "head" in g and not (r == self.P - 1 and v == self.V - 1):
+                    del g["head"]
+                out["grads"][v * self.P + r] = g
+        if self.w.loss_head:
+            l = self.actors[-1].losses()
+            out["loss"] = list(l[(self.V - 1) * self.M:self.V * self.M])
+        else:
+            out["y"] = [to_host(t) for t in self.y_out]
+        return out
