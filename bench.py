@@ -113,6 +113,44 @@ def cpu_baseline():
                       f"{flops / 1e9:.0f} algorithmic GFLOP"}
 
 
+def bench_pipeline(a, w, torch, B, inp):
+    """The configuration as a whole pipeline on one device: P actors with one virtual stage of
+    w.n_layers layers each (so P times the single-actor model), every actor running its own
+    1F1B list of the same M microbatches, outputs handed from actor to actor."""
+    from dataclasses import replace
+    from paper_2412_14374_amd.harness import Pipeline
+    wp = replace(w, V=1, sched=inp.SCHED_1F1B, rank=0)
+    P, M = wp.P, wp.n_microbatches
+    lists = [B.jpp_schedule_make(inp.SCHED_1F1B, P, r, 1, M) for r in range(P)]
+    pipe = Pipeline(wp, lists)
+    pipe.set_params_random(seed=0)
+    pipe.bind_random(seed=1)
+    for _ in range(a.warmup):
+        pipe.zero_grads()
+        pipe.run()
+    pipe.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        pipe.zero_grads()
+        pipe.run()
+    pipe.sync()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / a.steps * 1e3
+    # per actor: the body layers; the head, if any, on the last actor only
+    body = algorithmic_flops_per_microbatch(replace(wp, loss_head=0))
+    flops = (body * P + (algorithmic_flops_per_microbatch(wp) - body)) * M
+    finite = all(bool(torch.isfinite(s.grads_tensor(0)).all().item()) for s in pipe.actors)
+    pipe.close()
+    print(json.dumps({"metric": "whole pipeline on one GPU, fwd+bwd TFLOP/s", "value": flops / (ms * 1e-3) / 1e12,
+                      "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+                      "dtype": "bf16" if w.dtype == inp.DT_BF16 else "f32", "data": "synthetic",
+                      "pct_of_bf16_mfma_peak": 100.0 * flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                      "grads_finite": finite,
+                      "config": {"workload": w.name + " as a pipeline", "actors": P, "layers_per_actor": w.n_layers,
+                                 "n_microbatches": M, "schedule": "1f1b per actor"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +158,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
+                         "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
+                         "instead of a single actor; prints a line of its own")
     ap.add_argument("--kernel-only", action="store_true",
                     help="profiling aid: run only the dominant kernel's launches plus one 1 GiB device copy "
                          "(the reference that scales the FETCH_SIZE / WRITE_SIZE counters)")
@@ -149,6 +191,8 @@ def main():
         print(json.dumps({"kernel_only": True, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
                           "tflops": flops / avg_ms / 1e9}))
         return
+    if a.pipeline:
+        return bench_pipeline(a, w, torch, B, inp)
     st = Stage(w)
     st.set_params_random(seed=0)
     st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM

@@ -224,6 +224,30 @@ class Pipeline:
         for a in self.actors:
             a.set_params_host(params_by_stage)
 
+    def set_params_random(self, seed=0):
+        for r, a in enumerate(self.actors):
+            a.set_params_random(seed=seed + r)
+
+    def bind_random(self, seed=1):
+        """Synthetic outer inputs generated in HBM (benchmark path)."""
+        w, dt = self.w, torch_dtype(self.w)
+        shp = (w.microbatch, w.seq_len, w.d_model)
+        g = torch.Generator(device=self.dev)
+        g.manual_seed(seed)
+        self.x_in = [torch.randn(shp, generator=g, device=self.dev).to(dt) for _ in range(self.M)]
+        self.dx_out = [torch.zeros(shp, dtype=dt, device=self.dev) for _ in range(self.M)]
+        self.tg = self.cot_in = self.y_out = None
+        if w.loss_head:
+            self.tg = [torch.randint(0, w.vocab, (w.microbatch, w.seq_len), generator=g, device=self.dev,
+                                     dtype=torch.int32) for _ in range(self.M)]
+        else:
+            self.cot_in = [(torch.randn(shp, generator=g, device=self.dev) * w.cot_std).to(dt) for _ in range(self.M)]
+            self.y_out = [torch.zeros(shp, dtype=dt, device=self.dev) for _ in range(self.M)]
+        torch.cuda.synchronize()
+        ptrs = lambda ts: [t.data_ptr() for t in ts] if ts else None
+        B.jpp_pipeline_bind(self.h, ptrs(self.x_in), ptrs(self.dx_out), ptrs(self.tg), ptrs(self.cot_in),
+                            ptrs(self.y_out))
+
     def bind(self, x0, cot_last=None, targets=None):
         w, dt = self.w, torch_dtype(self.w)
         shp = (w.microbatch, w.seq_len, w.d_model)
