@@ -158,6 +158,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--remat", action="store_true",
+                    help="rematerialisation: keep only each layer's input, recompute the layer in the backward "
+                         "(the recomputation is not counted in the TFLOP/s)")
+    ap.add_argument("--schedule", choices=["gpipe", "1f1b", "interleaved"], default=None,
+                    help="override the configuration's schedule (same P, rank, V)")
     ap.add_argument("--pipeline", action="store_true",
                     help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
@@ -191,9 +196,21 @@ def main():
         print(json.dumps({"kernel_only": True, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
                           "tflops": flops / avg_ms / 1e9}))
         return
+    if a.remat or a.schedule:
+        from dataclasses import replace
+        kind = {"gpipe": inp.SCHED_GPIPE, "1f1b": inp.SCHED_1F1B, "interleaved": inp.SCHED_INTERLEAVED,
+                None: w.sched}[a.schedule]
+        w = replace(w, remat=1 if a.remat else 0, sched=kind)
     if a.pipeline:
         return bench_pipeline(a, w, torch, B, inp)
-    st = Stage(w)
+    tasks = None
+    if w.sched == inp.SCHED_GPIPE and w.V > 1:
+        # GPipe on a circular placement: every forward of every owned stage, then every backward
+        tasks = [(i, B.JPP_FWD, s) for s in w.stage_ids for i in range(w.n_microbatches)]
+        tasks += [(i, B.JPP_BWD, s) for s in reversed(w.stage_ids) for i in range(w.n_microbatches)]
+    st = Stage(w, tasks=tasks)
+    arena_gb = B.jpp_stage_arena_bytes(st.cfg, st.M, st.max_in_flight) / 1e9
+    stash_slots = st.max_in_flight
     st.set_params_random(seed=0)
     st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM
     for _ in range(a.warmup):
@@ -240,6 +257,7 @@ def main():
                    "d_model": w.d_model, "heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_ffn": w.d_ffn,
                    "seq_len": w.seq_len, "microbatch": w.microbatch, "n_microbatches": w.n_microbatches,
                    "schedule": ["gpipe", "1f1b", "interleaved-1f1b"][w.sched], "P": w.P, "rank": w.rank,
+                   "remat": bool(w.remat), "arena_gb": arena_gb, "stash_slots": stash_slots,
                    "algorithmic_tflop_per_microbatch": algorithmic_flops_per_microbatch(w) / 1e12},
     }
     if w.dtype == inp.DT_BF16:

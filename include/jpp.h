@@ -75,6 +75,10 @@ typedef struct {
   float norm_eps;
   int32_t loss_head;  /* 1: final norm + LM head + mean-token CE; output is loss[i]           */
   int32_t vocab;
+  int32_t remat;      /* 1: rematerialisation (Section 2.2.1: trade memory for recomputation): a
+                       * forward keeps only each layer's input; the backward re-runs the layer's
+                       * forward (without its last GEMM) before differentiating it.  Same results,
+                       * bit for bit; the stash shrinks from (8 d + 2 f) T to d T elements per layer */
   int32_t n_virtual;  /* stages owned by this actor                                           */
   int32_t stage_ids[JPP_MAX_VIRTUAL]; /* their global indices (interleaved: v*P + rank)       */
 } jpp_layer_config;

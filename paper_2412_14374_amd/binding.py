@@ -31,7 +31,7 @@ class jpp_layer_config(C.Structure):
                 ("d_ffn", C.c_int32), ("seq_len", C.c_int32), ("microbatch", C.c_int32),
                 ("norm", C.c_int32), ("act", C.c_int32), ("use_bias", C.c_int32), ("rope", C.c_int32),
                 ("rope_theta", C.c_float), ("norm_eps", C.c_float), ("loss_head", C.c_int32),
-                ("vocab", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
+                ("vocab", C.c_int32), ("remat", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
 
 
 _lib = None
@@ -113,7 +113,7 @@ def make_config(w):
     for f, _ in jpp_layer_config._fields_:
         if f in ("stage_ids", "n_virtual"):
             continue
-        setattr(c, f, getattr(w, f))
+        setattr(c, f, getattr(w, f, 0) if f == "remat" else getattr(w, f))   # remat is optional
     ids = list(w.stage_ids)
     c.n_virtual = len(ids)
     for k, s in enumerate(ids):

@@ -63,6 +63,7 @@ bool config_ok(const jpp_layer_config* c, int M, int max_in_flight, std::string&
       if (c->stage_ids[a] == c->stage_ids[b]) { why = "duplicate stage id"; return false; }
   if (M < 1 || max_in_flight < 1) { why = "n_microbatches and max_in_flight must be positive"; return false; }
   if (c->loss_head && c->vocab < 1) { why = "loss_head needs vocab"; return false; }
+  if (c->remat != 0 && c->remat != 1) { why = "remat must be 0 or 1"; return false; }
   const int chunk = c->dtype == JPP_BF16 ? 8 : 4;
   if (c->head_dim % chunk != 0 || c->head_dim > 256) { why = "head_dim must be a multiple of the 16-byte chunk and <= 256"; return false; }
   if (c->rope && (c->head_dim / 2) % chunk != 0) { why = "rope needs head_dim/2 to be a multiple of the 16-byte chunk"; return false; }
@@ -163,10 +164,13 @@ size_t carve(jpp_stage& st, char* base) {
       st.hs.dz = sub(T * m.vocab * e);
     }
     st.hs.bytes = o;
-    st.slot_bytes = st.ls.bytes * m.L + st.hs.bytes;
+    st.xbytes = align_up(T * m.d * e);
+    st.slot_bytes = (c.remat ? st.xbytes : st.ls.bytes) * m.L + st.hs.bytes;
   }
   st.slots.resize(st.max_in_flight);
   for (auto& s : st.slots) s.base = take(st.slot_bytes);
+  st.remat_f = c.remat ? take(st.ls.bytes) : nullptr;
+  st.remat_b = c.remat ? take(st.ls.bytes) : nullptr;
   st.tx.resize(kTxBuffers);
   for (auto& t : st.tx) t.p = take(T * m.d * e);
   st.cot.resize(kCotBuffers);
@@ -220,6 +224,35 @@ const void* pptr(const jpp_stage& st, int v, long off) {
 }
 float* gptr(const jpp_stage& st, int v, long off) { return off < 0 ? nullptr : st.grads[v] + off; }
 
+// Forward of layer l of local stage v on stream s: input x, every intermediate at the
+// LayerStash offsets from b, output to y (y == nullptr: the last GEMM is skipped, which is
+// all the backward needs when it recomputes a layer).
+hipError_t layer_forward(jpp_stage& st, hipStream_t s, int v, int l, char* x, char* b, char* y) {
+  const Dims& m = st.dm;
+  const jpp_layer_config& c = st.cfg;
+  const int dt = c.dtype;
+  const auto& o = st.loff[l];
+  K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, x, pptr(st, v, o.ln1_g), pptr(st, v, o.ln1_b),
+                        b + st.ls.n1, (float*)(b + st.ls.stats1), s));
+  K_TRY(gemm(st, s, m.T, m.nqkv, m.d, b + st.ls.n1, m.d, false, pptr(st, v, o.wqkv), m.d, false, b + st.ls.qkv,
+             m.nqkv, OUT_STORE, pptr(st, v, o.bqkv), nullptr));
+  if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, st.rope_table, false, s));
+  AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
+             nullptr, nullptr, nullptr};
+  K_TRY(attention_fwd(st, s, a));
+  K_TRY(gemm(st, s, m.T, m.d, m.nq, b + st.ls.O, m.nq, false, pptr(st, v, o.wo), m.nq, false, b + st.ls.x1, m.d,
+             OUT_STORE, pptr(st, v, o.bo), x));
+  K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, b + st.ls.x1, pptr(st, v, o.ln2_g),
+                        pptr(st, v, o.ln2_b), b + st.ls.n2, (float*)(b + st.ls.stats2), s));
+  K_TRY(gemm(st, s, m.T, m.f1, m.d, b + st.ls.n2, m.d, false, pptr(st, v, o.w1), m.d, false, b + st.ls.h, m.f1,
+             OUT_STORE, pptr(st, v, o.b1), nullptr));
+  K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, b + st.ls.h, b + st.ls.a, s));
+  if (y)
+    K_TRY(gemm(st, s, m.T, m.d, m.f, b + st.ls.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
+               pptr(st, v, o.b2), b + st.ls.x1));
+  return hipSuccess;
+}
+
 // Forward of all layers (and the loss head) of local stage v for microbatch i, reading the
 // input from the slot and writing the output to `y_out` (ignored for a loss-head stage).
 hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out) {
@@ -227,32 +260,12 @@ hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out)
   const jpp_layer_config& c = st.cfg;
   hipStream_t s = st.cs;
   const int dt = c.dtype;
+  char* hb = st.x_of(slot, m.L);   // head stash
   for (int l = 0; l < m.L; ++l) {
-    char* b = slot.base + (size_t)l * st.ls.bytes;
-    const auto& o = st.loff[l];
-    char* x = b + st.ls.x;
-    char* y = (l + 1 < m.L) ? slot.base + (size_t)(l + 1) * st.ls.bytes + st.ls.x
-                            : (st.is_head(v) ? slot.base + (size_t)m.L * st.ls.bytes + st.hs.yL : y_out);
-    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, x, pptr(st, v, o.ln1_g), pptr(st, v, o.ln1_b),
-                          b + st.ls.n1, (float*)(b + st.ls.stats1), s));
-    K_TRY(gemm(st, s, m.T, m.nqkv, m.d, b + st.ls.n1, m.d, false, pptr(st, v, o.wqkv), m.d, false, b + st.ls.qkv,
-               m.nqkv, OUT_STORE, pptr(st, v, o.bqkv), nullptr));
-    if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, st.rope_table, false, s));
-    AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
-               nullptr, nullptr, nullptr};
-    K_TRY(attention_fwd(st, s, a));
-    K_TRY(gemm(st, s, m.T, m.d, m.nq, b + st.ls.O, m.nq, false, pptr(st, v, o.wo), m.nq, false, b + st.ls.x1, m.d,
-               OUT_STORE, pptr(st, v, o.bo), x));
-    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, b + st.ls.x1, pptr(st, v, o.ln2_g),
-                          pptr(st, v, o.ln2_b), b + st.ls.n2, (float*)(b + st.ls.stats2), s));
-    K_TRY(gemm(st, s, m.T, m.f1, m.d, b + st.ls.n2, m.d, false, pptr(st, v, o.w1), m.d, false, b + st.ls.h, m.f1,
-               OUT_STORE, pptr(st, v, o.b1), nullptr));
-    K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, b + st.ls.h, b + st.ls.a, s));
-    K_TRY(gemm(st, s, m.T, m.d, m.f, b + st.ls.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
-               pptr(st, v, o.b2), b + st.ls.x1));
+    char* y = (l + 1 < m.L) ? st.x_of(slot, l + 1) : (st.is_head(v) ? hb + st.hs.yL : y_out);
+    K_TRY(layer_forward(st, s, v, l, st.x_of(slot, l), st.rest_of(slot, l, false), y));
   }
   if (st.is_head(v)) {
-    char* hb = slot.base + (size_t)m.L * st.ls.bytes;
     K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, hb + st.hs.yL, pptr(st, v, st.lnf_g),
                           pptr(st, v, st.lnf_b), hb + st.hs.nf, (float*)(hb + st.hs.statsf), s));
     K_TRY(gemm(st, s, m.T, m.vocab, m.d, hb + st.hs.nf, m.d, false, pptr(st, v, st.w_head), m.d, false, st.z,
@@ -286,7 +299,7 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
   // gradients, which read them, must be done
   if (st.w_task.recorded) K_TRY(hipStreamWaitEvent(s, st.w_task.ev, 0));
   if (st.is_head(v)) {
-    char* hb = slot.base + (size_t)m.L * st.ls.bytes;
+    char* hb = st.x_of(slot, m.L);
     K_TRY(wgrad(st, m.vocab, m.d, m.T, hb + st.hs.dz, m.vocab, hb + st.hs.nf, m.d, gptr(st, v, st.w_head)));
     K_TRY(gemm(st, s, m.T, m.d, m.vocab, hb + st.hs.dz, m.vocab, false, pptr(st, v, st.w_head), m.d, true, st.dn,
                m.d, OUT_STORE, nullptr, nullptr));
@@ -297,14 +310,18 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
     cur ^= 1;
   }
   for (int l = m.L - 1; l >= 0; --l) {
-    char* b = slot.base + (size_t)l * st.ls.bytes;
+    char* b = st.rest_of(slot, l, true);
+    char* xl = st.x_of(slot, l);
     const auto& o = st.loff[l];
     char* dx = (l == 0) ? dx_out : st.dbuf[cur];
     if (l != m.L - 1) {
-      // the layer above's weight gradients read dh, dx1, dqkv, which this layer rewrites
+      // the layer above's weight gradients read dh, dx1, dqkv (and, with rematerialisation,
+      // the recomputed activations), which this layer rewrites
       K_TRY(hipEventRecord(st.w_layer.ev, st.ws));
       K_TRY(hipStreamWaitEvent(s, st.w_layer.ev, 0));
     }
+    // Section 2.2.1, rematerialisation: only the layer's input was kept; run its forward again
+    if (c.remat) K_TRY(layer_forward(st, s, v, l, xl, b, nullptr));
     // FFN down projection
     K_TRY(wgrad(st, m.d, m.f, m.T, dy, m.d, b + st.ls.a, m.f, gptr(st, v, o.w2)));
     if (o.b2 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dy, m.d, gptr(st, v, o.b2), st.partial, s));
@@ -332,7 +349,7 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
     if (o.bqkv >= 0) K_TRY(launch_bias_grad(dt, m.T, m.nqkv, st.dqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
     K_TRY(gemm(st, s, m.T, m.d, m.nqkv, st.dqkv, m.nqkv, false, pptr(st, v, o.wqkv), m.d, true, st.dn, m.d,
                OUT_STORE, nullptr, nullptr));
-    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, b + st.ls.x, pptr(st, v, o.ln1_g), (float*)(b + st.ls.stats1),
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, xl, pptr(st, v, o.ln1_g), (float*)(b + st.ls.stats1),
                           st.dn, st.dx1, dx, gptr(st, v, o.ln1_g), gptr(st, v, o.ln1_b), st.partial, s));
     dy = dx;
     cur ^= 1;
@@ -401,7 +418,7 @@ hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* out
 hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes, hipEvent_t produced) {
   if (produced) K_TRY(hipStreamWaitEvent(st.ss, produced, 0));  // the sending actor's copy
   if (slot.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, slot.freed.ev, 0));
-  K_TRY(hipMemcpyAsync(slot.base + st.ls.x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
+  K_TRY(hipMemcpyAsync(st.x_of(slot, 0), src, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(slot.rx.ev, st.ss));
   slot.rx_issued = true;
   return hipSuccess;

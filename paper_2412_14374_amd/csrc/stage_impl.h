@@ -79,6 +79,21 @@ struct jpp_stage {
   LayerStash ls{};
   HeadStash hs{};
   size_t slot_bytes = 0;
+  // Rematerialisation: a slot then holds only the layers' inputs (xbytes each, then the head
+  // stash); everything else of a layer lives in one of two workspaces laid out like a layer
+  // stash, remat_f for the forward stream and remat_b for the backward's recomputation.
+  size_t xbytes = 0;
+  char *remat_f = nullptr, *remat_b = nullptr;
+  // input of layer l of the stash in `slot` (l == n_layers: start of the head stash)
+  char* x_of(const Slot& slot, int l) const {
+    if (cfg.remat) return slot.base + (size_t)l * xbytes;
+    return slot.base + (size_t)l * ls.bytes + (l < cfg.n_layers ? ls.x : 0);
+  }
+  // base for every other LayerStash offset of layer l
+  char* rest_of(const Slot& slot, int l, bool backward) const {
+    if (cfg.remat) return backward ? remat_b : remat_f;
+    return slot.base + (size_t)l * ls.bytes;
+  }
   std::vector<Slot> slots;
   std::vector<TxBuf> tx;
   std::vector<CotBuf> cot;

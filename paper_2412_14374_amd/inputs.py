@@ -43,6 +43,7 @@ class Workload:
     norm_eps: float = 1e-5
     loss_head: int = 0
     vocab: int = 0
+    remat: int = 0                   # 1: keep only each layer's input, recompute in the backward
     # schedule: kind, pipeline depth P, this actor's rank, virtual stages V
     sched: int = SCHED_GPIPE
     P: int = 1

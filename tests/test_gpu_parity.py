@@ -141,6 +141,46 @@ def test_bf16_twins_match_oracle(name):
     st.close()
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C5"])
+def test_rematerialisation_changes_memory_not_bits(name):
+    """Section 2.2.1: rematerialisation trades memory for recomputation and nothing else.  With
+    remat = 1 the forward keeps only each layer's input and the backward re-runs the layer:
+    outputs, input cotangents and accumulated gradients must be the bits of the run without
+    it (and so match the oracle), while the arena shrinks."""
+    from dataclasses import replace
+    w = inp.C1 if name == "C1" else TWINS[name]
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec),
+                                               so.head_param_shapes(spec) if w.loss_head else None, seed=9,
+                                               perturb=True)
+    outs, arena = [], []
+    for remat in (0, 1):
+        st = Stage(replace(w, remat=remat))
+        st.set_params_host(params)
+        st.bind(x, cot, tg)
+        st.zero_grads()
+        st.run()
+        st.sync()
+        torch.cuda.synchronize()
+        outs.append(([st.grads_tensor(v).cpu() for v in range(len(w.stage_ids))],
+                     [t.cpu().clone() for t in st.out_y], [t.cpu().clone() for t in st.out_dx],
+                     st.losses() if w.loss_head else None, st.results() if remat else None))
+        arena.append(B.jpp_stage_arena_bytes(st.cfg, st.M, st.max_in_flight))
+        st.close()
+    for a, b in zip(outs[0][0], outs[1][0]):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    for k in (1, 2):
+        for a, b in zip(outs[0][k], outs[1][k]):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    if w.loss_head:
+        assert np.array_equal(outs[0][3], outs[1][3])
+    assert arena[1] < arena[0]
+    ref = so.run_task_list(spec, params, oracle_tasks(B.jpp_schedule_make(w.sched, w.P, w.rank, w.V, w.n_microbatches)),
+                           x, cot, tg)
+    worst, err = compare(w, outs[1][4], ref)
+    assert err <= TOL[w.dtype], (worst, err)
+
+
 def test_gradients_bit_identical_across_schedules_and_runs():
     """Section 2.2.1: schedules only reorder tasks.  With the per-stage backward order kept,
     the fp32 accumulation G <- G + g_i has one association, so GPipe, 1F1B at every rank and a
