@@ -241,6 +241,18 @@ jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, i
                        const void* B, int ldb, int b_kstrided, void* C, int ldc, int out_mode,
                        const void* bias, const void* residual, void* stream);
 
+/* jpp_op_gemm with a scratch buffer (device, fp32, 16-byte aligned, caller-owned, not shared
+ * by launches that may overlap).  bf16 store modes only use it: when the last round of output
+ * tiles would fill at most half of the GPU, those tiles are cut into 2..8 ranges of k, the
+ * partial tiles go to the scratch and a second kernel sums them in ascending k order and
+ * applies bias / residual / rounding.  jpp_op_gemm_workspace_bytes returns the bytes a shape
+ * needs (0: never split); with less (or NULL) the launch is the unsplit one. */
+size_t jpp_op_gemm_workspace_bytes(int dtype, int M, int N, int K, int out_mode);
+jpp_status jpp_op_gemm_ws(int dtype, int M, int N, int K, const void* A, int lda, int a_kstrided,
+                          const void* B, int ldb, int b_kstrided, void* C, int ldc, int out_mode,
+                          const void* bias, const void* residual, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
 /* Benchmarking knob: 0 (default) lets the library pick the bf16 GEMM tile configuration
  * from the problem size; 1..8 force one (tile M x N x K-stage, LDS stages, waves):
  * 1 = 256x256x32, 4, 4;  2 = 256x256x32, 5, 4;  3 = 128x128x32, 4, 4;  4 = 256x256x64, 2, 4;

@@ -68,6 +68,10 @@ _SIGNATURES = {
     "jpp_stage_host_syncs": (C.c_int, [C.c_void_p]),
     "jpp_last_error": (C.c_char_p, []),
     "jpp_set_gemm_variant": (None, [C.c_int]),
+    "jpp_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int] * 5),
+    "jpp_op_gemm_ws": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                  C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "jpp_op_gemm": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
                               C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "jpp_op_attention_fwd": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 4),
@@ -286,6 +290,16 @@ def jpp_set_gemm_variant(v):
 def jpp_op_gemm(dtype, M, N, K, A, lda, a_ks, B, ldb, b_ks, Cp, ldc, out_mode, bias, residual, stream):
     _check(lib().jpp_op_gemm(dtype, M, N, K, A, lda, int(a_ks), B, ldb, int(b_ks), Cp, ldc, out_mode, bias,
                              residual, stream))
+
+
+def jpp_op_gemm_workspace_bytes(dtype, M, N, K, out_mode):
+    return lib().jpp_op_gemm_workspace_bytes(dtype, M, N, K, out_mode)
+
+
+def jpp_op_gemm_ws(dtype, M, N, K, A, lda, a_ks, B, ldb, b_ks, Cp, ldc, out_mode, bias, residual, workspace,
+                   workspace_bytes, stream):
+    _check(lib().jpp_op_gemm_ws(dtype, M, N, K, A, lda, int(a_ks), B, ldb, int(b_ks), Cp, ldc, out_mode, bias,
+                                residual, workspace, workspace_bytes, stream))
 
 
 def jpp_op_attention_fwd(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, stream):

@@ -36,7 +36,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-constexpr int kTileBytes = 64 * HD * 2;  // a 64-row tile of one head: 16 KiB in either layout
+constexpr int kTileBytes = 64 * HD * 2;
+constexpr f32x16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // a 64-row tile of one head: 16 KiB in either layout
 
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, long long bytes) {
   const uint32_t n = bytes > 0x7FFFFF00LL ? 0x7FFFFF00u : (bytes < 0 ? 0u : (uint32_t)bytes);
@@ -44,6 +45,11 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, long long byte
 }
 
 __device__ inline int swz7(int row) { return (row ^ (row >> 3)) & 7; }
+
+// 2^x by the hardware instruction alone (arguments here are <= 0 or masked; results below the
+// normal range flush to zero, which is what the sums want).  The library exp2f wraps the same
+// instruction in range scaling that triples its cost.
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- tile staging ------------------------------------------------------------------------
 // "Row" tile: [64 rows][128 d], 256 bytes per row, 16-byte chunk c stored at c ^ (row & 7).
@@ -65,8 +71,10 @@ __device__ inline void load_row_tile(char* tile, const bf16* base, int ld, int v
 
 // "Transposed" tile: [128 d][64 rows], 128 bytes per d, rows permuted inside each group of 16
 // (bits 2 and 3 of the row index swapped), 16-byte chunk c stored at c ^ swz7(d).
-// A thread loads 4 rows x 8 d (four 16-byte loads), transposes in registers and writes eight
-// 8-byte runs of 4 rows.
+// A thread loads 4 rows x 8 d (four 16-byte loads) into registers; from there the block is
+// written as four 16-byte chunks of a row tile (store_rows) or, transposed in registers, as
+// eight 8-byte runs of 4 rows of a transposed tile (store).  Issuing the loads of the next
+// tile before the current one is multiplied hides the memory latency behind the MFMAs.
 struct TransposedStage {
   u32x4 regs[4];
   __device__ inline void issue(const bf16* base, int ld, int valid, long long bytes_left) {
@@ -77,6 +85,14 @@ struct TransposedStage {
       const int row = rg * 4 + j;
       const uint32_t off = row < valid ? (uint32_t)(row * ld + db * 8) * 2u : kOOB;
       regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+    }
+  }
+  __device__ inline void store_rows(char* tile) const {
+    const int db = threadIdx.x & 15, rg = threadIdx.x >> 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = rg * 4 + j;
+      *reinterpret_cast<u32x4*>(tile + row * 256 + ((db ^ (row & 7)) << 4)) = regs[j];
     }
   }
   __device__ inline void store(char* tile) const {
@@ -160,59 +176,66 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* 
 
   const int q_end = min(q0 + 128, seq);      // keys needed: 0 .. q_end-1
   const int n_tiles = (q_end + 63) / 64;
+  TransposedStage ks, vs;
+  auto fetch = [&](int t) {
+    const int kv0 = t * 64;
+    const long long left_k = total_bytes - (long long)((kbase + (size_t)kv0 * ld) - qkv) * 2;
+    ks.issue(kbase + (size_t)kv0 * ld, ld, seq - kv0, left_k);
+    vs.issue(vbase + (size_t)kv0 * ld, ld, seq - kv0, left_k - (long long)Hkv * HD * 2);
+  };
+  fetch(0);
   for (int t = 0; t < n_tiles; ++t) {
     const int kv0 = t * 64;
-    __syncthreads();
-    const long long left_k = total_bytes - (long long)((kbase + (size_t)kv0 * ld) - qkv) * 2;
-    load_row_tile(k_tile, kbase + (size_t)kv0 * ld, ld, seq - kv0, left_k);
-    TransposedStage vs;
-    vs.issue(vbase + (size_t)kv0 * ld, ld, seq - kv0, left_k - (long long)Hkv * HD * 2);
+    __syncthreads();                          // every wave is done with the previous tile
+    ks.store_rows(k_tile);
     vs.store(vt_tile);
     __syncthreads();
+    if (t + 1 < n_tiles) fetch(t + 1);        // in flight while this tile is multiplied
     if (kv0 > qw0 + 31) continue;             // every key of this tile is in this wave's future
     f32x16 s[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, 0, l32, half), qf[0], kZero16, 0, 0, 0);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[i][r] = 0.f;
-#pragma unroll
-    for (int kd = 0; kd < 8; ++kd)
+    for (int kd = 1; kd < 8; ++kd)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
         s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, kd, l32, half), qf[kd], s[i], 0, 0, 0);
-    // s[i][r] = q(qw0 + l32) . k(kv0 + 32 i + 8 (r/4) + 4 half + r%4)
-    const bool need_mask = kv0 + 63 > qw0;
-    float mx = -INFINITY;
+    // s[i][r] = q(qw0 + l32) . k(kv0 + 32 i + 8 (r/4) + 4 half + r%4), unscaled
+    if (kv0 + 63 > qw0) {                     // only tiles that cross the diagonal need the mask
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
+          if (key > qrow) s[i][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = s[i][r] * sl2;
-        if (need_mask) {
-          const int key = kv0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (key > qrow) v = -INFINITY;
-        }
-        s[i][r] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mnew = fmaxf(m, mx);          // finite: key kv0 <= qw0 + 31 ... and key 0 <= any query
-    const float alpha = exp2f(m - mnew);
+      for (int r = 0; r < 16; ++r) mx = __builtin_fmaxf(mx, s[i][r]);
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // the scale is positive, so it commutes with the maximum; m is kept in scaled log2 units
+    const float mnew = __builtin_fmaxf(m, mx * sl2);   // finite: key kv0 <= qw0 + 31 and key 0 <= any query
+    const float alpha = fast_exp2(m - mnew);
     float psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[i][r] - mnew);
+        const float p = fast_exp2(__builtin_fmaf(s[i][r], sl2, -mnew));
         s[i][r] = p;
         psum += p;
       }
     l = l * alpha + psum;
     m = mnew;
+    if (__any(alpha != 1.f)) {                // late tiles rarely move the maximum
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
 #pragma unroll
     for (int sk = 0; sk < 4; ++sk) {
       const bf16x8 pf = acc_frag(s[sk >> 1], sk & 1);
@@ -332,27 +355,40 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
       if (qt0 + 63 < kw0) continue;            // every query of this tile precedes this wave's keys
       f32x16 s[2], dp[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i) {
+        s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(q_tile, i, 0, l32, half), kf[0], kZero16, 0, 0, 0);
+        dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(do_tile, i, 0, l32, half), vf[0], kZero16, 0, 0, 0);
+      }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[i][r] = 0.f; dp[i][r] = 0.f; }
-#pragma unroll
-      for (int kd = 0; kd < 8; ++kd)
+      for (int kd = 1; kd < 8; ++kd)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
           s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(q_tile, i, kd, l32, half), kf[kd], s[i], 0, 0, 0);
           dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(do_tile, i, kd, l32, half), vf[kd], dp[i], 0, 0, 0);
         }
       // s[i][r]: query qt0 + 32 i + 8 (r/4) + 4 half + r%4, key kw0 + l32
-      const bool need_mask = qt0 < kw0 + 31;
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int ql = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-          float p = exp2f(s[i][r] * sl2 - lse_s[ql]);
-          if (need_mask && qt0 + ql < krow) p = 0.f;
-          s[i][r] = p;
-          dp[i][r] = p * (dp[i][r] - delta_s[ql]);
+          s[i][r] = fast_exp2(__builtin_fmaf(s[i][r], sl2, -lse_s[ql]));
+        }
+      if (qt0 < kw0 + 31) {                    // only tiles that cross the diagonal need the mask
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int ql = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (qt0 + ql < krow) s[i][r] = 0.f;
+          }
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ql = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
+          dp[i][r] = s[i][r] * (dp[i][r] - delta_s[ql]);
         }
 #pragma unroll
       for (int sk = 0; sk < 4; ++sk) {
@@ -438,28 +474,34 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
     if (kv0 > qw0 + 31) continue;
     f32x16 s[2], dp[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+      s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, 0, l32, half), qf[0], kZero16, 0, 0, 0);
+      dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(v_tile, i, 0, l32, half), dof[0], kZero16, 0, 0, 0);
+    }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s[i][r] = 0.f; dp[i][r] = 0.f; }
-#pragma unroll
-    for (int kd = 0; kd < 8; ++kd)
+    for (int kd = 1; kd < 8; ++kd)
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, kd, l32, half), qf[kd], s[i], 0, 0, 0);
         dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(v_tile, i, kd, l32, half), dof[kd], dp[i], 0, 0, 0);
       }
-    const bool need_mask = kv0 + 63 > qw0;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = exp2f(s[i][r] * sl2 - lse2);
-        if (need_mask) {
+      for (int r = 0; r < 16; ++r) s[i][r] = fast_exp2(__builtin_fmaf(s[i][r], sl2, -lse2));
+    if (kv0 + 63 > qw0) {                     // only tiles that cross the diagonal need the mask
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
           const int key = kv0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (key > qrow) p = 0.f;
+          if (key > qrow) s[i][r] = 0.f;
         }
-        dp[i][r] = p * (dp[i][r] - dlt);
-      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dp[i][r] = s[i][r] * (dp[i][r] - dlt);
 #pragma unroll
     for (int sk = 0; sk < 4; ++sk) {
       const bf16x8 dsf = acc_frag(dp[sk >> 1], sk & 1);

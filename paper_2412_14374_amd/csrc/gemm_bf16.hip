@@ -87,9 +87,14 @@ __device__ inline uint32_t lds_addr_of(const void* p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const char*)p;
 }
 
+constexpr int kCus = 256;   // compute units of the MI355X
+
 struct Epilogue {
   void* C; int ldc; int out_mode;
   const bf16* bias; const bf16* residual;
+  // Split tail (see launch_cfg): workgroups with id >= split_first each compute one of
+  // split_s k-ranges of a tile and store the fp32 partial tile to split_ws; 0 = no splitting.
+  int split_first; int split_s; float* split_ws;
 };
 
 struct Operand {
@@ -271,8 +276,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   };
 
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  int pid = blockIdx.x, part = -1, kbeg = 0;
+  int nk = (K + BKT - 1) / BKT;
+  if (ep.split_s > 0 && pid >= ep.split_first) {
+    const int j = pid - ep.split_first;
+    pid = ep.split_first + j / ep.split_s;
+    part = j % ep.split_s;
+    const int per = (nk + ep.split_s - 1) / ep.split_s;
+    kbeg = part * per;
+    nk = (nk < kbeg + per ? nk : kbeg + per) - kbeg;   // > 0: the host sizes split_s so
+  }
   int tm, tn;
-  tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn);
+  tile_of(pid, tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -296,8 +311,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   bf16x8 af[2][MI], bfr[2][NI];
   // one load of k-tile kt (A loads first, then B loads) into the stage at LDS address dst
   auto issue_load = [&](int kt, uint32_t dst, int idx) {
-    if (idx < TA::kLoads) TA::issue_one(A, m0, kt * BKT, K, dst, idx);
-    else TB::issue_one(B, n0, kt * BKT, K, dst + kABytes, idx - TA::kLoads);
+    if (idx < TA::kLoads) TA::issue_one(A, m0, (kbeg + kt) * BKT, K, dst, idx);
+    else TB::issue_one(B, n0, (kbeg + kt) * BKT, K, dst + kABytes, idx - TA::kLoads);
   };
   auto mfma_row = [&](int set, int i) {
 #pragma unroll
@@ -326,7 +341,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   constexpr int kWaitSteady = NS == 2 ? 0 : (NS - 3) * kLoadsPerStage + kIssuedBeforeBarrier;
   static_assert(kWaitSteady < 64, "too many loads in flight for the 6-bit vmcnt");
 
-  const int nk = (K + BKT - 1) / BKT;
   if constexpr (VG) {
     // Register-staged loads (two LDS stages): tile kt+2 travels in registers while tile kt is
     // multiplied; at the start of iteration kt the registers (tile kt+1, loaded one iteration
@@ -337,8 +351,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
     constexpr int kBefore = (KSTEPS - 1) * MI + MI / 2;      // groups before the barrier
     u32x4 regs[L];
     auto vload = [&](int kt, int idx) {
-      regs[idx] = idx < TA::kLoads ? TA::load_one(A, m0, kt * BKT, K, idx)
-                                   : TB::load_one(B, n0, kt * BKT, K, idx - TA::kLoads);
+      regs[idx] = idx < TA::kLoads ? TA::load_one(A, m0, (kbeg + kt) * BKT, K, idx)
+                                   : TB::load_one(B, n0, (kbeg + kt) * BKT, K, idx - TA::kLoads);
     };
     auto vstore = [&](char* dst, int idx) {
       if (idx < TA::kLoads) TA::store_one(dst, idx, regs[idx]);
@@ -444,6 +458,28 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   static_assert(kWavesPerStage >= 1 && kWavesPerStage * NS >= NT / 64, "epilogue staging must fit in LDS");
   float* stg = reinterpret_cast<float*>(stage(wave / kWavesPerStage) + (wave % kWavesPerStage) * kRegion);
   const int erow = lane / LPR, ecol = (lane % LPR) * 4;
+  if (part >= 0) {
+    // k-range of a split tile: the whole fp32 tile goes to its slot of the workspace, row
+    // major with BN columns; bias, residual and the conversion happen in the fix-up kernel
+    float* dst = ep.split_ws + ((size_t)(pid - ep.split_first) * ep.split_s + part) * (size_t)(BM * BN);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      wave_lds_sync();
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          stg[(8 * (r >> 2) + 4 * half + (r & 3)) * LDW + j * 32 + l32] = acc[i][j][r];
+      wave_lds_sync();
+#pragma unroll
+      for (int st = 0; st < kSteps; ++st) {
+        const int row = wm * TM + i * 32 + st * RPI + erow;
+        *reinterpret_cast<f32x4*>(dst + (size_t)row * BN + wn * TN + ecol) =
+            *reinterpret_cast<const f32x4*>(stg + (st * RPI + erow) * LDW + ecol);
+      }
+    }
+    return;
+  }
   const int n = n0 + wn * TN + ecol;
   const bool n_ok = n < N;
   f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
@@ -497,14 +533,91 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   }
 }
 
+// Sums the split_s partial tiles of every split tile in ascending k order, adds bias and
+// residual and stores in the output mode.  One thread per 4 consecutive columns.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_split_fixup_kernel(int M, int N, Epilogue ep, int n_split) {
+  constexpr int kQuads = BM * BN / 4;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  for (long long q = blockIdx.x * 256LL + threadIdx.x; q < (long long)n_split * kQuads; q += 256LL * gridDim.x) {
+    const int t = (int)(q / kQuads), e = (int)(q % kQuads);
+    const int row = e / (BN / 4), col = (e % (BN / 4)) * 4;
+    int tm, tn;
+    tile_of(ep.split_first + t, tiles_m, tiles_n, tm, tn);
+    const int m = tm * BM + row, n = tn * BN + col;
+    if (m >= M || n >= N) continue;
+    const float* src = ep.split_ws + (size_t)t * ep.split_s * (size_t)(BM * BN) + (size_t)row * BN + col;
+    f32x4 v = *reinterpret_cast<const f32x4*>(src);
+    for (int p = 1; p < ep.split_s; ++p) v += *reinterpret_cast<const f32x4*>(src + (size_t)p * (BM * BN));
+    const size_t idx = (size_t)m * ep.ldc + n;
+    if (ep.bias) {
+      const bf16x4 b = *reinterpret_cast<const bf16x4*>(ep.bias + n);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[c] += (float)b[c];
+    }
+    if (ep.residual) {
+      const bf16x4 rv = *reinterpret_cast<const bf16x4*>(ep.residual + idx);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[c] += (float)rv[c];
+    }
+    if (ep.out_mode == OUT_STORE) {
+      bf16x4 o;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) o[c] = (bf16)v[c];
+      *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(ep.C) + idx) = o;
+    } else {
+      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = v;
+    }
+  }
+}
+
+// How the tail of a launch is split.  A launch of `tiles` workgroups runs in rounds of `slots`
+// (CUs x workgroups per CU); when the last round is at most half full its tiles are cut into
+// s k-ranges each, so that the round is as short as 1/s of a full one.
+struct SplitPlan { int first; int s; size_t bytes; };
+template <int BM, int BN, int BKT, int WGS_PER_CU>
+SplitPlan plan_split(int M, int N, int K, int out_mode) {
+  SplitPlan p{0, 0, 0};
+  if (out_mode == OUT_ACC_F32) return p;   // many rounds, and G must be added to exactly once
+  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const int slots = kCus * WGS_PER_CU;
+  const int rem = tiles % slots;
+  const int nk = (K + BKT - 1) / BKT;
+  if (rem == 0 || rem * 2 > slots) return p;
+  int s = slots / rem;
+  if (s > 8) s = 8;
+  if (s > nk / 4) s = nk / 4;              // at least 4 k-steps per part
+  if (s < 2) return p;
+  const int per = (nk + s - 1) / s;
+  s = (nk + per - 1) / per;                // no empty part
+  if (s < 2) return p;
+  p.first = tiles - rem;
+  p.s = s;
+  p.bytes = (size_t)rem * s * BM * BN * 4;
+  return p;
+}
+
 template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false>
 hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   constexpr int NT = 64 * WM * WN;
+  constexpr int kWgsPerCu = BM * BN >= 256 * 256 ? 1 : 2;
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   Operand A{(const bf16*)g.A, g.lda, g.M};
   Operand B{(const bf16*)g.B, g.ldb, g.N};
-  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual};
-  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG><<<tiles, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
+  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual, 0, 0, nullptr};
+  int grid = tiles;
+  const SplitPlan sp = plan_split<BM, BN, BKT, kWgsPerCu>(g.M, g.N, g.K, g.out_mode);
+  const bool split = g.workspace && sp.s >= 2 && sp.bytes <= g.workspace_bytes;
+  if (split) {
+    ep.split_first = sp.first; ep.split_s = sp.s; ep.split_ws = (float*)g.workspace;
+    grid = sp.first + (tiles - sp.first) * sp.s;
+  }
+  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG><<<grid, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
+  if (split) {
+    const long long quads = (long long)(tiles - sp.first) * (BM * BN / 4);
+    const int blocks = (int)((quads + 255) / 256 < 4096 ? (quads + 255) / 256 : 4096);
+    gemm_split_fixup_kernel<BM, BN><<<blocks, 256, 0, s>>>(g.M, g.N, ep, tiles - sp.first);
+  }
   return hipGetLastError();
 }
 
@@ -542,6 +655,13 @@ bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why) {
 }
 
 void set_gemm_variant(int v) { g_variant = v; }
+
+size_t gemm_bf16_workspace_bytes(int M, int N, int K, int out_mode) {
+  // mirrors the automatic choice of launch_gemm_bf16
+  const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  if (big_tiles >= 192) return plan_split<256, 256, 64, 1>(M, N, K, out_mode).bytes;
+  return plan_split<128, 128, 64, 2>(M, N, K, out_mode).bytes;
+}
 
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
   switch (g_variant) {

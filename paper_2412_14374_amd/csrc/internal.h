@@ -29,10 +29,16 @@ struct GemmDesc {
   void* C; int ldc; int out_mode;
   const void* bias;      // storage dtype [N] or null
   const void* residual;  // storage dtype, leading dimension ldc, or null
+  // Optional fp32 scratch (bf16 GEMM, store modes): when given and large enough
+  // (gemm_bf16_workspace_bytes), the tiles of a mostly empty last round of workgroups are
+  // split along k and summed by a second kernel.  Must not be shared by concurrent launches.
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
 };
 hipError_t launch_gemm_f32(const GemmDesc& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s);
 bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why);
+size_t gemm_bf16_workspace_bytes(int M, int N, int K, int out_mode);  // 0: this shape is never split
 void set_gemm_variant(int v);  // 0 = automatic tile selection; 1..3 force a configuration (benchmarking)
 
 struct AttnDesc {

@@ -16,11 +16,26 @@ void jpp_set_gemm_variant(int variant) { set_gemm_variant(variant); }
 jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, int a_kstrided, const void* B,
                        int ldb, int b_kstrided, void* C, int ldc, int out_mode, const void* bias,
                        const void* residual, void* stream) {
+  return jpp_op_gemm_ws(dtype, M, N, K, A, lda, a_kstrided, B, ldb, b_kstrided, C, ldc, out_mode, bias, residual,
+                        nullptr, 0, stream);
+}
+
+size_t jpp_op_gemm_workspace_bytes(int dtype, int M, int N, int K, int out_mode) {
+  if (dtype != JPP_BF16 || M < 1 || N < 1 || K < 1) return 0;
+  return gemm_bf16_workspace_bytes(M, N, K, out_mode);
+}
+
+jpp_status jpp_op_gemm_ws(int dtype, int M, int N, int K, const void* A, int lda, int a_kstrided, const void* B,
+                          int ldb, int b_kstrided, void* C, int ldc, int out_mode, const void* bias,
+                          const void* residual, void* workspace, size_t workspace_bytes, void* stream) {
   if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
+  if (workspace && ((uintptr_t)workspace % 16) != 0) return fail(JPP_EINVAL, "workspace must be 16-byte aligned");
   if (!A || !B || !C) return fail(JPP_EINVAL, "null operand");
   if (M < 1 || N < 1 || K < 1) return fail(JPP_EINVAL, "sizes must be positive");
   if (out_mode < OUT_STORE || out_mode > OUT_ACC_F32) return fail(JPP_EINVAL, "bad out_mode");
   GemmDesc g{M, N, K, A, lda, a_kstrided != 0, B, ldb, b_kstrided != 0, C, ldc, out_mode, bias, residual};
+  g.workspace = workspace;
+  g.workspace_bytes = workspace ? workspace_bytes : 0;
   hipError_t e;
   if (dtype == JPP_BF16) {
     std::string why;

@@ -185,6 +185,18 @@ size_t carve(jpp_stage& st, char* base) {
     st.z = (float*)take(T * m.vocab * 4);
     st.row_loss = (float*)take(T * 4);
   }
+  // scratch for GEMMs whose last round of tiles is split along k: the largest need over the
+  // store-mode GEMM shapes of this stage (forward, and input gradient = same M with N, K swapped)
+  st.split_bytes = 0;
+  if (c.dtype == JPP_BF16) {
+    const int shapes[][2] = {{m.nqkv, m.d}, {m.d, m.nq}, {m.f1, m.d}, {m.d, m.f}, {c.loss_head ? m.vocab : 8, m.d}};
+    for (const auto& nk : shapes) {
+      st.split_bytes = std::max(st.split_bytes, gemm_bf16_workspace_bytes(m.T, nk[0], nk[1], OUT_STORE));
+      st.split_bytes = std::max(st.split_bytes, gemm_bf16_workspace_bytes(m.T, nk[1], nk[0], OUT_STORE));
+    }
+  }
+  st.split_f = st.split_bytes ? take(st.split_bytes) : nullptr;
+  st.split_b = st.split_bytes ? take(st.split_bytes) : nullptr;
   return off;
 }
 
@@ -201,6 +213,9 @@ hipError_t gemm(const jpp_stage& st, hipStream_t s, int M, int N, int K, const v
                 const void* B, int ldb, bool bks, void* C, int ldc, int mode, const void* bias,
                 const void* residual) {
   GemmDesc g{M, N, K, A, lda, aks, B, ldb, bks, C, ldc, mode, bias, residual};
+  // one scratch per stream: launches on one stream are serial, the streams are not
+  g.workspace = s == st.cs ? st.split_f : (s == st.bs ? st.split_b : nullptr);
+  g.workspace_bytes = g.workspace ? st.split_bytes : 0;
   return st.cfg.dtype == JPP_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
 }
 

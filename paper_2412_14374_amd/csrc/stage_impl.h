@@ -101,6 +101,9 @@ struct jpp_stage {
   char *dbuf[2] = {nullptr, nullptr}, *da = nullptr, *dh = nullptr, *dn = nullptr, *dx1 = nullptr, *dO = nullptr,
        *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr, *z = nullptr, *row_loss = nullptr;
+  // GEMM split scratch, one per stream that launches store-mode GEMMs (forward, backward chain)
+  char *split_f = nullptr, *split_b = nullptr;
+  size_t split_bytes = 0;
 
   // boundary
   std::vector<const void*> inbox_x, inbox_cot;

@@ -112,6 +112,83 @@ def test_gemm_bf16_every_tile_configuration_gives_the_same_bits(variant, aks, bk
             assert torch.equal(got, auto)
 
 
+SPLIT_SHAPES = [
+    # M, N, K: few output tiles and a long k, so that the launch is split along k
+    (264, 520, 1000), (512, 384, 1000), (1032, 776, 2056), (8, 8, 4096), (136, 72, 520),
+]
+
+
+@pytest.mark.parametrize("M,N,K", SPLIT_SHAPES)
+@pytest.mark.parametrize("aks,bks", [(0, 0), (0, 1), (1, 1), (1, 0)])
+def test_gemm_bf16_split_along_k_with_scratch(M, N, K, aks, bks):
+    """jpp_op_gemm_ws: partial tiles through the scratch buffer, summed by the second kernel
+    with bias, residual and rounding.  Checked against the definition; the scratch is sized by
+    jpp_op_gemm_workspace_bytes, and a too small one must fall back to the unsplit launch."""
+    rng = np.random.default_rng(M + 3 * N + K + aks * 2 + bks)
+    A = inp.round_to_dtype(rng.standard_normal((M, K)), inp.DT_BF16)
+    Bm = inp.round_to_dtype(rng.standard_normal((N, K)), inp.DT_BF16)
+    bias = inp.round_to_dtype(rng.standard_normal(N), inp.DT_BF16)
+    res = inp.round_to_dtype(rng.standard_normal((M, N)), inp.DT_BF16)
+    ref = A @ Bm.T
+    At = dev(A.T if aks else A, torch.bfloat16)
+    Bt = dev(Bm.T if bks else Bm, torch.bfloat16)
+    lda, ldb = (M if aks else K), (N if bks else K)
+    bt, rt = dev(bias, torch.bfloat16), dev(res, torch.bfloat16)
+    need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_STORE)
+    assert need > 0                                           # these shapes are meant to split
+    assert B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_ACC_F32) == 0
+    ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device=DEV)
+    a = (B.JPP_BF16, M, N, K, At.data_ptr(), lda, aks, Bt.data_ptr(), ldb, bks)
+    Cb = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    Cf = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    Cs = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    Cu = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    B.jpp_op_gemm_ws(*a, Cb.data_ptr(), N, B.OUT_STORE, bt.data_ptr(), rt.data_ptr(), ws.data_ptr(), need, stream())
+    B.jpp_op_gemm_ws(*a, Cf.data_ptr(), N, B.OUT_STORE_F32, None, None, ws.data_ptr(), need, stream())
+    B.jpp_op_gemm_ws(*a, Cs.data_ptr(), N, B.OUT_STORE_F32, None, None, ws.data_ptr(), need - 16, stream())
+    B.jpp_op_gemm(*a, Cu.data_ptr(), N, B.OUT_STORE_F32, None, None, stream())
+    torch.cuda.synchronize()
+    assert rel_l2(host(Cf), ref) < 1e-5
+    assert np.abs(host(Cf) - ref).max() < 1e-3 * math.sqrt(K)
+    assert rel_l2(host(Cb), ref + bias[None, :] + res) < 4e-3
+    assert torch.equal(Cs, Cu)                                # scratch too small: the unsplit launch
+    assert bool(torch.isnan(ws[need // 4:]).all())            # nothing written past the stated size
+
+
+SPLIT_FULL = [
+    # benchmark-size GEMMs whose last round of 256 x 256 tiles is half empty
+    ("ffn-down fwd", 2048, 12288, 49152, 0, 0), ("ffn-up dgrad", 2048, 12288, 49152, 0, 1),
+    ("qkv fwd", 2048, 36864, 12288, 0, 0), ("attn-out fwd", 2048, 12288, 12288, 0, 0),
+]
+
+
+@pytest.mark.parametrize("name,M,N,K,aks,bks", SPLIT_FULL)
+def test_gemm_split_full_shape_sampled_entries(name, M, N, K, aks, bks):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(M + N + K + 1)
+    A = torch.randn((K, M) if aks else (M, K), generator=g, device=DEV).to(torch.bfloat16)
+    Bm = (torch.randn((K, N) if bks else (N, K), generator=g, device=DEV) * 0.02).to(torch.bfloat16)
+    bias = torch.randn(N, generator=g, device=DEV).to(torch.bfloat16)
+    res = torch.randn((M, N), generator=g, device=DEV).to(torch.bfloat16)
+    need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_STORE)
+    assert need > 0
+    ws = torch.empty(need // 4, dtype=torch.float32, device=DEV)
+    Cc = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    B.jpp_op_gemm_ws(B.JPP_BF16, M, N, K, A.data_ptr(), M if aks else K, aks, Bm.data_ptr(), N if bks else K, bks,
+                     Cc.data_ptr(), N, B.OUT_STORE, bias.data_ptr(), res.data_ptr(), ws.data_ptr(), need, stream())
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    ms = np.concatenate([rng.integers(0, M, 4096), [0, 0, M - 1, M - 1, 255, 256, M - 256, M - 257]])
+    ns = np.concatenate([rng.integers(0, N, 4096), [0, N - 1, 0, N - 1, 255, 256, N - 256, N - 257]])
+    mi, ni = torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)
+    a_rows = (A[:, mi].T if aks else A[mi, :]).float().cpu().numpy().astype(np.float64)
+    b_rows = (Bm[:, ni].T if bks else Bm[ni, :]).float().cpu().numpy().astype(np.float64)
+    ref = np.einsum("sk,sk->s", a_rows, b_rows) + bias[ni].double().cpu().numpy() + res[mi, ni].double().cpu().numpy()
+    got = Cc[mi, ni].double().cpu().numpy()
+    assert rel_l2(got, ref) < 4e-3, name
+    assert bool(torch.isfinite(Cc.float()).all())
+
+
 def test_gemm_bf16_padded_leading_dimensions_do_not_touch_neighbours():
     """Sub-matrix views: ld > row length.  The cells outside C's view must stay untouched."""
     rng = np.random.default_rng(0)
