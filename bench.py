@@ -163,6 +163,9 @@ def main():
                          "(the recomputation is not counted in the TFLOP/s)")
     ap.add_argument("--schedule", choices=["gpipe", "1f1b", "interleaved"], default=None,
                     help="override the configuration's schedule (same P, rank, V)")
+    ap.add_argument("--optimizer", choices=["sgd", "adamw"], default=None,
+                    help="end every step with the parameter update (jpp_stage_apply_gradients) and report "
+                         "its own bandwidth; off by default: the headline metric is the stage's fwd+bwd")
     ap.add_argument("--pipeline", action="store_true",
                     help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
@@ -213,9 +216,20 @@ def main():
     stash_slots = st.max_in_flight
     st.set_params_random(seed=0)
     st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM
+    opt_kind = {None: None, "sgd": B.JPP_OPT_SGD, "adamw": B.JPP_OPT_ADAMW}[a.optimizer]
+    if opt_kind is not None:
+        st.optimizer_bind(opt_kind)
+    step_no = [0]
+
+    def update():
+        if opt_kind is not None:
+            step_no[0] += 1
+            st.apply_gradients(opt_kind, lr=1e-4 / w.n_microbatches, weight_decay=0.01, step=step_no[0])
+
     for _ in range(a.warmup):
         st.zero_grads()
         st.run()
+        update()
     st.sync()
     torch.cuda.synchronize()
     # per-step marks on the stage's compute stream (every run is joined back into it), recorded
@@ -226,6 +240,7 @@ def main():
     for k in range(a.steps):
         st.zero_grads()
         st.run()
+        update()
         marks[k + 1].record(st.compute)
     st.sync()
     torch.cuda.synchronize()
@@ -235,6 +250,22 @@ def main():
     flops_step = algorithmic_flops_per_microbatch(w) * w.n_microbatches
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     mb_per_s = w.n_microbatches / (ms_per_step * 1e-3)
+    opt_info = None
+    if opt_kind is not None:
+        # the update alone: HBM-bound, 4 (g) + 2 x esz (w) bytes per parameter for SGD,
+        # 16 read + 12 written in fp32 state plus esz written for AdamW
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st.compute)
+        for _ in range(3):
+            update()
+        e1.record(st.compute)
+        st.sync()
+        ms_u = e0.elapsed_time(e1) / 3
+        esz = 2 if w.dtype == inp.DT_BF16 else 4
+        per = (4 + 2 * esz) if opt_kind == B.JPP_OPT_SGD else (28 + esz)
+        nbytes = per * st.pcount * len(w.stage_ids)
+        opt_info = {"kind": a.optimizer, "ms": ms_u, "bytes": nbytes, "achieved_GBps": nbytes / ms_u / 1e6,
+                    "peak_GBps": PEAK_HBM_GBS, "frac": nbytes / ms_u / 1e6 / PEAK_HBM_GBS}
     # sanity: the run produced finite gradients
     g = st.grads_tensor(0)
     finite = bool(torch.isfinite(g).all().item())
@@ -253,6 +284,7 @@ def main():
         # the same time with attention counted over the full score matrix (no causal halving)
         "value_full_attention_count": tflops * flops_full_attention(w) / algorithmic_flops_per_microbatch(w),
         "grads_finite": finite,
+        "optimizer": opt_info,
         "config": {"workload": w.name, "layers_per_stage": w.n_layers, "virtual_stages": w.V,
                    "d_model": w.d_model, "heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_ffn": w.d_ffn,
                    "seq_len": w.seq_len, "microbatch": w.microbatch, "n_microbatches": w.n_microbatches,

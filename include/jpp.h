@@ -177,6 +177,38 @@ jpp_status jpp_stage_grads(jpp_stage* st, int vstage, const float** grads_dev, s
  * are collected per microbatch, not averaged over microbatches). Synchronises. */
 jpp_status jpp_stage_losses(jpp_stage* st, const float** loss_dev);
 
+/* ---- parameter update after accumulation (Section 3.1: the step ends with
+ * state.apply_gradient(grads, learning_rate); the paper names no optimizer) -----------
+ * Per element, g = accumulated gradient (sum over microbatches, no 1/M: scale lr accordingly):
+ *   JPP_OPT_SGD:   w <- w - lr (g + weight_decay w), computed in fp32 from the stored w and
+ *                  rounded back to the storage dtype; no state.
+ *   JPP_OPT_ADAMW: fp32 master weights and moments; step t = 1, 2, ...
+ *                  m <- b1 m + (1-b1) g; v <- b2 v + (1-b2) g^2;
+ *                  w <- w - lr (m/(1-b1^t) / (sqrt(v/(1-b2^t)) + eps) + weight_decay w);
+ *                  the stored parameters become the master weights rounded to the storage dtype.
+ * Every parameter is treated alike (weight decay included). */
+enum { JPP_OPT_SGD = 0, JPP_OPT_ADAMW = 1 };
+typedef struct {
+  int32_t kind;       /* JPP_OPT_*                                  */
+  float lr, beta1, beta2, eps, weight_decay;
+  int32_t step;       /* AdamW: 1-based step count (bias correction) */
+} jpp_optimizer_step;
+
+/* Borrowed device pointer to the parameters of local virtual stage `vstage` (storage dtype,
+ * param_count elements, layout of jpp_stage_param_info).  Waits for the compute stream. */
+jpp_status jpp_stage_params(jpp_stage* st, int vstage, const void** params_dev, size_t* n_elems);
+
+/* AdamW state: n_virtual x [master | m | v], param_count floats each, in caller-owned device
+ * memory of jpp_stage_optimizer_bytes (0 for SGD), 16-byte aligned.  bind copies the current
+ * parameters into the master weights and zeroes the moments (enqueued on `stream`). */
+size_t jpp_stage_optimizer_bytes(const jpp_stage* st, int kind);
+jpp_status jpp_stage_optimizer_bind(jpp_stage* st, int kind, void* state_dev, size_t state_bytes, void* stream);
+
+/* Enqueues the update of every virtual stage's parameters from its gradient buffer on
+ * `stream`; use the compute stream of jpp_stage_run so that it follows the accumulation and
+ * precedes the next run.  Gradients are left as they are (call jpp_stage_zero_grads). */
+jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* step, void* stream);
+
 /* Introspection of the last run (host bookkeeping, used by tests). */
 int jpp_stage_peak_in_flight(const jpp_stage* st);   /* stash slots high-water mark            */
 int jpp_stage_pending_peak(const jpp_stage* st);     /* pending-deletion queue high-water mark */

@@ -34,6 +34,13 @@ class jpp_layer_config(C.Structure):
                 ("vocab", C.c_int32), ("remat", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
 
 
+class jpp_optimizer_step(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("step", C.c_int32)]
+
+
+JPP_OPT_SGD, JPP_OPT_ADAMW = 0, 1
+
 _lib = None
 
 _SIGNATURES = {
@@ -62,6 +69,10 @@ _SIGNATURES = {
     "jpp_pipeline_run": (C.c_int, [C.c_void_p, C.POINTER(C.POINTER(jpp_task)), C.POINTER(C.c_int),
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
     "jpp_pipeline_sync": (C.c_int, [C.c_void_p]),
+    "jpp_stage_params": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
+    "jpp_stage_optimizer_bytes": (C.c_size_t, [C.c_void_p, C.c_int]),
+    "jpp_stage_optimizer_bind": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "jpp_stage_apply_gradients": (C.c_int, [C.c_void_p, C.POINTER(jpp_optimizer_step), C.c_void_p]),
     "jpp_stage_peak_in_flight": (C.c_int, [C.c_void_p]),
     "jpp_stage_pending_peak": (C.c_int, [C.c_void_p]),
     "jpp_stage_prefetched": (C.c_int, [C.c_void_p]),
@@ -265,6 +276,26 @@ def jpp_pipeline_run(h, task_lists, compute_streams, side_streams):
 
 def jpp_pipeline_sync(h):
     _check(lib().jpp_pipeline_sync(h))
+
+
+def jpp_stage_params(h, vstage):
+    p = C.c_void_p()
+    n = C.c_size_t()
+    _check(lib().jpp_stage_params(h, vstage, C.byref(p), C.byref(n)))
+    return p.value, n.value
+
+
+def jpp_stage_optimizer_bytes(h, kind):
+    return lib().jpp_stage_optimizer_bytes(h, kind)
+
+
+def jpp_stage_optimizer_bind(h, kind, state_ptr, state_bytes, stream):
+    _check(lib().jpp_stage_optimizer_bind(h, kind, C.c_void_p(state_ptr), state_bytes, C.c_void_p(stream)))
+
+
+def jpp_stage_apply_gradients(h, kind, lr, stream, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1):
+    o = jpp_optimizer_step(kind, lr, beta1, beta2, eps, weight_decay, step)
+    _check(lib().jpp_stage_apply_gradients(h, C.byref(o), C.c_void_p(stream)))
 
 
 def jpp_stage_peak_in_flight(h):

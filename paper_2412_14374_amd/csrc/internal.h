@@ -81,5 +81,10 @@ hipError_t launch_rope(int dtype, int mb, int seq, int Hq, int Hkv, int hd, void
 hipError_t launch_cross_entropy(int dtype, int rows, int vocab, const float* z, const int32_t* targets,
                                 void* dz, float* row_loss, float* loss, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// Parameter updates over n elements (n a multiple of 4): w in the storage dtype, g fp32.
+hipError_t launch_sgd(int dtype, void* w, const float* g, size_t n, float lr, float wd, hipStream_t s);
+hipError_t launch_adamw(int dtype, void* w, float* master, float* m, float* v, const float* g, size_t n, float lr,
+                        float b1, float b2, float eps, float wd, int step, hipStream_t s);
+hipError_t launch_widen(int dtype, const void* w, float* master, size_t n, hipStream_t s);  // master <- (float) w
 
 }  // namespace jpp

@@ -5,6 +5,8 @@
 // The paper defines none of these operations (its Evaluation section only names the
 // GPT-3 and Llama 2 model families); the formulas are the standard ones and are stated
 // next to each kernel.
+#include <cmath>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -409,6 +411,64 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(u32x4* __restrict__
     p[i] = z;
 }
 
+// ---- parameter update after gradient accumulation (Section 3.1: apply_gradient) -----------
+// Four consecutive elements per thread.  SGD works on the stored parameters; AdamW keeps fp32
+// master weights and moments and rounds the master weights into the storage type.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void sgd_kernel(T* __restrict__ w, const float* __restrict__ g, size_t n4,
+                                                       float lr, float wd) {
+  typedef T T4 __attribute__((ext_vector_type(4)));
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    const f32x4 gv = reinterpret_cast<const f32x4*>(g)[i];
+    T4 wv = reinterpret_cast<T4*>(w)[i];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float x = (float)wv[e];
+      wv[e] = (T)(x - lr * (gv[e] + wd * x));
+    }
+    reinterpret_cast<T4*>(w)[i] = wv;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void adamw_kernel(T* __restrict__ w, float* __restrict__ master,
+                                                         float* __restrict__ m, float* __restrict__ v,
+                                                         const float* __restrict__ g, size_t n4, float lr, float b1,
+                                                         float b2, float eps, float wd, float c1, float c2) {
+  typedef T T4 __attribute__((ext_vector_type(4)));
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    const f32x4 gv = reinterpret_cast<const f32x4*>(g)[i];
+    f32x4 mv = reinterpret_cast<f32x4*>(m)[i], vv = reinterpret_cast<f32x4*>(v)[i];
+    f32x4 x = reinterpret_cast<f32x4*>(master)[i];
+    T4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      mv[e] = b1 * mv[e] + (1.f - b1) * gv[e];
+      vv[e] = b2 * vv[e] + (1.f - b2) * gv[e] * gv[e];
+      const float mh = mv[e] * c1, vh = vv[e] * c2;      // c1 = 1 / (1 - b1^t), c2 = 1 / (1 - b2^t)
+      x[e] = x[e] - lr * (mh / (sqrtf(vh) + eps) + wd * x[e]);
+      out[e] = (T)x[e];
+    }
+    reinterpret_cast<f32x4*>(m)[i] = mv;
+    reinterpret_cast<f32x4*>(v)[i] = vv;
+    reinterpret_cast<f32x4*>(master)[i] = x;
+    reinterpret_cast<T4*>(w)[i] = out;
+  }
+}
+
+// master <- (float) w
+template <typename T>
+__global__ __launch_bounds__(kThreads) void widen_kernel(const T* __restrict__ w, float* __restrict__ master, size_t n4) {
+  typedef T T4 __attribute__((ext_vector_type(4)));
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    const T4 wv = reinterpret_cast<const T4*>(w)[i];
+    f32x4 x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = (float)wv[e];
+    reinterpret_cast<f32x4*>(master)[i] = x;
+  }
+}
+
 inline int grid_for(size_t items) {
   size_t g = (items + kThreads - 1) / kThreads;
   const size_t cap = 256 * 16;  // 16 workgroups per CU
@@ -549,6 +609,32 @@ hipError_t launch_cross_entropy(int dtype, int rows, int vocab, const float* z, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   mean_rows_kernel<<<1, kThreads, 0, s>>>(row_loss, rows, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_sgd(int dtype, void* w, const float* g, size_t n, float lr, float wd, hipStream_t s) {
+  const size_t n4 = n / 4;   // parameter buffers are padded to multiples of 8 elements
+  if (dtype == JPP_BF16) sgd_kernel<bf16><<<grid_for(n4), kThreads, 0, s>>>((bf16*)w, g, n4, lr, wd);
+  else sgd_kernel<float><<<grid_for(n4), kThreads, 0, s>>>((float*)w, g, n4, lr, wd);
+  return hipGetLastError();
+}
+
+hipError_t launch_adamw(int dtype, void* w, float* master, float* m, float* v, const float* g, size_t n, float lr,
+                        float b1, float b2, float eps, float wd, int step, hipStream_t s) {
+  const size_t n4 = n / 4;
+  // bias corrections in double on the host: 1 - b^t loses digits in fp32 for b close to 1
+  const float c1 = (float)(1.0 / (1.0 - pow((double)b1, step))), c2 = (float)(1.0 / (1.0 - pow((double)b2, step)));
+  if (dtype == JPP_BF16)
+    adamw_kernel<bf16><<<grid_for(n4), kThreads, 0, s>>>((bf16*)w, master, m, v, g, n4, lr, b1, b2, eps, wd, c1, c2);
+  else
+    adamw_kernel<float><<<grid_for(n4), kThreads, 0, s>>>((float*)w, master, m, v, g, n4, lr, b1, b2, eps, wd, c1, c2);
+  return hipGetLastError();
+}
+
+hipError_t launch_widen(int dtype, const void* w, float* master, size_t n, hipStream_t s) {
+  const size_t n4 = n / 4;
+  if (dtype == JPP_BF16) widen_kernel<bf16><<<grid_for(n4), kThreads, 0, s>>>((const bf16*)w, master, n4);
+  else widen_kernel<float><<<grid_for(n4), kThreads, 0, s>>>((const float*)w, master, n4);
   return hipGetLastError();
 }
 

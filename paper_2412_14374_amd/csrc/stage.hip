@@ -793,6 +793,61 @@ jpp_status jpp_stage_losses(jpp_stage* st, const float** loss_dev) {
   return JPP_OK;
 }
 
+jpp_status jpp_stage_params(jpp_stage* st, int vstage, const void** params_dev, size_t* n_elems) {
+  if (!st || !params_dev) return fail(JPP_EINVAL, "null argument");
+  if (vstage < 0 || vstage >= st->cfg.n_virtual) return fail(JPP_EINVAL, "vstage out of range");
+  if (st->cs) HIP_TRY(hipStreamSynchronize(st->cs));
+  *params_dev = st->params[vstage];
+  if (n_elems) *n_elems = st->pcount;
+  return JPP_OK;
+}
+
+size_t jpp_stage_optimizer_bytes(const jpp_stage* st, int kind) {
+  if (!st || kind != JPP_OPT_ADAMW) return 0;
+  return (size_t)st->cfg.n_virtual * 3 * st->pcount * sizeof(float);
+}
+
+jpp_status jpp_stage_optimizer_bind(jpp_stage* st, int kind, void* state_dev, size_t state_bytes, void* stream) {
+  if (!st) return fail(JPP_EINVAL, "null stage");
+  if (kind == JPP_OPT_SGD) { st->opt_state = nullptr; return JPP_OK; }
+  if (kind != JPP_OPT_ADAMW) return fail(JPP_EINVAL, "unknown optimizer kind");
+  for (bool b : st->params_set)
+    if (!b) return fail(JPP_ESTATE, "set the parameters first: the master weights are copied from them");
+  if (!state_dev || ((uintptr_t)state_dev % 16) != 0) return fail(JPP_EINVAL, "state must be 16-byte aligned");
+  if (state_bytes < jpp_stage_optimizer_bytes(st, kind)) return fail(JPP_EINVAL, "optimizer state too small");
+  hipStream_t s = (hipStream_t)stream;
+  float* base = (float*)state_dev;
+  for (int v = 0; v < st->cfg.n_virtual; ++v) {
+    float* master = base + (size_t)v * 3 * st->pcount;
+    HIP_TRY(launch_widen(st->cfg.dtype, st->params[v], master, st->pcount, s));
+    HIP_TRY(launch_fill_zero(master + st->pcount, 2 * st->pcount * sizeof(float), s));
+  }
+  st->opt_state = base;
+  return JPP_OK;
+}
+
+jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* o, void* stream) {
+  if (!st || !o) return fail(JPP_EINVAL, "null argument");
+  if (st->running) return fail(JPP_ESTATE, "a run is being enqueued on this stage");
+  hipStream_t s = (hipStream_t)stream;
+  if (o->kind == JPP_OPT_SGD) {
+    for (int v = 0; v < st->cfg.n_virtual; ++v)
+      HIP_TRY(launch_sgd(st->cfg.dtype, st->params[v], st->grads[v], st->pcount, o->lr, o->weight_decay, s));
+    return JPP_OK;
+  }
+  if (o->kind != JPP_OPT_ADAMW) return fail(JPP_EINVAL, "unknown optimizer kind");
+  if (!st->opt_state) return fail(JPP_ESTATE, "AdamW needs jpp_stage_optimizer_bind first");
+  if (o->step < 1) return fail(JPP_EINVAL, "step counts from 1");
+  if (!(o->beta1 >= 0.f && o->beta1 < 1.f && o->beta2 >= 0.f && o->beta2 < 1.f))
+    return fail(JPP_EINVAL, "beta1 and beta2 must be in [0, 1)");
+  for (int v = 0; v < st->cfg.n_virtual; ++v) {
+    float* master = st->opt_state + (size_t)v * 3 * st->pcount;
+    HIP_TRY(launch_adamw(st->cfg.dtype, st->params[v], master, master + st->pcount, master + 2 * st->pcount,
+                         st->grads[v], st->pcount, o->lr, o->beta1, o->beta2, o->eps, o->weight_decay, o->step, s));
+  }
+  return JPP_OK;
+}
+
 int jpp_stage_peak_in_flight(const jpp_stage* st) { return st ? st->peak_in_flight : -1; }
 int jpp_stage_pending_peak(const jpp_stage* st) { return st ? st->pending_peak : -1; }
 int jpp_stage_prefetched(const jpp_stage* st) { return st ? st->prefetched : -1; }

@@ -135,6 +135,10 @@ struct jpp_stage {
   std::vector<hipEvent_t> wait_x, wait_cot, signal_y, signal_dx;
   std::vector<char> avail_x, avail_cot;
 
+  // AdamW state, caller-owned (jpp_stage_optimizer_bind): per virtual stage [master | m | v],
+  // pcount floats each
+  float* opt_state = nullptr;
+
   // The loss head, if configured, belongs to the actor's last virtual stage.
   bool is_head(int v) const { return cfg.loss_head != 0 && v == cfg.n_virtual - 1; }
 };

@@ -169,6 +169,22 @@ class Stage:
         assert off >= 0 and base <= ptr
         return self.arena[off:off + n * 4].view(torch.float32).clone()
 
+    def params_tensor(self, v):
+        """Device tensor copy (storage dtype) of local virtual stage v's flat parameter buffer."""
+        ptr, n = B.jpp_stage_params(self.h, v)
+        esz = 2 if self.w.dtype == inp.DT_BF16 else 4
+        off = ptr - self.arena.data_ptr()
+        return self.arena[off:off + n * esz].view(torch_dtype(self.w)).clone()
+
+    def optimizer_bind(self, kind):
+        """Allocates and binds the optimizer state (AdamW: fp32 master weights and moments)."""
+        nbytes = B.jpp_stage_optimizer_bytes(self.h, kind)
+        self.opt_state = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=self.dev)
+        B.jpp_stage_optimizer_bind(self.h, kind, self.opt_state.data_ptr(), nbytes, self.compute.cuda_stream)
+
+    def apply_gradients(self, kind, lr, **kw):
+        B.jpp_stage_apply_gradients(self.h, kind, lr, self.compute.cuda_stream, **kw)
+
     def losses(self):
         ptr = B.jpp_stage_losses(self.h)
         off = ptr - self.arena.data_ptr()
