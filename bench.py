@@ -113,6 +113,90 @@ def cpu_baseline():
                       f"{flops / 1e9:.0f} algorithmic GFLOP"}
 
 
+def bench_kernels(w, torch, B, inp):
+    """Every kernel of one layer (forward and backward) alone on the device at the
+    configuration's shapes: milliseconds, achieved rate and fraction of the roofline that bounds
+    it (MFMA peak for GEMMs and attention with the counted FLOPs, HBM peak for the row-wise and
+    element-wise kernels with their algorithmic bytes).  One JSON line per kernel."""
+    dev = "cuda:0"
+    bf = torch.bfloat16
+    T, d, f = w.tokens, w.d_model, w.d_ffn
+    nq, nkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
+    nqkv, f1 = nq + 2 * nkv, (2 * f if w.act == inp.ACT_SWIGLU else f)
+    strm = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, reps=5):
+        fn(); fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def emit(name, shape, ms, work, bound):
+        peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBS
+        ach = work / ms / (1e9 if bound == "mfma" else 1e6)
+        print(json.dumps({"kernel": name, "shape": shape, "ms": round(ms, 4), "bound": bound,
+                          "achieved": round(ach, 1), "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
+                          "peak": peak, "frac": round(ach / peak, 3)}), flush=True)
+
+    gemms = [("qkv fwd", T, nqkv, d, 0, 0, 0), ("attn-out fwd", T, d, nq, 0, 0, 0), ("ffn-up fwd", T, f1, d, 0, 0, 0),
+             ("ffn-down fwd", T, d, f, 0, 0, 0), ("qkv dgrad", T, d, nqkv, 0, 1, 0), ("attn-out dgrad", T, nq, d, 0, 1, 0),
+             ("ffn-up dgrad", T, d, f1, 0, 1, 0), ("ffn-down dgrad", T, f, d, 0, 1, 0),
+             ("qkv wgrad", nqkv, d, T, 1, 1, 2), ("attn-out wgrad", d, nq, T, 1, 1, 2),
+             ("ffn-up wgrad", f1, d, T, 1, 1, 2), ("ffn-down wgrad", d, f, T, 1, 1, 2)]
+    for name, M, N, K, aks, bks, mode in gemms:
+        A = torch.randn((K, M) if aks else (M, K), device=dev).to(bf)
+        Bm = (torch.randn((K, N) if bks else (N, K), device=dev) * 0.02).to(bf)
+        Cc = torch.zeros((M, N), dtype=bf if mode == 0 else torch.float32, device=dev)
+        need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, mode)
+        ws = torch.empty(max(need // 4, 4), dtype=torch.float32, device=dev)
+        ms = timed(lambda: B.jpp_op_gemm_ws(B.JPP_BF16, M, N, K, A.data_ptr(), M if aks else K, aks, Bm.data_ptr(),
+                                            N if bks else K, bks, Cc.data_ptr(), N, mode, None, None,
+                                            ws.data_ptr() if need else None, need, strm))
+        emit("gemm " + name, f"{M}x{N}x{K}", ms, 2.0 * M * N * K, "mfma")
+        del A, Bm, Cc, ws
+    mb, seq, Hq, Hkv, hd = w.microbatch, w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim
+    qkv = torch.randn(T, nqkv, device=dev).to(bf)
+    do = torch.randn(T, nq, device=dev).to(bf)
+    out = torch.zeros(T, nq, dtype=bf, device=dev)
+    lse = torch.zeros(mb, Hq, seq, dtype=torch.float32, device=dev)
+    dqkv, delta = torch.zeros_like(qkv), torch.zeros_like(lse)
+    fl = 2.0 * mb * Hq * seq * seq * hd
+    ms = timed(lambda: B.jpp_op_attention_fwd(B.JPP_BF16, mb, seq, Hq, Hkv, hd, qkv.data_ptr(), out.data_ptr(),
+                                              lse.data_ptr(), strm))
+    emit("attention fwd", f"mb{mb} seq{seq} Hq{Hq} Hkv{Hkv} hd{hd}", ms, fl, "mfma")
+    ms = timed(lambda: B.jpp_op_attention_bwd(B.JPP_BF16, mb, seq, Hq, Hkv, hd, qkv.data_ptr(), out.data_ptr(),
+                                              lse.data_ptr(), do.data_ptr(), dqkv.data_ptr(), delta.data_ptr(), strm))
+    emit("attention bwd (delta + dK/dV + dQ kernels)", f"mb{mb} seq{seq} Hq{Hq} Hkv{Hkv} hd{hd}", ms, 2 * fl, "mfma")
+    del qkv, do, out, lse, dqkv, delta
+    x = torch.randn(T, d, device=dev).to(bf)
+    y, dy, dx = torch.zeros_like(x), torch.randn(T, d, device=dev).to(bf), torch.zeros_like(x)
+    gam, bet = torch.ones(d, dtype=bf, device=dev), torch.zeros(d, dtype=bf, device=dev)
+    stats = torch.zeros(2 * T, dtype=torch.float32, device=dev)
+    gg, gb = torch.zeros(d, dtype=torch.float32, device=dev), torch.zeros(d, dtype=torch.float32, device=dev)
+    part = torch.zeros(B.jpp_op_colreduce_scratch(T, d), dtype=torch.float32, device=dev)
+    ms = timed(lambda: B.jpp_op_norm_fwd(B.JPP_BF16, w.norm, T, d, w.norm_eps, x.data_ptr(), gam.data_ptr(),
+                                         bet.data_ptr(), y.data_ptr(), stats.data_ptr(), strm))
+    emit("norm fwd", f"{T}x{d}", ms, 4.0 * T * d, "hbm")
+    ms = timed(lambda: B.jpp_op_norm_bwd(B.JPP_BF16, w.norm, T, d, x.data_ptr(), gam.data_ptr(), stats.data_ptr(),
+                                         dy.data_ptr(), None, dx.data_ptr(), gg.data_ptr(), gb.data_ptr(),
+                                         part.data_ptr(), strm))
+    emit("norm bwd (+ gain/offset gradient partials and finish)", f"{T}x{d}", ms, 6.0 * T * d, "hbm")
+    del x, y, dy, dx
+    h = torch.randn(T, f1, device=dev).to(bf)
+    a_ = torch.zeros(T, f, dtype=bf, device=dev)
+    da, dh = torch.randn(T, f, device=dev).to(bf), torch.zeros(T, f1, dtype=bf, device=dev)
+    swiglu = w.act == inp.ACT_SWIGLU
+    ms = timed(lambda: B.jpp_op_act_fwd(B.JPP_BF16, w.act, T, f, h.data_ptr(), a_.data_ptr(), strm))
+    emit("activation fwd", f"{T}x{f}", ms, (6.0 if swiglu else 4.0) * T * f, "hbm")
+    ms = timed(lambda: B.jpp_op_act_bwd(B.JPP_BF16, w.act, T, f, h.data_ptr(), da.data_ptr(), dh.data_ptr(), strm))
+    emit("activation bwd", f"{T}x{f}", ms, (10.0 if swiglu else 6.0) * T * f, "hbm")
+
+
 def bench_pipeline(a, w, torch, B, inp):
     """The configuration as a whole pipeline on one device: P actors with one virtual stage of
     w.n_layers layers each (so P times the single-actor model), every actor running its own
@@ -166,6 +250,9 @@ def main():
     ap.add_argument("--optimizer", choices=["sgd", "adamw"], default=None,
                     help="end every step with the parameter update (jpp_stage_apply_gradients) and report "
                          "its own bandwidth; off by default: the headline metric is the stage's fwd+bwd")
+    ap.add_argument("--kernels", action="store_true",
+                    help="time every kernel of one layer alone at the configuration's shapes and print one "
+                         "JSON line per kernel with its rate against its own roofline")
     ap.add_argument("--pipeline", action="store_true",
                     help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
@@ -204,6 +291,8 @@ def main():
         kind = {"gpipe": inp.SCHED_GPIPE, "1f1b": inp.SCHED_1F1B, "interleaved": inp.SCHED_INTERLEAVED,
                 None: w.sched}[a.schedule]
         w = replace(w, remat=1 if a.remat else 0, sched=kind)
+    if a.kernels:
+        return bench_kernels(w, torch, B, inp)
     if a.pipeline:
         return bench_pipeline(a, w, torch, B, inp)
     tasks = None
