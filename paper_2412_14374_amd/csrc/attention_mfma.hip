@@ -52,7 +52,9 @@ __device__ inline int swz7(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- tile staging ------------------------------------------------------------------------
-// "Row" tile: [64 rows][128 d], 256 bytes per row, 16-byte chunk c stored at c ^ (row & 7).
+// "Row" tile: [64 rows][128 d], 256 bytes per row (one line of the 64 x 4-byte LDS banks), 16-byte
+// chunk c stored at c ^ (row & 15): 16 consecutive rows reading the same logical chunk hit 16
+// different bank quads.
 // Filled HBM -> LDS directly: each wave instruction fills 4 rows (1 KiB) in lane order.
 // `base` points at (row 0, d 0) of the tile in global memory, `ld` is the row pitch in
 // elements, rows >= valid read as zero.
@@ -63,7 +65,7 @@ __device__ inline void load_row_tile(char* tile, const bf16* base, int ld, int v
   for (int i = 0; i < 4; ++i) {
     const int blk = wave * 4 + i;               // 4-row block index, 16 per tile
     const int row = blk * 4 + (lane >> 4);
-    const int c = (lane & 15) ^ (row & 7);
+    const int c = (lane & 15) ^ (row & 15);
     const uint32_t off = row < valid ? (uint32_t)(row * ld + c * 8) * 2u : kOOB;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + blk * 1024), 16, (int)off, 0, 0, 0);
   }
@@ -92,7 +94,7 @@ struct TransposedStage {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int row = rg * 4 + j;
-      *reinterpret_cast<u32x4*>(tile + row * 256 + ((db ^ (row & 7)) << 4)) = regs[j];
+      *reinterpret_cast<u32x4*>(tile + row * 256 + ((db ^ (row & 15)) << 4)) = regs[j];
     }
   }
   __device__ inline void store(char* tile) const {
@@ -117,7 +119,7 @@ struct TransposedStage {
 // A operand from a row tile: rows mt*32 + l32, k = d chunk (2*kd + half).
 __device__ inline bf16x8 row_frag(const char* tile, int mt, int kd, int l32, int half) {
   const int row = mt * 32 + l32;
-  return *reinterpret_cast<const bf16x8*>(tile + row * 256 + (((kd * 2 + half) ^ (row & 7)) << 4));
+  return *reinterpret_cast<const bf16x8*>(tile + row * 256 + (((kd * 2 + half) ^ (row & 15)) << 4));
 }
 // A operand from a transposed tile: rows (d) dt*32 + l32, k = the 16 tile-rows of step s in
 // the permuted order described above.

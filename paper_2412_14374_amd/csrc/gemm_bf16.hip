@@ -111,7 +111,11 @@ template <int R, int BKT, int NT>
 struct KContigTile {
   static constexpr int kRowBytes = BKT * 2;
   static constexpr int CPR = BKT / 8;            // 16-byte chunks per row
-  static constexpr int RPL = 128 / kRowBytes;    // rows per 128-byte LDS line (1 or 2)
+  // The LDS of gfx950 has 64 banks of 4 bytes: 16 lanes x 16 bytes are served per clock when
+  // they fall into 16 different bank quads.  Rows that share a 256-byte line get the same
+  // swizzle, consecutive lines rotate it, so 16 consecutive rows reading the same logical chunk
+  // touch every quad once.
+  static constexpr int RPL = 256 / kRowBytes;    // rows per 256-byte LDS line (2 or 4)
   static constexpr int kRowsPerInstr = 64 / CPR;
   static constexpr int kLoads = R * CPR / NT;
   static constexpr int kBytes = R * kRowBytes;
@@ -171,7 +175,7 @@ struct KStridedTile {
     const i32x4 rs = make_rsrc(base, ((long long)(K - k0) * op.ld - r0) * 2);
     const int blk = i * (NT / 64) + wave;
     const int k = blk * kRowsPerInstr + lane / CPR;
-    const int c = (lane % CPR) ^ ((k & 3) << 1);
+    const int c = (lane % CPR) ^ ((k & 3) << 2);
     const uint32_t off = (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
     dma16(rs, tile + blk * 1024, off);
   }
@@ -186,15 +190,17 @@ struct KStridedTile {
   __device__ static inline void store_one(char* tile, int i, const u32x4& v) {
     const int cidx = i * NT + threadIdx.x;
     const int k = cidx / CPR, c = cidx % CPR;
-    *reinterpret_cast<u32x4*>(tile + k * kRowBytes + ((c ^ ((k & 3) << 1)) << 4)) = v;
+    *reinterpret_cast<u32x4*>(tile + k * kRowBytes + ((c ^ ((k & 3) << 2)) << 4)) = v;
   }
   // Lane l of a 16-lane group addresses the 8-byte row (k = .. + (l>>2), rows 4*(l&3) .. +3)
-  // and receives k = .. + 0..3 for row (l & 15) of the group's 16 rows.
+  // and receives k = .. + 0..3 for row (l & 15) of the group's 16 rows.  The 32 lanes served
+  // together read 4 k-rows x 32 rows; k-row k has its 16-byte chunks XORed with 4 * (k & 3), which
+  // sends the four k-rows to four different 64-byte bank groups: 256 distinct bytes, no conflict.
   __device__ static inline int frag_base(int row0, int l32, int half) {
     const int r = l32 & 15;
     const int row = row0 + (l32 & 16) + 4 * (r & 3);
     const int k = half * 8 + (r >> 2);
-    return k * kRowBytes + (((row >> 3) ^ ((k & 3) << 1)) << 4) + (row & 4) * 2;
+    return k * kRowBytes + (((row >> 3) ^ ((k & 3) << 2)) << 4) + (row & 4) * 2;
   }
   __device__ static inline bf16x8 frag(const char* tile, int base, int kk) {
     const char* p = tile + base + kk * 16 * kRowBytes;
@@ -449,7 +455,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, i
   // Accumulator register r of lane (l32, half) is C[8*(r/4) + 4*half + r%4][l32] of its 32x32
   // block.  Each wave stages one 32 x TN row block at a time in its private LDS region and
   // reads it back row-major, 4 consecutive columns per lane.
-  constexpr int LDW = TN + 4;                 // padded row length in floats
+  constexpr int LDW = TN + 8;                 // padded row length in floats: lanes 32..63 (4 rows down) land 32 banks away
   constexpr int LPR = TN / 4;                 // lanes per row
   constexpr int RPI = 64 / LPR;               // rows per wave instruction
   constexpr int kSteps = 32 / RPI;
@@ -671,8 +677,7 @@ hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
     case 4: return launch_layout<256, 256, 64, 2, 2, 2>(g, s);
     case 5: return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
     case 6: return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
-    case 7: return launch_layout<256, 256, 64, 2, 2, 2, true>(g, s);
-    case 8: return launch_layout<128, 128, 64, 2, 2, 2, true>(g, s);
+    case 7: return launch_layout<128, 128, 64, 2, 2, 2, true>(g, s);
     default: break;
   }
   // Large tiles when they still give every CU work; smaller ones otherwise.

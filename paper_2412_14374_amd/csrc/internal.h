@@ -39,7 +39,7 @@ hipError_t launch_gemm_f32(const GemmDesc& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s);
 bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why);
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, int out_mode);  // 0: this shape is never split
-void set_gemm_variant(int v);  // 0 = automatic tile selection; 1..3 force a configuration (benchmarking)
+void set_gemm_variant(int v);  // 0 = automatic tile selection; 1..7 force a configuration (benchmarking)
 
 struct AttnDesc {
   int mb, seq, Hq, Hkv, hd;
