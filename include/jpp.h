@@ -157,13 +157,16 @@ jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream);
  * on compute_stream, backward tasks on two library-owned streams that start after the work
  * already queued on compute_stream and are joined back into it before the call returns, so
  * that a forward and a backward of different microbatches, and a layer's weight and input
- * gradients, may overlap (Section 2.2.1: any order that honours the data dependencies).  Receives are copies inbox -> stage input issued on side_stream ahead of
- * their consumer (prefetch), sends are copies stage output -> outbox issued on
- * side_stream right after the producing task (Section 4.2); staging buffers whose send
- * has not completed are parked in a pending-deletion queue and reclaimed later
- * (Section 4.3).  Returns after enqueueing; results are complete when both streams are.
- * The two streams must differ and have the default priority.  Calls on one stage must
- * not overlap. */
+ * gradients, may overlap (Section 2.2.1: any order that honours the data dependencies).
+ * Receives are copies inbox -> stage input issued on side_stream ahead of their consumer
+ * (prefetch), sends are copies stage output -> outbox issued on side_stream right after the
+ * producing task (Section 4.2); staging buffers whose send has not completed are parked in a
+ * pending-deletion queue and reclaimed later (Section 4.3).  Returns after enqueueing; the
+ * side stream, too, is joined into compute_stream at the end, so the run is complete when
+ * compute_stream is.  The two streams must differ and have the default priority.  Calls on
+ * one stage must not overlap.
+ * HIP graphs: JPP_ESTATE when compute_stream is capturing (the run queries event completion
+ * and refers to events of earlier runs; recording it into a graph is not supported). */
 jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream,
                          void* side_stream);
 

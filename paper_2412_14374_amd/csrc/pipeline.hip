@@ -232,6 +232,12 @@ jpp_status jpp_pipeline_run(jpp_pipeline* p, const jpp_task* const* task_lists, 
   if (!p || !task_lists || !n_tasks || !compute_streams || !side_streams) return fail(JPP_EINVAL, "null argument");
   if (!p->bound) return fail(JPP_ESTATE, "pipeline boundary buffers not bound");
   const int P = p->P;
+  for (int r = 0; r < P; ++r) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing((hipStream_t)compute_streams[r], &cap));
+    if (cap != hipStreamCaptureStatusNone)
+      return fail(JPP_ESTATE, "jpp_pipeline_run cannot be recorded into a HIP graph (jpp_stage_run can)");
+  }
   // everything that can be refused is checked before anything is enqueued
   for (int r = 0; r < P; ++r) {
     if (!task_lists[r] || n_tasks[r] < 0) return fail(JPP_EINVAL, "null task list");

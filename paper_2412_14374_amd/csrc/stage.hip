@@ -609,6 +609,13 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
                                    std::to_string(st->max_in_flight));
 
   hipStream_t cs = (hipStream_t)compute_stream, ss = (hipStream_t)side_stream;
+  // A run queries event completion (pending-deletion queue) and refers to events of earlier
+  // runs, neither of which a stream capture allows; a capture-safe variant of this function
+  // was tried and ending its capture crashed inside the HIP runtime, so it is refused.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  HIP_TRY(hipStreamIsCapturing(cs, &cap));
+  if (cap != hipStreamCaptureStatusNone)
+    return fail(JPP_ESTATE, "jpp_stage_run cannot be recorded into a HIP graph");
   // order this run after the previous one on both streams (device-side waits only)
   if (st->end_compute.recorded) {
     HIP_TRY(hipStreamWaitEvent(cs, st->end_side.ev, 0));
@@ -622,6 +629,7 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
   HIP_TRY(hipEventRecord(st->run_start.ev, cs));
   HIP_TRY(hipStreamWaitEvent(st->bs, st->run_start.ev, 0));
   HIP_TRY(hipStreamWaitEvent(st->ws, st->run_start.ev, 0));
+  HIP_TRY(hipStreamWaitEvent(ss, st->run_start.ev, 0));
   st->w_task.recorded = false;
   st->peak_in_flight = 0; st->pending_peak = 0; st->prefetched = 0; st->host_syncs = 0;
   st->free_slots.clear();
@@ -753,8 +761,10 @@ jpp_status run_end(jpp_stage* st) {
   HIP_TRY(hipEventRecord(st->w_end.ev, st->ws));
   HIP_TRY(hipStreamWaitEvent(st->cs, st->b_end.ev, 0));
   HIP_TRY(hipStreamWaitEvent(st->cs, st->w_end.ev, 0));
-  HIP_TRY(hipEventRecord(st->end_compute.ev, st->cs));
+  // ... and the side stream: when the compute stream reaches this point the run is over
   HIP_TRY(hipEventRecord(st->end_side.ev, st->ss));
+  HIP_TRY(hipStreamWaitEvent(st->cs, st->end_side.ev, 0));
+  HIP_TRY(hipEventRecord(st->end_compute.ev, st->cs));
   st->end_compute.recorded = true;
   return JPP_OK;
 }
