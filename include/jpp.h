@@ -232,6 +232,13 @@ const char* jpp_last_error(void);
  * Destroy the pipeline before its actors. */
 typedef struct jpp_pipeline jpp_pipeline;
 
+/* Host-only (no GPU needed): the order in which jpp_pipeline_run enqueues the tasks of
+ * n_actors lists (actor r owning the stages r, P + r, ...): order[k] = the actor whose next
+ * task is enqueued at step k; cap >= the total number of tasks.  JPP_ESCHED, naming the
+ * blocked tasks, when the lists wait for each other in a cycle (Section 4.2). */
+jpp_status jpp_pipeline_merge_order(int n_actors, int n_virtual, int n_microbatches,
+                                    const jpp_task* const* task_lists, const int* n_tasks, int* order, int cap);
+
 /* Bytes of device memory for the boundary buffers: 2 * (P * n_virtual - 1) * M tensors. */
 size_t jpp_pipeline_arena_bytes(const jpp_layer_config* cfg, int n_actors, int n_microbatches);
 

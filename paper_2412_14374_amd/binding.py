@@ -61,6 +61,8 @@ _SIGNATURES = {
     "jpp_stage_run": (C.c_int, [C.c_void_p, C.POINTER(jpp_task), C.c_int, C.c_void_p, C.c_void_p]),
     "jpp_stage_grads": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
     "jpp_stage_losses": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p)]),
+    "jpp_pipeline_merge_order": (C.c_int, [C.c_int] * 3 + [C.POINTER(C.POINTER(jpp_task)), C.POINTER(C.c_int),
+                                                           C.POINTER(C.c_int), C.c_int]),
     "jpp_pipeline_arena_bytes": (C.c_size_t, [C.POINTER(jpp_layer_config), C.c_int, C.c_int]),
     "jpp_pipeline_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_size_t,
                                       C.POINTER(C.c_void_p)]),
@@ -242,6 +244,17 @@ def jpp_stage_losses(h):
     p = C.c_void_p()
     _check(lib().jpp_stage_losses(h, C.byref(p)))
     return p.value
+
+
+def jpp_pipeline_merge_order(P, V, M, task_lists):
+    """Returns [actor, ...]: which actor enqueues its next task at each step."""
+    arrs = [tasks_array(t) for t in task_lists]
+    lists = (C.POINTER(jpp_task) * P)(*[C.cast(a, C.POINTER(jpp_task)) for a, _ in arrs])
+    counts = (C.c_int * P)(*[n for _, n in arrs])
+    total = sum(n for _, n in arrs)
+    out = (C.c_int * max(total, 1))()
+    _check(lib().jpp_pipeline_merge_order(P, V, M, lists, counts, out, total))
+    return list(out[:total])
 
 
 def jpp_pipeline_arena_bytes(cfg, n_actors, M):

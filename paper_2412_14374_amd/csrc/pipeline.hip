@@ -50,7 +50,8 @@ size_t boundary_bytes(const jpp_layer_config& c) {
 
 // The producing task of `t`'s operand as (actor, key into that actor's tables), or actor -1.
 struct Dep { int actor; size_t key; bool is_fwd; };
-Dep producer_of(const jpp_pipeline& p, const jpp_task& t) {
+struct Shape { int P, V, M, S; };
+Dep producer_of(const Shape& p, const jpp_task& t) {
   if (t.ty == JPP_FWD) {
     if (t.stage == 0) return {-1, 0, true};
     const int s = t.stage - 1;
@@ -63,7 +64,7 @@ Dep producer_of(const jpp_pipeline& p, const jpp_task& t) {
 
 // Merges the lists: order[k] = actor that enqueues its next task at step k.  Fails with the
 // blocked tasks named when the lists wait for each other.
-jpp_status merge_lists(const jpp_pipeline& p, const jpp_task* const* lists, const int* n, std::vector<int>& order) {
+jpp_status merge_lists(const Shape& p, const jpp_task* const* lists, const int* n, std::vector<int>& order) {
   std::vector<int> next(p.P, 0);
   std::vector<std::vector<char>> fwd_done(p.P), bwd_done(p.P);
   for (int r = 0; r < p.P; ++r) {
@@ -103,6 +104,30 @@ jpp_status merge_lists(const jpp_pipeline& p, const jpp_task* const* lists, cons
 }  // namespace
 
 extern "C" {
+
+jpp_status jpp_pipeline_merge_order(int n_actors, int n_virtual, int n_microbatches, const jpp_task* const* task_lists,
+                                    const int* n_tasks, int* order, int cap) {
+  if (n_actors < 1 || n_virtual < 1 || n_microbatches < 1 || !task_lists || !n_tasks || !order)
+    return fail(JPP_EINVAL, "bad arguments");
+  const Shape sh{n_actors, n_virtual, n_microbatches, n_actors * n_virtual};
+  long long total = 0;
+  for (int r = 0; r < n_actors; ++r) {
+    if (n_tasks[r] < 0 || (n_tasks[r] > 0 && !task_lists[r])) return fail(JPP_EINVAL, "null task list");
+    for (int k = 0; k < n_tasks[r]; ++k) {
+      const jpp_task& t = task_lists[r][k];
+      if (t.i < 0 || t.i >= n_microbatches || t.stage < 0 || t.stage >= sh.S || t.stage % n_actors != r ||
+          (t.ty != JPP_FWD && t.ty != JPP_BWD))
+        return fail(JPP_ESCHED, "actor " + std::to_string(r) + ": task out of range or on the wrong actor");
+    }
+    total += n_tasks[r];
+  }
+  if (total > cap) return fail(JPP_EINVAL, "output array too small");
+  std::vector<int> o;
+  const jpp_status rc = merge_lists(sh, task_lists, n_tasks, o);
+  if (rc != JPP_OK) return rc;
+  std::copy(o.begin(), o.end(), order);
+  return JPP_OK;
+}
 
 size_t jpp_pipeline_arena_bytes(const jpp_layer_config* cfg, int n_actors, int n_microbatches) {
   if (!cfg || n_actors < 1 || n_microbatches < 1 || cfg->n_virtual < 1) {
@@ -255,7 +280,7 @@ jpp_status jpp_pipeline_run(jpp_pipeline* p, const jpp_task* const* task_lists, 
                                      " stashes alive, its arena holds " + std::to_string(a.max_in_flight));
   }
   std::vector<int> order;
-  jpp_status rc = merge_lists(*p, task_lists, n_tasks, order);
+  jpp_status rc = merge_lists(Shape{p->P, p->V, p->M, p->S}, task_lists, n_tasks, order);
   if (rc != JPP_OK) return rc;
 
   // Boundary buffers are rewritten by this run: every actor starts after every actor's

@@ -129,3 +129,29 @@ def test_arena_size_and_config_errors():
     bad.d_model = 2052                                  # not a multiple of 8 in bf16 mode
     with pytest.raises(B.JppError):
         B.jpp_stage_arena_bytes(bad, 8, 4)
+
+
+def test_pipeline_merge_order_matches_the_oracle_and_reports_deadlocks():
+    """The host-side merge of several actors' lists (Section 4.2: tasks are walked in a
+    topological order of the task graph) against the oracle's, which uses the same round-robin
+    rule; every task follows its producer; cyclic lists are refused."""
+    from oracle import pipeline_oracle as po
+    for P, V, M in [(2, 2, 4), (4, 2, 8), (3, 1, 5), (1, 2, 3)]:
+        if V > 1 or P == 1:
+            lists = [osch.interleaved_1f1b(P, r, V, M) for r in range(P)] if M % P == 0 else None
+        if V == 1 and P > 1:
+            lists = [osch.one_f_one_b(P, r, M) for r in range(P)]
+        if lists is None:
+            lists = [[(i, "fwd", v * P + r) for v in range(V) for i in range(M)] +
+                     [(i, "bwd", v * P + r) for v in reversed(range(V)) for i in range(M)] for r in range(P)]
+        got = B.jpp_pipeline_merge_order(P, V, M, lists)
+        want = [r for (r, _) in po.global_order(lists, P * V)]
+        assert got == want
+    bad0 = [(0, "fwd", 2), (0, "fwd", 0), (0, "bwd", 2), (0, "bwd", 0)]
+    good1 = [(0, "fwd", 1), (0, "fwd", 3), (0, "bwd", 3), (0, "bwd", 1)]
+    with pytest.raises(B.JppError) as e:
+        B.jpp_pipeline_merge_order(2, 2, 1, [bad0, good1])
+    assert e.value.status == B.JPP_ESCHED and "deadlock" in str(e.value) and "actor 0" in str(e.value)
+    with pytest.raises(B.JppError) as e:
+        B.jpp_pipeline_merge_order(2, 2, 1, [[(0, "fwd", 1)], good1])      # stage 1 is not actor 0's
+    assert e.value.status == B.JPP_ESCHED
