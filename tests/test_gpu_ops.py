@@ -218,6 +218,14 @@ def test_gemm_rejects_unsupported_shapes():
     with pytest.raises(B.JppError):
         B.jpp_op_gemm(B.JPP_BF16, 64, 64, 64, None, 64, 0, t.data_ptr(), 64, 0, f.data_ptr(), 64,
                       B.OUT_STORE_F32, None, None, stream())
+    # a row pitch beyond what the 32-bit tile offsets can address is refused, nothing is launched
+    with pytest.raises(B.JppError) as e:
+        B.jpp_op_gemm(B.JPP_BF16, 64, 64, 64, t.data_ptr(), 1 << 24, 0, t.data_ptr(), 64, 0, f.data_ptr(), 64,
+                      B.OUT_STORE_F32, None, None, stream())
+    assert e.value.status == B.JPP_EINVAL and "32-bit" in str(e.value)
+    with pytest.raises(B.JppError):
+        B.jpp_op_gemm_ws(B.JPP_BF16, 64, 64, 64, t.data_ptr(), 64, 0, t.data_ptr(), 64, 0, f.data_ptr(), 64,
+                         B.OUT_STORE_F32, None, None, f.data_ptr() + 4, 1024, stream())      # misaligned scratch
 
 
 @pytest.mark.parametrize("M,N,K", [(5, 3, 7), (130, 70, 33), (64, 64, 16)])

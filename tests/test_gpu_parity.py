@@ -117,6 +117,31 @@ def test_fp32_variants_match_oracle(name):
     st.close()
 
 
+DEGENERATE = {
+    # one microbatch, one token: attention returns v, the norm sees a single row
+    "fp32-one-token": inp.Workload("deg1", inp.DT_F32, 1, 8, 1, 1, 8, 8, 1, 1, 1, w_std=0.3, cot_std=1.0),
+    # fp32, sizes below every tile and vector width that still satisfy the 16-byte chunk rule
+    "fp32-smallest-llama": inp.Workload("deg2", inp.DT_F32, 2, 16, 2, 1, 8, 4, 3, 1, 2, norm=inp.NORM_RMSNORM,
+                                        act=inp.ACT_SWIGLU, use_bias=0, rope=1, w_std=0.3, cot_std=1.0,
+                                        sched=inp.SCHED_1F1B, P=2, rank=0),
+    # bf16 at the smallest legal sizes (multiples of 8 everywhere), generic attention (head_dim 8), loss head
+    "bf16-smallest-head": inp.Workload("deg3", inp.DT_BF16, 1, 8, 1, 1, 8, 8, 8, 1, 2, loss_head=1, vocab=8,
+                                       w_std=0.3, sched=inp.SCHED_1F1B, P=2, rank=1),
+    # bf16, one tile short of everything: MFMA attention (head_dim 128) with 8 tokens
+    "bf16-eight-tokens-hd128": inp.Workload("deg4", inp.DT_BF16, 1, 128, 1, 1, 128, 8, 8, 1, 1, w_std=0.1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(DEGENERATE))
+def test_degenerate_sizes_match_oracle(name):
+    """The smallest legal problems: one token, one microbatch, dimensions below every tile."""
+    w = DEGENERATE[name]
+    st, got, ref = run_both(w, perturb=True, seed=21)
+    worst, err = compare(w, got, ref)
+    assert err <= TOL[w.dtype], (worst, err)
+    st.close()
+
+
 TWINS = {
     # same structure as the benchmark configurations, at sizes the oracle finishes in seconds;
     # sizes chosen to span several GEMM tiles with ragged tails (e.g. 320 = 256 + 64)
