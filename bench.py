@@ -253,6 +253,9 @@ def main():
     ap.add_argument("--kernels", action="store_true",
                     help="time every kernel of one layer alone at the configuration's shapes and print one "
                          "JSON line per kernel with its rate against its own roofline")
+    ap.add_argument("--streams", type=int, choices=[1, 2, 3], default=3,
+                    help="streams a run computes on: 3 = forward, input-gradient chain and weight-gradient GEMMs "
+                         "on their own streams (default), 2 = forward + backward, 1 = everything on one")
     ap.add_argument("--pipeline", action="store_true",
                     help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
@@ -276,6 +279,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     w = inp.CONFIGS[a.config]
+    B.jpp_set_stream_mode(3 - a.streams)
     if a.kernel_only:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)

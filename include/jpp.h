@@ -212,6 +212,12 @@ jpp_status jpp_stage_optimizer_bind(jpp_stage* st, int kind, void* state_dev, si
  * precedes the next run.  Gradients are left as they are (call jpp_stage_zero_grads). */
 jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* step, void* stream);
 
+/* Benchmarking knob, process-wide, read at the start of every run: which streams carry the
+ * backward tasks.  0 (default): input-gradient chain and weight-gradient GEMMs on two
+ * library-owned streams (three-way overlap with the forward stream); 1: both on one
+ * library-owned stream; 2: everything on compute_stream.  Results are identical. */
+void jpp_set_stream_mode(int mode);
+
 /* Introspection of the last run (host bookkeeping, used by tests). */
 int jpp_stage_peak_in_flight(const jpp_stage* st);   /* stash slots high-water mark            */
 int jpp_stage_pending_peak(const jpp_stage* st);     /* pending-deletion queue high-water mark */

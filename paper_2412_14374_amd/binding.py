@@ -81,6 +81,7 @@ _SIGNATURES = {
     "jpp_stage_host_syncs": (C.c_int, [C.c_void_p]),
     "jpp_last_error": (C.c_char_p, []),
     "jpp_set_gemm_variant": (None, [C.c_int]),
+    "jpp_set_stream_mode": (None, [C.c_int]),
     "jpp_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int] * 5),
     "jpp_op_gemm_ws": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                   C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -325,6 +326,10 @@ def jpp_stage_prefetched(h):
 
 def jpp_stage_host_syncs(h):
     return lib().jpp_stage_host_syncs(h)
+
+
+def jpp_set_stream_mode(mode):
+    lib().jpp_set_stream_mode(mode)
 
 
 def jpp_set_gemm_variant(v):

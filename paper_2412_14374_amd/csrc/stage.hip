@@ -32,6 +32,7 @@
 namespace jpp {
 
 static thread_local std::string g_last_error;
+static int g_stream_mode = 0;
 
 jpp_status fail(jpp_status code, const std::string& msg) {
   g_last_error = msg;
@@ -493,8 +494,9 @@ jpp_status jpp_stage_create(const jpp_layer_config* cfg, int n_microbatches, int
   for (auto& t : st->cot) { mk(t.freed); mk(t.rx); }
   mk(st->end_compute); mk(st->end_side); mk(st->run_start); mk(st->b2w); mk(st->w_layer); mk(st->w_task);
   mk(st->b_end); mk(st->w_end);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->bs, hipStreamNonBlocking);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->ws, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->bs_own, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->ws_own, hipStreamNonBlocking);
+  st->bs = st->bs_own; st->ws = st->ws_own;
   if (e == hipSuccess && cfg->rope) {
     e = launch_rope_table(st->rope_table, cfg->seq_len, cfg->head_dim, cfg->rope_theta, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -508,8 +510,8 @@ void jpp_stage_destroy(jpp_stage* st) {
   if (!st) return;
   if (st->cs) (void)hipStreamSynchronize(st->cs);
   if (st->ss) (void)hipStreamSynchronize(st->ss);
-  if (st->bs) { (void)hipStreamSynchronize(st->bs); (void)hipStreamDestroy(st->bs); }
-  if (st->ws) { (void)hipStreamSynchronize(st->ws); (void)hipStreamDestroy(st->ws); }
+  if (st->bs_own) { (void)hipStreamSynchronize(st->bs_own); (void)hipStreamDestroy(st->bs_own); }
+  if (st->ws_own) { (void)hipStreamSynchronize(st->ws_own); (void)hipStreamDestroy(st->ws_own); }
   for (auto& s : st->slots) { ev_destroy(s.freed); ev_destroy(s.rx); ev_destroy(s.fwd_done); }
   for (auto& t : st->tx) { ev_destroy(t.produced); ev_destroy(t.sent); }
   for (auto& t : st->cot) { ev_destroy(t.freed); ev_destroy(t.rx); }
@@ -624,6 +626,9 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
     HIP_TRY(hipStreamWaitEvent(ss, st->end_side.ev, 0));
   }
   st->cs = cs; st->ss = ss;
+  // which streams carry the backward (benchmarking knob; the default is three-way overlap)
+  st->bs = g_stream_mode == 2 ? cs : st->bs_own;
+  st->ws = g_stream_mode == 2 ? cs : (g_stream_mode == 1 ? st->bs_own : st->ws_own);
   // the internal streams start after everything already queued on the compute stream
   // (e.g. jpp_stage_zero_grads)
   HIP_TRY(hipEventRecord(st->run_start.ev, cs));
@@ -857,6 +862,8 @@ jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* o,
   }
   return JPP_OK;
 }
+
+void jpp_set_stream_mode(int mode) { jpp::g_stream_mode = mode < 0 || mode > 2 ? 0 : mode; }
 
 int jpp_stage_peak_in_flight(const jpp_stage* st) { return st ? st->peak_in_flight : -1; }
 int jpp_stage_pending_peak(const jpp_stage* st) { return st ? st->pending_peak : -1; }
