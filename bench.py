@@ -62,7 +62,10 @@ def time_dominant_kernel(w, torch, B, reps=3):
     total_ms, total_flops, n = 0.0, 0.0, 0
     with torch.cuda.stream(s):
         for (M, N, K) in shapes:
-            A = torch.randn((K, M), device="cuda:0").to(torch.bfloat16)
+            # operands with the value distributions the step feeds this kernel: an output-gradient
+            # matrix at the cotangents' scale and an activation matrix of unit scale (the matrix
+            # pipes' clock, hence the rate, depends on the data)
+            A = (torch.randn((K, M), device="cuda:0") * w.cot_std).to(torch.bfloat16)
             Bm = torch.randn((K, N), device="cuda:0").to(torch.bfloat16)
             C = torch.zeros((M, N), dtype=torch.float32, device="cuda:0")
             args = (B.JPP_BF16, M, N, K, A.data_ptr(), M, 1, Bm.data_ptr(), N, 1, C.data_ptr(), N, B.OUT_ACC_F32,
