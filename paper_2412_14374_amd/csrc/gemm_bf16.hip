@@ -250,9 +250,10 @@ __device__ inline void wait_loads_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(int M, int N, int K, Operand A, Operand B,
-                                                                  Epilogue ep) {
+// MINW: waves per SIMD the register allocation must leave room for (1 = use the whole file).
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false, int MINW = 1>
+__global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, int N, int K, Operand A, Operand B,
+                                                                        Epilogue ep) {
   constexpr int NT = 64 * WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
@@ -603,7 +604,7 @@ SplitPlan plan_split(int M, int N, int K, int out_mode) {
   return p;
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false, int MINW = 1>
 hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   constexpr int NT = 64 * WM * WN;
   constexpr int kWgsPerCu = BM * BN >= 256 * 256 ? 1 : 2;
@@ -618,7 +619,7 @@ hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
     ep.split_first = sp.first; ep.split_s = sp.s; ep.split_ws = (float*)g.workspace;
     grid = sp.first + (tiles - sp.first) * sp.s;
   }
-  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG><<<grid, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
+  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG, MINW><<<grid, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
   if (split) {
     const long long quads = (long long)(tiles - sp.first) * (BM * BN / 4);
     const int blocks = (int)((quads + 255) / 256 < 4096 ? (quads + 255) / 256 : 4096);
@@ -627,12 +628,12 @@ hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool VG = false>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool VG = false, int MINW = 1>
 hipError_t launch_layout(const GemmDesc& g, hipStream_t s) {
-  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, false, VG>(g, s);
-  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, true, VG>(g, s);
-  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, true, true, VG>(g, s);
-  return launch_cfg<BM, BN, BKT, NS, WM, WN, true, false, VG>(g, s);
+  if (!g.a_kstrided && !g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, false, VG, MINW>(g, s);
+  if (!g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, false, true, VG, MINW>(g, s);
+  if (g.a_kstrided && g.b_kstrided) return launch_cfg<BM, BN, BKT, NS, WM, WN, true, true, VG, MINW>(g, s);
+  return launch_cfg<BM, BN, BKT, NS, WM, WN, true, false, VG, MINW>(g, s);
 }
 
 int g_variant = 0;
@@ -673,17 +674,17 @@ hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
   switch (g_variant) {
     case 1: return launch_layout<256, 256, 32, 4, 2, 2>(g, s);
     case 2: return launch_layout<256, 256, 32, 5, 2, 2>(g, s);
-    case 3: return launch_layout<128, 128, 32, 4, 2, 2>(g, s);
+    case 3: return launch_layout<128, 128, 32, 4, 2, 2, false, 2>(g, s);
     case 4: return launch_layout<256, 256, 64, 2, 2, 2>(g, s);
-    case 5: return launch_layout<256, 256, 64, 2, 2, 4>(g, s);
-    case 6: return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
-    case 7: return launch_layout<128, 128, 64, 2, 2, 2, true>(g, s);
+    case 5: return launch_layout<256, 256, 64, 2, 2, 4, false, 2>(g, s);
+    case 6: return launch_layout<256, 256, 64, 2, 2, 4, true, 2>(g, s);
+    case 7: return launch_layout<128, 128, 64, 2, 2, 2, true, 2>(g, s);
     default: break;
   }
   // Large tiles when they still give every CU work; smaller ones otherwise.
   const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4, true>(g, s);
-  return launch_layout<128, 128, 64, 2, 2, 2, true>(g, s);
+  if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4, true, 2>(g, s);
+  return launch_layout<128, 128, 64, 2, 2, 2, true, 2>(g, s);
 }
 
 }  // namespace jpp
