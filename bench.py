@@ -42,8 +42,9 @@ def flops_full_attention(w):
 
 
 def wgrad_shapes(w):
-    """(M, N, K) of the weight-gradient GEMMs of one backward task, in launch order."""
-    T = w.tokens
+    """(M, N, K) of the weight-gradient GEMMs that the backward task completing a group
+    launches, in launch order: the contraction runs over the tokens of the whole group."""
+    T = w.tokens * max(1, w.wgrad_group)
     nq, nkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
     f1 = 2 * w.d_ffn if w.act == 2 else w.d_ffn
     per_layer = [(w.d_model, w.d_ffn, T), (f1, w.d_model, T), (w.d_model, nq, T), (nq + 2 * nkv, w.d_model, T)]
@@ -124,6 +125,7 @@ def bench_kernels(w, torch, B, inp):
     dev = "cuda:0"
     bf = torch.bfloat16
     T, d, f = w.tokens, w.d_model, w.d_ffn
+    Tg = T * max(1, w.wgrad_group)     # a weight gradient contracts over its whole group's tokens
     nq, nkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
     nqkv, f1 = nq + 2 * nkv, (2 * f if w.act == inp.ACT_SWIGLU else f)
     strm = torch.cuda.current_stream().cuda_stream
@@ -149,8 +151,8 @@ def bench_kernels(w, torch, B, inp):
     gemms = [("qkv fwd", T, nqkv, d, 0, 0, 0), ("attn-out fwd", T, d, nq, 0, 0, 0), ("ffn-up fwd", T, f1, d, 0, 0, 0),
              ("ffn-down fwd", T, d, f, 0, 0, 0), ("qkv dgrad", T, d, nqkv, 0, 1, 0), ("attn-out dgrad", T, nq, d, 0, 1, 0),
              ("ffn-up dgrad", T, d, f1, 0, 1, 0), ("ffn-down dgrad", T, f, d, 0, 1, 0),
-             ("qkv wgrad", nqkv, d, T, 1, 1, 2), ("attn-out wgrad", d, nq, T, 1, 1, 2),
-             ("ffn-up wgrad", f1, d, T, 1, 1, 2), ("ffn-down wgrad", d, f, T, 1, 1, 2)]
+             ("qkv wgrad", nqkv, d, Tg, 1, 1, 2), ("attn-out wgrad", d, nq, Tg, 1, 1, 2),
+             ("ffn-up wgrad", f1, d, Tg, 1, 1, 2), ("ffn-down wgrad", d, f, Tg, 1, 1, 2)]
     for name, M, N, K, aks, bks, mode in gemms:
         A = torch.randn((K, M) if aks else (M, K), device=dev).to(bf)
         Bm = (torch.randn((K, N) if bks else (N, K), device=dev) * 0.02).to(bf)
@@ -248,6 +250,9 @@ def main():
     ap.add_argument("--remat", action="store_true",
                     help="rematerialisation: keep only each layer's input, recompute the layer in the backward "
                          "(the recomputation is not counted in the TFLOP/s)")
+    ap.add_argument("--wgrad-group", type=int, default=None,
+                    help="microbatches per weight-gradient group (jpp_layer_config.wgrad_group); 1 = every "
+                         "backward task accumulates its own weight gradients; default min(8, M), 1 with --remat")
     ap.add_argument("--schedule", choices=["gpipe", "1f1b", "interleaved"], default=None,
                     help="override the configuration's schedule (same P, rank, V)")
     ap.add_argument("--optimizer", choices=["sgd", "adamw"], default=None,
@@ -256,9 +261,10 @@ def main():
     ap.add_argument("--kernels", action="store_true",
                     help="time every kernel of one layer alone at the configuration's shapes and print one "
                          "JSON line per kernel with its rate against its own roofline")
-    ap.add_argument("--streams", type=int, choices=[1, 2, 3], default=3,
+    ap.add_argument("--streams", type=int, choices=[1, 2, 3], default=None,
                     help="streams a run computes on: 3 = forward, input-gradient chain and weight-gradient GEMMs "
-                         "on their own streams (default), 2 = forward + backward, 1 = everything on one")
+                         "on their own streams, 2 = forward + backward, 1 = everything on one; default: the "
+                         "library picks 1 or 3 from the stage's GEMM sizes")
     ap.add_argument("--pipeline", action="store_true",
                     help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
@@ -282,7 +288,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     w = inp.CONFIGS[a.config]
-    B.jpp_set_stream_mode(3 - a.streams)
+    B.jpp_set_stream_mode(-1 if a.streams is None else 3 - a.streams)
+    from dataclasses import replace
+    kind = {"gpipe": inp.SCHED_GPIPE, "1f1b": inp.SCHED_1F1B, "interleaved": inp.SCHED_INTERLEAVED,
+            None: w.sched}[a.schedule]
+    # weight-gradient groups: by default 8 microbatches (for C4: P, one run of backwards of a
+    # virtual stage in the interleaved schedule); rematerialisation drops what a group keeps
+    group = a.wgrad_group if a.wgrad_group is not None else (1 if a.remat else min(8, w.n_microbatches))
+    w = replace(w, remat=1 if a.remat else 0, sched=kind, wgrad_group=group)
     if a.kernel_only:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -293,11 +306,6 @@ def main():
         print(json.dumps({"kernel_only": True, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
                           "tflops": flops / avg_ms / 1e9}))
         return
-    if a.remat or a.schedule:
-        from dataclasses import replace
-        kind = {"gpipe": inp.SCHED_GPIPE, "1f1b": inp.SCHED_1F1B, "interleaved": inp.SCHED_INTERLEAVED,
-                None: w.sched}[a.schedule]
-        w = replace(w, remat=1 if a.remat else 0, sched=kind)
     if a.kernels:
         return bench_kernels(w, torch, B, inp)
     if a.pipeline:
@@ -308,6 +316,7 @@ def main():
         tasks = [(i, B.JPP_FWD, s) for s in w.stage_ids for i in range(w.n_microbatches)]
         tasks += [(i, B.JPP_BWD, s) for s in reversed(w.stage_ids) for i in range(w.n_microbatches)]
     st = Stage(w, tasks=tasks)
+    streams = 3 - B.jpp_stage_stream_mode(st.h)
     arena_gb = B.jpp_stage_arena_bytes(st.cfg, st.M, st.max_in_flight) / 1e9
     stash_slots = st.max_in_flight
     st.set_params_random(seed=0)
@@ -385,7 +394,7 @@ def main():
                    "d_model": w.d_model, "heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "d_ffn": w.d_ffn,
                    "seq_len": w.seq_len, "microbatch": w.microbatch, "n_microbatches": w.n_microbatches,
                    "schedule": ["gpipe", "1f1b", "interleaved-1f1b"][w.sched], "P": w.P, "rank": w.rank,
-                   "remat": bool(w.remat), "arena_gb": arena_gb, "stash_slots": stash_slots,
+                   "remat": bool(w.remat), "wgrad_group": max(1, w.wgrad_group), "streams": streams, "arena_gb": arena_gb, "stash_slots": stash_slots,
                    "algorithmic_tflop_per_microbatch": algorithmic_flops_per_microbatch(w) / 1e12},
     }
     if w.dtype == inp.DT_BF16:

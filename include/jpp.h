@@ -79,6 +79,18 @@ typedef struct {
                        * forward keeps only each layer's input; the backward re-runs the layer's
                        * forward (without its last GEMM) before differentiating it.  Same results,
                        * bit for bit; the stash shrinks from (8 d + 2 f) T to d T elements per layer */
+  int32_t wgrad_group; /* 0 or 1: every backward task adds its own weight gradients.  g > 1: the
+                       * microbatches g*k .. g*k+g-1 of a stage form a group (the last one may be
+                       * smaller).  Their backward tasks run the input-gradient chain, the bias and
+                       * norm gradients and the send as usual and keep the operands of the
+                       * weight-gradient GEMMs (activations and cotangents) in the stash; the task
+                       * that completes the group runs one GEMM per weight over all the group's
+                       * tokens, so the fp32 gradient is read and written once per group, not
+                       * once per microbatch.  The sums are those of Section 3.1; only the rounding
+                       * order differs from g = 1, and it depends on the microbatch indices alone,
+                       * so the result is still the same for every schedule.  A group occupies g
+                       * stash places from its first forward to its last backward
+                       * (jpp_schedule_validate counts that).  Not together with remat.         */
   int32_t n_virtual;  /* stages owned by this actor                                           */
   int32_t stage_ids[JPP_MAX_VIRTUAL]; /* their global indices (interleaved: v*P + rank)       */
 } jpp_layer_config;
@@ -212,11 +224,17 @@ jpp_status jpp_stage_optimizer_bind(jpp_stage* st, int kind, void* state_dev, si
  * precedes the next run.  Gradients are left as they are (call jpp_stage_zero_grads). */
 jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* step, void* stream);
 
-/* Benchmarking knob, process-wide, read at the start of every run: which streams carry the
- * backward tasks.  0 (default): input-gradient chain and weight-gradient GEMMs on two
- * library-owned streams (three-way overlap with the forward stream); 1: both on one
- * library-owned stream; 2: everything on compute_stream.  Results are identical. */
+/* Process-wide, read at the start of every run: which streams carry the backward tasks.
+ * 0: input-gradient chain and weight-gradient GEMMs on two library-owned streams (three-way
+ * overlap with the forward stream); 1: both on one library-owned stream; 2: everything on
+ * compute_stream.  -1 (default): chosen per stage from its size: 2 when the layer's
+ * smallest GEMM (the attention output projection, 2 T d n_q_heads head_dim flop) has at
+ * least 1e11 flop, because kernels that fill the whole device on their own only disturb each
+ * other's cache when they run side by side, else 0, where overlap fills the gaps that short
+ * kernels leave.  Results are identical in every mode. */
 void jpp_set_stream_mode(int mode);
+/* The mode (0, 1 or 2) that the next run of `st` uses under the current setting. */
+int jpp_stage_stream_mode(const jpp_stage* st);
 
 /* Introspection of the last run (host bookkeeping, used by tests). */
 int jpp_stage_peak_in_flight(const jpp_stage* st);   /* stash slots high-water mark            */

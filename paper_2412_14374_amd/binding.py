@@ -31,7 +31,7 @@ class jpp_layer_config(C.Structure):
                 ("d_ffn", C.c_int32), ("seq_len", C.c_int32), ("microbatch", C.c_int32),
                 ("norm", C.c_int32), ("act", C.c_int32), ("use_bias", C.c_int32), ("rope", C.c_int32),
                 ("rope_theta", C.c_float), ("norm_eps", C.c_float), ("loss_head", C.c_int32),
-                ("vocab", C.c_int32), ("remat", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
+                ("vocab", C.c_int32), ("remat", C.c_int32), ("wgrad_group", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
 
 
 class jpp_optimizer_step(C.Structure):
@@ -82,6 +82,7 @@ _SIGNATURES = {
     "jpp_last_error": (C.c_char_p, []),
     "jpp_set_gemm_variant": (None, [C.c_int]),
     "jpp_set_stream_mode": (None, [C.c_int]),
+    "jpp_stage_stream_mode": (C.c_int, [C.c_void_p]),
     "jpp_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int] * 5),
     "jpp_op_gemm_ws": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                   C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -131,7 +132,8 @@ def make_config(w):
     for f, _ in jpp_layer_config._fields_:
         if f in ("stage_ids", "n_virtual"):
             continue
-        setattr(c, f, getattr(w, f, 0) if f == "remat" else getattr(w, f))   # remat is optional
+        optional = f in ("remat", "wgrad_group")
+        setattr(c, f, getattr(w, f, 0) if optional else getattr(w, f))
     ids = list(w.stage_ids)
     c.n_virtual = len(ids)
     for k, s in enumerate(ids):
@@ -330,6 +332,10 @@ def jpp_stage_host_syncs(h):
 
 def jpp_set_stream_mode(mode):
     lib().jpp_set_stream_mode(mode)
+
+
+def jpp_stage_stream_mode(h):
+    return lib().jpp_stage_stream_mode(h)
 
 
 def jpp_set_gemm_variant(v):

@@ -9,6 +9,7 @@
 // printed in Section 4.2.
 #include "internal.h"
 
+#include <algorithm>
 #include <vector>
 
 namespace jpp {
@@ -83,6 +84,12 @@ int validate_tasks(const jpp_layer_config* cfg, int M, const jpp_task* tasks, in
   if (M < 1 || n < 0 || (n > 0 && !tasks)) { why = "bad task array"; return JPP_ESCHED; }
   // state per (local stage, microbatch): 0 = nothing, 1 = forward done, 2 = backward done
   std::vector<uint8_t> state((size_t)V * M, 0);
+  // Stashes in use.  With weight-gradient groups of g microbatches a group's g places are
+  // taken from its first forward until its last backward (without: g = 1, a stash lives from
+  // its forward to its backward).
+  const int g = cfg->wgrad_group > 1 ? cfg->wgrad_group : 1;
+  const int ng = (M + g - 1) / g;
+  std::vector<int> grp_fwd((size_t)V * ng, 0), grp_bwd((size_t)V * ng, 0);
   int live = 0, hi = 0;
   for (int t = 0; t < n; ++t) {
     const jpp_task& k = tasks[t];
@@ -95,12 +102,13 @@ int validate_tasks(const jpp_layer_config* cfg, int M, const jpp_task* tasks, in
     if (k.ty == JPP_FWD) {
       if (s != 0) { why = "task " + std::to_string(t) + ": duplicate forward"; return JPP_ESCHED; }
       s = 1;
-      if (++live > hi) hi = live;
+      if (grp_fwd[(size_t)local * ng + k.i / g]++ == 0) live += g;
+      if (live > hi) hi = live;
     } else if (k.ty == JPP_BWD) {
       if (s == 0) { why = "task " + std::to_string(t) + ": backward before its forward"; return JPP_ESCHED; }
       if (s == 2) { why = "task " + std::to_string(t) + ": duplicate backward"; return JPP_ESCHED; }
       s = 2;
-      --live;
+      if (++grp_bwd[(size_t)local * ng + k.i / g] == std::min(g, M - k.i / g * g)) live -= g;
     } else {
       why = "task " + std::to_string(t) + ": unknown task type";
       return JPP_ESCHED;

@@ -32,7 +32,7 @@
 namespace jpp {
 
 static thread_local std::string g_last_error;
-static int g_stream_mode = 0;
+static int g_stream_mode = -1;
 
 jpp_status fail(jpp_status code, const std::string& msg) {
   g_last_error = msg;
@@ -65,6 +65,12 @@ bool config_ok(const jpp_layer_config* c, int M, int max_in_flight, std::string&
   if (M < 1 || max_in_flight < 1) { why = "n_microbatches and max_in_flight must be positive"; return false; }
   if (c->loss_head && c->vocab < 1) { why = "loss_head needs vocab"; return false; }
   if (c->remat != 0 && c->remat != 1) { why = "remat must be 0 or 1"; return false; }
+  if (c->wgrad_group < 0 || c->wgrad_group > M) { why = "wgrad_group must be in [0, n_microbatches]"; return false; }
+  if (c->wgrad_group > 1) {
+    if (c->remat) { why = "wgrad_group > 1 keeps the activations a rematerialising stage drops: not with remat"; return false; }
+    if (max_in_flight < c->wgrad_group) { why = "max_in_flight must hold at least one group (wgrad_group stashes)"; return false; }
+    if (c->dtype == JPP_F32 && c->loss_head && c->vocab % 4 != 0) { why = "wgrad_group > 1 in fp32 needs vocab to be a multiple of 4"; return false; }
+  }
   const int chunk = c->dtype == JPP_BF16 ? 8 : 4;
   if (c->head_dim % chunk != 0 || c->head_dim > 256) { why = "head_dim must be a multiple of the 16-byte chunk and <= 256"; return false; }
   if (c->rope && (c->head_dim / 2) % chunk != 0) { why = "rope needs head_dim/2 to be a multiple of the 16-byte chunk"; return false; }
@@ -149,27 +155,41 @@ size_t carve(jpp_stage& st, char* base) {
   st.rope_table = c.rope ? (float*)take((size_t)m.seq * (m.hd / 2) * 2 * 4) : nullptr;
   st.losses = (float*)take((size_t)V * st.M * 4);
 
-  // stash layout inside a slot
+  // stash layout inside a (group) slot
+  const size_t G = st.G = std::max(1, c.wgrad_group);
   {
     size_t o = 0;
-    auto sub = [&](size_t bytes) { size_t r = o; o += align_up(bytes); return r; };
-    st.ls.x = sub(T * m.d * e); st.ls.n1 = sub(T * m.d * e); st.ls.qkv = sub(T * m.nqkv * e);
-    st.ls.O = sub(T * m.nq * e); st.ls.x1 = sub(T * m.d * e); st.ls.n2 = sub(T * m.d * e);
-    st.ls.h = sub(T * m.f1 * e); st.ls.a = sub(T * m.f * e);
-    st.ls.stats1 = sub(2 * T * 4); st.ls.stats2 = sub(2 * T * 4);
-    st.ls.lse = sub((size_t)m.mb * m.Hq * m.seq * 4);
-    st.ls.bytes = o;
+    // a tensor of the G members: packed (GEMM operands of the weight gradients: the members
+    // form one matrix) or each member aligned for itself
+    auto packed = [&](size_t bytes) { Fld f{o, bytes}; o += align_up(bytes * G); return f; };
+    auto apart = [&](size_t bytes) { Fld f{o, align_up(bytes)}; o += align_up(bytes) * G; return f; };
+    LayerStash& ls = st.ls;
+    ls.x = apart(T * m.d * e); ls.n1 = packed(T * m.d * e); ls.qkv = apart(T * m.nqkv * e);
+    ls.O = packed(T * m.nq * e); ls.x1 = apart(T * m.d * e); ls.n2 = packed(T * m.d * e);
+    ls.h = apart(T * m.f1 * e); ls.a = packed(T * m.f * e);
+    ls.stats1 = apart(2 * T * 4); ls.stats2 = apart(2 * T * 4);
+    ls.lse = apart((size_t)m.mb * m.Hq * m.seq * 4);
+    if (G > 1) {
+      ls.cdy = packed(T * m.d * e); ls.cdh = packed(T * m.f1 * e); ls.cdx1 = packed(T * m.d * e);
+      ls.cdqkv = packed(T * m.nqkv * e);
+    }
+    ls.bytes = o;
     o = 0;
     if (c.loss_head) {
-      st.hs.yL = sub(T * m.d * e); st.hs.nf = sub(T * m.d * e); st.hs.statsf = sub(2 * T * 4);
-      st.hs.dz = sub(T * m.vocab * e);
+      st.hs.yL = apart(T * m.d * e); st.hs.nf = packed(T * m.d * e); st.hs.statsf = apart(2 * T * 4);
+      st.hs.dz = packed(T * m.vocab * e);
     }
     st.hs.bytes = o;
     st.xbytes = align_up(T * m.d * e);
     st.slot_bytes = (c.remat ? st.xbytes : st.ls.bytes) * m.L + st.hs.bytes;
   }
-  st.slots.resize(st.max_in_flight);
-  for (auto& s : st.slots) s.base = take(st.slot_bytes);
+  // max_in_flight stashes = max_in_flight / G group slots of G members each
+  const size_t n_gslots = st.max_in_flight / G;
+  st.slots.resize(n_gslots * G);
+  for (size_t gs = 0; gs < n_gslots; ++gs) {
+    char* b = take(st.slot_bytes);
+    for (size_t j = 0; j < G; ++j) { st.slots[gs * G + j].base = b; st.slots[gs * G + j].j = (int)j; }
+  }
   st.remat_f = c.remat ? take(st.ls.bytes) : nullptr;
   st.remat_b = c.remat ? take(st.ls.bytes) : nullptr;
   st.tx.resize(kTxBuffers);
@@ -240,32 +260,33 @@ const void* pptr(const jpp_stage& st, int v, long off) {
 }
 float* gptr(const jpp_stage& st, int v, long off) { return off < 0 ? nullptr : st.grads[v] + off; }
 
-// Forward of layer l of local stage v on stream s: input x, every intermediate at the
-// LayerStash offsets from b, output to y (y == nullptr: the last GEMM is skipped, which is
-// all the backward needs when it recomputes a layer).
-hipError_t layer_forward(jpp_stage& st, hipStream_t s, int v, int l, char* x, char* b, char* y) {
+// Forward of layer l of local stage v on stream s: input w.x, every intermediate to its place
+// in w, output to y (y == nullptr: the last GEMM is skipped, which is all the backward needs
+// when it recomputes a layer).
+hipError_t layer_forward(jpp_stage& st, hipStream_t s, int v, int l, const LayerView& w, char* y) {
+  char* x = w.x;
   const Dims& m = st.dm;
   const jpp_layer_config& c = st.cfg;
   const int dt = c.dtype;
   const auto& o = st.loff[l];
   K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, x, pptr(st, v, o.ln1_g), pptr(st, v, o.ln1_b),
-                        b + st.ls.n1, (float*)(b + st.ls.stats1), s));
-  K_TRY(gemm(st, s, m.T, m.nqkv, m.d, b + st.ls.n1, m.d, false, pptr(st, v, o.wqkv), m.d, false, b + st.ls.qkv,
+                        w.n1, (float*)(w.stats1), s));
+  K_TRY(gemm(st, s, m.T, m.nqkv, m.d, w.n1, m.d, false, pptr(st, v, o.wqkv), m.d, false, w.qkv,
              m.nqkv, OUT_STORE, pptr(st, v, o.bqkv), nullptr));
-  if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, st.rope_table, false, s));
-  AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
+  if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, w.qkv, st.rope_table, false, s));
+  AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, w.qkv, w.O, (float*)(w.lse),
              nullptr, nullptr, nullptr};
   K_TRY(attention_fwd(st, s, a));
-  K_TRY(gemm(st, s, m.T, m.d, m.nq, b + st.ls.O, m.nq, false, pptr(st, v, o.wo), m.nq, false, b + st.ls.x1, m.d,
+  K_TRY(gemm(st, s, m.T, m.d, m.nq, w.O, m.nq, false, pptr(st, v, o.wo), m.nq, false, w.x1, m.d,
              OUT_STORE, pptr(st, v, o.bo), x));
-  K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, b + st.ls.x1, pptr(st, v, o.ln2_g),
-                        pptr(st, v, o.ln2_b), b + st.ls.n2, (float*)(b + st.ls.stats2), s));
-  K_TRY(gemm(st, s, m.T, m.f1, m.d, b + st.ls.n2, m.d, false, pptr(st, v, o.w1), m.d, false, b + st.ls.h, m.f1,
+  K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, w.x1, pptr(st, v, o.ln2_g),
+                        pptr(st, v, o.ln2_b), w.n2, (float*)(w.stats2), s));
+  K_TRY(gemm(st, s, m.T, m.f1, m.d, w.n2, m.d, false, pptr(st, v, o.w1), m.d, false, w.h, m.f1,
              OUT_STORE, pptr(st, v, o.b1), nullptr));
-  K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, b + st.ls.h, b + st.ls.a, s));
+  K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, w.h, w.a, s));
   if (y)
-    K_TRY(gemm(st, s, m.T, m.d, m.f, b + st.ls.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
-               pptr(st, v, o.b2), b + st.ls.x1));
+    K_TRY(gemm(st, s, m.T, m.d, m.f, w.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
+               pptr(st, v, o.b2), w.x1));
   return hipSuccess;
 }
 
@@ -276,17 +297,17 @@ hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out)
   const jpp_layer_config& c = st.cfg;
   hipStream_t s = st.cs;
   const int dt = c.dtype;
-  char* hb = st.x_of(slot, m.L);   // head stash
+  const HeadView hv = st.head_view(slot, slot.j);
   for (int l = 0; l < m.L; ++l) {
-    char* y = (l + 1 < m.L) ? st.x_of(slot, l + 1) : (st.is_head(v) ? hb + st.hs.yL : y_out);
-    K_TRY(layer_forward(st, s, v, l, st.x_of(slot, l), st.rest_of(slot, l, false), y));
+    char* y = (l + 1 < m.L) ? st.layer_view(slot, l + 1, false).x : (st.is_head(v) ? hv.yL : y_out);
+    K_TRY(layer_forward(st, s, v, l, st.layer_view(slot, l, false), y));
   }
   if (st.is_head(v)) {
-    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, hb + st.hs.yL, pptr(st, v, st.lnf_g),
-                          pptr(st, v, st.lnf_b), hb + st.hs.nf, (float*)(hb + st.hs.statsf), s));
-    K_TRY(gemm(st, s, m.T, m.vocab, m.d, hb + st.hs.nf, m.d, false, pptr(st, v, st.w_head), m.d, false, st.z,
+    K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, hv.yL, pptr(st, v, st.lnf_g),
+                          pptr(st, v, st.lnf_b), hv.nf, (float*)hv.statsf, s));
+    K_TRY(gemm(st, s, m.T, m.vocab, m.d, hv.nf, m.d, false, pptr(st, v, st.w_head), m.d, false, st.z,
                m.vocab, OUT_STORE_F32, nullptr, nullptr));
-    K_TRY(launch_cross_entropy(dt, m.T, m.vocab, st.z, st.targets[(size_t)v * st.M + i], hb + st.hs.dz,
+    K_TRY(launch_cross_entropy(dt, m.T, m.vocab, st.z, st.targets[(size_t)v * st.M + i], hv.dz,
                                st.row_loss, st.losses + (size_t)v * st.M + i, s));
   }
   return hipSuccess;
@@ -300,73 +321,86 @@ hipError_t wgrad(jpp_stage& st, int M, int N, int K, const void* dy, int ldy, co
   return gemm(st, st.ws, M, N, K, dy, ldy, true, x, ldx, true, G, N, OUT_ACC_F32, nullptr, nullptr);
 }
 
-// Backward of local stage v: reads the output cotangent from `dy_in` (ignored for a
-// loss-head stage), adds this microbatch's parameter gradients to the fp32 buffers and
-// writes the input cotangent to `dx_out`.  The input-gradient chain runs on the backward
-// stream, the weight-gradient GEMMs on the wgrad stream.
-hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in, char* dx_out) {
+// Backward of local stage v for the microbatch in `slot`: reads the output cotangent from
+// `dy_in` (ignored for a loss-head stage; with grouping it already lies in the stash, at the
+// top layer's cdy), adds this microbatch's parameter gradients to the fp32 buffers and writes
+// the input cotangent to `dx_out`.  The input-gradient chain runs on the backward stream, the
+// weight-gradient GEMMs on the wgrad stream.  `wg_members`: how many members' worth of rows
+// the weight-gradient GEMMs contract over, starting at the group's first member; 0 = none
+// now (a later member of the group runs them).  Without grouping it is always 1.
+hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in, char* dx_out, int wg_members) {
   const Dims& m = st.dm;
   const jpp_layer_config& c = st.cfg;
   hipStream_t s = st.bs;
   const int dt = c.dtype;
+  const bool grouped = st.G > 1;
+  const int K = wg_members * m.T;
   int cur = 0;
   const char* dy = dy_in;
-  // the workspace buffers are about to be overwritten: the previous backward's weight
-  // gradients, which read them, must be done
-  if (st.w_task.recorded) K_TRY(hipStreamWaitEvent(s, st.w_task.ev, 0));
+  // Without grouping the cotangents live in workspace buffers that are about to be
+  // overwritten: the previous backward's weight gradients, which read them, must be done.
+  // With grouping every cotangent a weight gradient reads has its own place in the stash.
+  if (!grouped && st.w_task.recorded) K_TRY(hipStreamWaitEvent(s, st.w_task.ev, 0));
   if (st.is_head(v)) {
-    char* hb = st.x_of(slot, m.L);
-    K_TRY(wgrad(st, m.vocab, m.d, m.T, hb + st.hs.dz, m.vocab, hb + st.hs.nf, m.d, gptr(st, v, st.w_head)));
-    K_TRY(gemm(st, s, m.T, m.d, m.vocab, hb + st.hs.dz, m.vocab, false, pptr(st, v, st.w_head), m.d, true, st.dn,
+    const HeadView hv = st.head_view(slot, slot.j), hg = st.head_view(slot, 0);
+    if (wg_members) K_TRY(wgrad(st, m.vocab, m.d, K, hg.dz, m.vocab, hg.nf, m.d, gptr(st, v, st.w_head)));
+    K_TRY(gemm(st, s, m.T, m.d, m.vocab, hv.dz, m.vocab, false, pptr(st, v, st.w_head), m.d, true, st.dn,
                m.d, OUT_STORE, nullptr, nullptr));
-    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, hb + st.hs.yL, pptr(st, v, st.lnf_g), (float*)(hb + st.hs.statsf),
-                          st.dn, nullptr, st.dbuf[cur], gptr(st, v, st.lnf_g), gptr(st, v, st.lnf_b), st.partial,
-                          s));
-    dy = st.dbuf[cur];
+    char* top = grouped ? st.layer_view(slot, m.L - 1, true).cdy : st.dbuf[cur];
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, hv.yL, pptr(st, v, st.lnf_g), (float*)hv.statsf,
+                          st.dn, nullptr, top, gptr(st, v, st.lnf_g), gptr(st, v, st.lnf_b), st.partial, s));
+    dy = top;
     cur ^= 1;
   }
   for (int l = m.L - 1; l >= 0; --l) {
-    char* b = st.rest_of(slot, l, true);
-    char* xl = st.x_of(slot, l);
+    const LayerView w = st.layer_view(slot, l, true);      // this member
+    const LayerView g = st.layer_view(slot, l, 0, true);   // the group's packed matrices
     const auto& o = st.loff[l];
-    char* dx = (l == 0) ? dx_out : st.dbuf[cur];
-    if (l != m.L - 1) {
+    char* dx = (l == 0) ? dx_out : (grouped ? st.layer_view(slot, l - 1, true).cdy : st.dbuf[cur]);
+    char* dh = grouped ? w.cdh : st.dh;
+    char* dx1 = grouped ? w.cdx1 : st.dx1;
+    char* dqkv = grouped ? w.cdqkv : st.dqkv;
+    // operands of the weight gradients: the whole group's rows, or this microbatch's
+    const char* wdy = grouped ? g.cdy : dy;
+    const char* wdh = grouped ? g.cdh : dh;
+    const char* wdx1 = grouped ? g.cdx1 : dx1;
+    const char* wdqkv = grouped ? g.cdqkv : dqkv;
+    if (!grouped && l != m.L - 1) {
       // the layer above's weight gradients read dh, dx1, dqkv (and, with rematerialisation,
       // the recomputed activations), which this layer rewrites
       K_TRY(hipEventRecord(st.w_layer.ev, st.ws));
       K_TRY(hipStreamWaitEvent(s, st.w_layer.ev, 0));
     }
     // Section 2.2.1, rematerialisation: only the layer's input was kept; run its forward again
-    if (c.remat) K_TRY(layer_forward(st, s, v, l, xl, b, nullptr));
+    if (c.remat) K_TRY(layer_forward(st, s, v, l, w, nullptr));
     // FFN down projection
-    K_TRY(wgrad(st, m.d, m.f, m.T, dy, m.d, b + st.ls.a, m.f, gptr(st, v, o.w2)));
+    if (wg_members) K_TRY(wgrad(st, m.d, m.f, K, wdy, m.d, g.a, m.f, gptr(st, v, o.w2)));
     if (o.b2 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dy, m.d, gptr(st, v, o.b2), st.partial, s));
     K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, st.da, m.f, OUT_STORE, nullptr,
                nullptr));
-    K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, b + st.ls.h, st.da, st.dh, s));
+    K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, w.h, st.da, dh, s));
     // FFN up projection
-    K_TRY(wgrad(st, m.f1, m.d, m.T, st.dh, m.f1, b + st.ls.n2, m.d, gptr(st, v, o.w1)));
-    if (o.b1 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.f1, st.dh, m.f1, gptr(st, v, o.b1), st.partial, s));
-    K_TRY(gemm(st, s, m.T, m.d, m.f1, st.dh, m.f1, false, pptr(st, v, o.w1), m.d, true, st.dn, m.d, OUT_STORE,
+    if (wg_members) K_TRY(wgrad(st, m.f1, m.d, K, wdh, m.f1, g.n2, m.d, gptr(st, v, o.w1)));
+    if (o.b1 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.f1, dh, m.f1, gptr(st, v, o.b1), st.partial, s));
+    K_TRY(gemm(st, s, m.T, m.d, m.f1, dh, m.f1, false, pptr(st, v, o.w1), m.d, true, st.dn, m.d, OUT_STORE,
                nullptr, nullptr));
-    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, b + st.ls.x1, pptr(st, v, o.ln2_g), (float*)(b + st.ls.stats2),
-                          st.dn, dy, st.dx1, gptr(st, v, o.ln2_g), gptr(st, v, o.ln2_b), st.partial, s));
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, w.x1, pptr(st, v, o.ln2_g), (float*)w.stats2,
+                          st.dn, dy, dx1, gptr(st, v, o.ln2_g), gptr(st, v, o.ln2_b), st.partial, s));
     // attention output projection
-    K_TRY(wgrad(st, m.d, m.nq, m.T, st.dx1, m.d, b + st.ls.O, m.nq, gptr(st, v, o.wo)));
-    if (o.bo >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, st.dx1, m.d, gptr(st, v, o.bo), st.partial, s));
-    K_TRY(gemm(st, s, m.T, m.nq, m.d, st.dx1, m.d, false, pptr(st, v, o.wo), m.nq, true, st.dO, m.nq, OUT_STORE,
+    if (wg_members) K_TRY(wgrad(st, m.d, m.nq, K, wdx1, m.d, g.O, m.nq, gptr(st, v, o.wo)));
+    if (o.bo >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dx1, m.d, gptr(st, v, o.bo), st.partial, s));
+    K_TRY(gemm(st, s, m.T, m.nq, m.d, dx1, m.d, false, pptr(st, v, o.wo), m.nq, true, st.dO, m.nq, OUT_STORE,
                nullptr, nullptr));
-    AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, b + st.ls.qkv, b + st.ls.O, (float*)(b + st.ls.lse),
-               st.dO, st.dqkv, st.delta};
+    AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, w.qkv, w.O, (float*)w.lse, st.dO, dqkv, st.delta};
     K_TRY(attention_bwd(st, s, a));
-    if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, st.dqkv, st.rope_table, true, s));
+    if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, dqkv, st.rope_table, true, s));
     // QKV projection
-    K_TRY(wgrad(st, m.nqkv, m.d, m.T, st.dqkv, m.nqkv, b + st.ls.n1, m.d, gptr(st, v, o.wqkv)));
-    if (o.bqkv >= 0) K_TRY(launch_bias_grad(dt, m.T, m.nqkv, st.dqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
-    K_TRY(gemm(st, s, m.T, m.d, m.nqkv, st.dqkv, m.nqkv, false, pptr(st, v, o.wqkv), m.d, true, st.dn, m.d,
+    if (wg_members) K_TRY(wgrad(st, m.nqkv, m.d, K, wdqkv, m.nqkv, g.n1, m.d, gptr(st, v, o.wqkv)));
+    if (o.bqkv >= 0) K_TRY(launch_bias_grad(dt, m.T, m.nqkv, dqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
+    K_TRY(gemm(st, s, m.T, m.d, m.nqkv, dqkv, m.nqkv, false, pptr(st, v, o.wqkv), m.d, true, st.dn, m.d,
                OUT_STORE, nullptr, nullptr));
-    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, xl, pptr(st, v, o.ln1_g), (float*)(b + st.ls.stats1),
-                          st.dn, st.dx1, dx, gptr(st, v, o.ln1_g), gptr(st, v, o.ln1_b), st.partial, s));
+    K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, w.x, pptr(st, v, o.ln1_g), (float*)w.stats1,
+                          st.dn, dx1, dx, gptr(st, v, o.ln1_g), gptr(st, v, o.ln1_b), st.partial, s));
     dy = dx;
     cur ^= 1;
   }
@@ -434,7 +468,7 @@ hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* out
 hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes, hipEvent_t produced) {
   if (produced) K_TRY(hipStreamWaitEvent(st.ss, produced, 0));  // the sending actor's copy
   if (slot.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, slot.freed.ev, 0));
-  K_TRY(hipMemcpyAsync(st.x_of(slot, 0), src, bytes, hipMemcpyDeviceToDevice, st.ss));
+  K_TRY(hipMemcpyAsync(st.layer_view(slot, 0, false).x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(slot.rx.ev, st.ss));
   slot.rx_issued = true;
   return hipSuccess;
@@ -627,8 +661,9 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
   }
   st->cs = cs; st->ss = ss;
   // which streams carry the backward (benchmarking knob; the default is three-way overlap)
-  st->bs = g_stream_mode == 2 ? cs : st->bs_own;
-  st->ws = g_stream_mode == 2 ? cs : (g_stream_mode == 1 ? st->bs_own : st->ws_own);
+  const int mode = jpp_stage_stream_mode(st);
+  st->bs = mode == 2 ? cs : st->bs_own;
+  st->ws = mode == 2 ? cs : (mode == 1 ? st->bs_own : st->ws_own);
   // the internal streams start after everything already queued on the compute stream
   // (e.g. jpp_stage_zero_grads)
   HIP_TRY(hipEventRecord(st->run_start.ev, cs));
@@ -638,7 +673,10 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
   st->w_task.recorded = false;
   st->peak_in_flight = 0; st->pending_peak = 0; st->prefetched = 0; st->host_syncs = 0;
   st->free_slots.clear();
-  for (int k = st->max_in_flight - 1; k >= 0; --k) st->free_slots.push_back(k);
+  for (int k = (int)st->slots.size() / st->G - 1; k >= 0; --k) st->free_slots.push_back(k);
+  st->grp_slot.assign((size_t)st->cfg.n_virtual * st->n_groups(), -1);
+  st->grp_bwd.assign((size_t)st->cfg.n_virtual * st->n_groups(), 0);
+  st->grp_fwd.assign((size_t)st->cfg.n_virtual * st->n_groups(), 0);
   for (auto& s : st->slots) s.rx_issued = false;
   // staging buffers still pending from the previous run are ordered by the waits above
   st->tx_free.clear(); st->tx_pending.clear();
@@ -668,9 +706,14 @@ hipError_t issue_recv(jpp_stage* st, int k, bool ahead) {
   if (t.ty == JPP_FWD) {
     if (st->slot_of[key] >= 0) return hipSuccess;  // already prefetched
     if (!st->avail_x.empty() && !st->avail_x[key]) return hipErrorNotReady;
-    if (st->free_slots.empty()) return hipErrorNotReady;  // retried when the task itself starts
-    const int sl = st->free_slots.back();
-    st->free_slots.pop_back();
+    // the first forward of a weight-gradient group opens a group slot, the others join it
+    int& gs = st->grp_slot[(size_t)v * st->n_groups() + t.i / st->G];
+    if (gs < 0) {
+      if (st->free_slots.empty()) return hipErrorNotReady;  // retried when the task itself starts
+      gs = st->free_slots.back();
+      st->free_slots.pop_back();
+    }
+    const int sl = gs * st->G + t.i % st->G;
     st->slot_of[key] = sl;
     if (ahead) ++st->prefetched;
     return issue_recv_x(*st, st->slots[sl], st->inbox_x[key], bbytes,
@@ -713,7 +756,8 @@ jpp_status run_step(jpp_stage* st) {
   }
   if (t.ty == JPP_FWD) {
     Slot& slot = st->slots[st->slot_of[key]];
-    ++st->live;
+    // stashes in use: a group holds all its G places from its first forward on
+    if (st->grp_fwd[(size_t)v * st->n_groups() + t.i / st->G]++ == 0) st->live += st->G;
     st->peak_in_flight = std::max(st->peak_in_flight, st->live);
     HIP_TRY(hipStreamWaitEvent(cs, slot.rx.ev, 0));
     int txb = -1;
@@ -728,31 +772,52 @@ jpp_status run_step(jpp_stage* st) {
     Slot& slot = st->slots[st->slot_of[key]];
     const char* dy = nullptr;
     HIP_TRY(hipStreamWaitEvent(st->bs, slot.fwd_done.ev, 0));  // the forward that filled the stash
+    const bool grouped = st->G > 1;
     if (!head) {
       CotBuf& cb = st->cot[st->cot_of[key]];
       HIP_TRY(hipStreamWaitEvent(st->bs, cb.rx.ev, 0));
       dy = cb.p;
+      if (grouped) {
+        // the group's weight gradients read this cotangent later: move it into the stash and
+        // give the ring entry back at once
+        char* kept = st->layer_view(slot, m.L - 1, true).cdy;
+        HIP_TRY(hipMemcpyAsync(kept, cb.p, bbytes, hipMemcpyDeviceToDevice, st->bs));
+        HIP_TRY(hipEventRecord(cb.freed.ev, st->bs));
+        cb.freed.recorded = true;
+        dy = kept;
+      }
     }
+    // the task that completes its group runs the group's weight gradients
+    const int grp = t.i / st->G;
+    const size_t gkey = (size_t)v * st->n_groups() + grp;
+    const bool completes = ++st->grp_bwd[gkey] == st->group_size(grp);
     int txb = -1;
     HIP_TRY(acquire_tx(*st, st->bs, txb));
-    e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p);
+    e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p, completes ? st->group_size(grp) : 0);
     if (e != hipSuccess) return fail_hip(e, "backward kernels");
     // enqueue_backward left the wgrad stream behind both the input-gradient chain and the
     // weight gradients of this task: events recorded there cover every reader
-    if (!head) {
+    if (!head && !grouped) {
       CotBuf& cb = st->cot[st->cot_of[key]];
       HIP_TRY(hipEventRecord(cb.freed.ev, st->ws));
       cb.freed.recorded = true;
     }
     HIP_TRY(send_and_delete(*st, st->bs, txb, st->outbox_dx[key], bbytes,
                             st->signal_dx.empty() ? nullptr : st->signal_dx[key]));
-    // the stash is dead: release the slot; the event protects it against an early receive
-    // on the side stream (and, through the receive, against the next forward)
-    HIP_TRY(hipEventRecord(slot.freed.ev, st->ws));
-    slot.freed.recorded = true;
-    st->free_slots.push_back(st->slot_of[key]);
     st->slot_of[key] = -1;
-    --st->live;
+    if (completes) {
+      // the group's stash is dead: release its slot; the events protect every member against
+      // an early receive on the side stream (and, through the receive, against the next forward)
+      const int gs = st->grp_slot[gkey];
+      for (int j = 0; j < st->G; ++j) {
+        Slot& member = st->slots[(size_t)gs * st->G + j];
+        HIP_TRY(hipEventRecord(member.freed.ev, st->ws));
+        member.freed.recorded = true;
+      }
+      st->free_slots.push_back(gs);
+      st->grp_slot[gkey] = -1;
+      st->live -= st->G;
+    }
   }
   st->run_next = k + 1;
   return JPP_OK;
@@ -863,7 +928,13 @@ jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* o,
   return JPP_OK;
 }
 
-void jpp_set_stream_mode(int mode) { jpp::g_stream_mode = mode < 0 || mode > 2 ? 0 : mode; }
+void jpp_set_stream_mode(int mode) { jpp::g_stream_mode = mode < 0 || mode > 2 ? -1 : mode; }
+
+int jpp_stage_stream_mode(const jpp_stage* st) {
+  if (jpp::g_stream_mode >= 0 || !st) return std::max(0, jpp::g_stream_mode);
+  const jpp::Dims& m = st->dm;
+  return 2.0 * m.T * m.d * m.nq >= 1e11 ? 2 : 0;
+}
 
 int jpp_stage_peak_in_flight(const jpp_stage* st) { return st ? st->peak_in_flight : -1; }
 int jpp_stage_pending_peak(const jpp_stage* st) { return st ? st->pending_peak : -1; }

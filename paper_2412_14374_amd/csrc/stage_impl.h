@@ -2,6 +2,7 @@
 // pipeline driver.  Not part of the C interface.
 #pragma once
 
+#include <algorithm>
 #include <deque>
 #include <string>
 #include <vector>
@@ -23,11 +24,21 @@ struct Dims {
   size_t esz;
 };
 
-// Element offsets (in bytes from the slot base) of one layer's stash.
+// One tensor of the stash: a slot holds it for the g microbatches of a weight-gradient group
+// (g = 1 without grouping), member j at off + j * stride bytes.  The operands of the
+// weight-gradient GEMMs are packed (stride = the tensor's own size), so that a group's
+// members form one matrix with g * T rows.
+struct Fld { size_t off = 0, stride = 0; };
+// One layer's stash.  cdy, cdh, cdx1, cdqkv exist with grouping only: the cotangents that
+// the weight gradients of w2, w1, wo, wqkv contract with, kept until the group is complete.
 struct LayerStash {
-  size_t x, n1, qkv, O, x1, n2, h, a, stats1, stats2, lse, bytes;
+  Fld x, n1, qkv, O, x1, n2, h, a, stats1, stats2, lse, cdy, cdh, cdx1, cdqkv;
+  size_t bytes = 0;
 };
-struct HeadStash { size_t yL, nf, statsf, dz, bytes; };
+struct HeadStash { Fld yL, nf, statsf, dz; size_t bytes = 0; };
+// The same, as addresses for one member of one slot.
+struct LayerView { char *x, *n1, *qkv, *O, *x1, *n2, *h, *a, *stats1, *stats2, *lse, *cdy, *cdh, *cdx1, *cdqkv; };
+struct HeadView { char *yL, *nf, *statsf, *dz; };
 
 struct Event {
   hipEvent_t ev = nullptr;
@@ -35,8 +46,9 @@ struct Event {
 };
 
 struct Slot {
-  char* base = nullptr;
-  Event freed;  // recorded on the compute stream when the backward that used the slot is done
+  char* base = nullptr;  // of the group slot this member belongs to
+  int j = 0;             // member index in the group
+  Event freed;  // recorded on the wgrad stream when the last reader of the (group) slot is done
   Event rx;     // recorded on the side stream when the received input is in place
   Event fwd_done;  // recorded on the compute stream when the forward that filled the slot is enqueued
   bool rx_issued = false;
@@ -59,7 +71,8 @@ struct CotBuf {
 struct jpp_stage {
   typedef jpp::Dims Dims; typedef jpp::ParamInfo ParamInfo; typedef jpp::LayerStash LayerStash;
   typedef jpp::HeadStash HeadStash; typedef jpp::Event Event; typedef jpp::Slot Slot;
-  typedef jpp::TxBuf TxBuf; typedef jpp::CotBuf CotBuf;
+  typedef jpp::TxBuf TxBuf; typedef jpp::CotBuf CotBuf; typedef jpp::Fld Fld;
+  typedef jpp::LayerView LayerView; typedef jpp::HeadView HeadView;
   jpp_layer_config cfg;
   int M = 0, max_in_flight = 0;
   Dims dm{};
@@ -84,17 +97,26 @@ struct jpp_stage {
   // stash, remat_f for the forward stream and remat_b for the backward's recomputation.
   size_t xbytes = 0;
   char *remat_f = nullptr, *remat_b = nullptr;
-  // input of layer l of the stash in `slot` (l == n_layers: start of the head stash)
-  char* x_of(const Slot& slot, int l) const {
-    if (cfg.remat) return slot.base + (size_t)l * xbytes;
-    return slot.base + (size_t)l * ls.bytes + (l < cfg.n_layers ? ls.x : 0);
+  int G = 1;   // weight-gradient group size (cfg.wgrad_group, at least 1)
+  int group_size(int grp) const { return std::min(G, M - grp * G); }
+  int n_groups() const { return (M + G - 1) / G; }
+  // Addresses of layer l's stash for member j of the slot's group (j = 0: the start of the
+  // group's packed matrices).  `backward` picks the rematerialisation workspace.
+  LayerView layer_view(const Slot& slot, int l, int j, bool backward) const {
+    char* b = cfg.remat ? (backward ? remat_b : remat_f) : slot.base + (size_t)l * ls.bytes;
+    auto at = [&](const Fld& f) { return b + f.off + (size_t)j * f.stride; };
+    LayerView w{at(ls.x), at(ls.n1), at(ls.qkv), at(ls.O), at(ls.x1), at(ls.n2), at(ls.h), at(ls.a),
+                at(ls.stats1), at(ls.stats2), at(ls.lse), at(ls.cdy), at(ls.cdh), at(ls.cdx1), at(ls.cdqkv)};
+    if (cfg.remat) w.x = slot.base + (size_t)l * xbytes;
+    return w;
   }
-  // base for every other LayerStash offset of layer l
-  char* rest_of(const Slot& slot, int l, bool backward) const {
-    if (cfg.remat) return backward ? remat_b : remat_f;
-    return slot.base + (size_t)l * ls.bytes;
+  LayerView layer_view(const Slot& slot, int l, bool backward) const { return layer_view(slot, l, slot.j, backward); }
+  HeadView head_view(const Slot& slot, int j) const {
+    char* b = slot.base + (size_t)cfg.n_layers * (cfg.remat ? xbytes : ls.bytes);
+    auto at = [&](const Fld& f) { return b + f.off + (size_t)j * f.stride; };
+    return HeadView{at(hs.yL), at(hs.nf), at(hs.statsf), at(hs.dz)};
   }
-  std::vector<Slot> slots;
+  std::vector<Slot> slots;   // G members per group slot: slots[gs * G + j]
   std::vector<TxBuf> tx;
   std::vector<CotBuf> cot;
   // workspace
@@ -118,7 +140,8 @@ struct jpp_stage {
   hipStream_t bs_own = nullptr, ws_own = nullptr;   // the two library-owned streams
   Event end_compute, end_side, run_start, b2w, w_layer, w_task, b_end, w_end;
   int peak_in_flight = 0, pending_peak = 0, prefetched = 0, host_syncs = 0;
-  std::vector<int> free_slots;
+  std::vector<int> free_slots;      // free group slots
+  std::vector<int> grp_slot, grp_fwd, grp_bwd;  // per (v, group): its group slot (-1: none), forwards / backwards enqueued
   std::vector<int> tx_free;
   std::deque<int> tx_pending;
   // the task list being enqueued (between run_begin and run_end)

@@ -35,7 +35,8 @@ class Stage:
         self.tasks = tasks if tasks is not None else default_tasks(w)
         peak = B.jpp_schedule_validate(self.cfg, self.M, self.tasks)
         # one slot above the schedule's peak lets the next forward's input be prefetched
-        self.max_in_flight = max_in_flight if max_in_flight is not None else peak + 1
+        # (with weight-gradient groups a prefetch may open a group: one group's worth above it)
+        self.max_in_flight = max_in_flight if max_in_flight is not None else peak + max(1, self.cfg.wgrad_group)
         nbytes = B.jpp_stage_arena_bytes(self.cfg, self.M, self.max_in_flight)
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         base = (self.arena.data_ptr() + 255) // 256 * 256

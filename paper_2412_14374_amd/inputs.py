@@ -44,6 +44,7 @@ class Workload:
     loss_head: int = 0
     vocab: int = 0
     remat: int = 0                   # 1: keep only each layer's input, recompute in the backward
+    wgrad_group: int = 0             # g > 1: one weight-gradient GEMM per group of g microbatches
     # schedule: kind, pipeline depth P, this actor's rank, virtual stages V
     sched: int = SCHED_GPIPE
     P: int = 1

@@ -83,6 +83,39 @@ def test_validator_peaks_follow_section_2_2_1():
     assert peak == osch.validate(osch.interleaved_1f1b(8, 0, 2, 32), [0, 8], 32) == 23
 
 
+def test_validator_counts_group_places():
+    """With weight-gradient groups of g a group holds g stash places from its first forward to
+    its last backward; checked against a brute-force count over the generated lists."""
+    def brute(tasks, M, g):
+        first, done, live, hi = set(), {}, 0, 0
+        for (i, ty, s) in tasks:
+            key = (s, i // g)
+            if ty == B.JPP_FWD:
+                if key not in first:
+                    first.add(key)
+                    live += g
+                hi = max(hi, live)
+            else:
+                done[key] = done.get(key, 0) + 1
+                if done[key] == min(g, M - (i // g) * g):
+                    live -= g
+        return hi
+    for kind, P, r, V, M in [(inp.SCHED_GPIPE, 4, 1, 1, 7), (inp.SCHED_1F1B, 4, 0, 1, 8), (inp.SCHED_1F1B, 4, 3, 1, 5),
+                             (inp.SCHED_INTERLEAVED, 8, 0, 2, 32), (inp.SCHED_INTERLEAVED, 2, 1, 3, 6)]:
+        ids = [v * P + r for v in range(V)]
+        tasks = B.jpp_schedule_make(kind, P, r, V, M)
+        for g in (1, 2, 3, 4, 8, M):
+            if g > M:
+                continue
+            cfg = cfg_for(ids)
+            cfg.wgrad_group = g
+            assert B.jpp_schedule_validate(cfg, M, tasks) == brute(tasks, M, g), (kind, P, r, V, M, g)
+    # the benchmark's schedule: groups of 8 = one run of backwards of a virtual stage
+    cfg = cfg_for([0, 8])
+    cfg.wgrad_group = 8
+    assert B.jpp_schedule_validate(cfg, 32, B.jpp_schedule_make(inp.SCHED_INTERLEAVED, 8, 0, 2, 32)) == 32
+
+
 def test_validator_rejects_rule_violations():
     cfg = cfg_for([0])
     good = B.jpp_schedule_make(inp.SCHED_GPIPE, 1, 0, 1, 2)
