@@ -399,6 +399,9 @@ def main():
     }
     if w.dtype == inp.DT_BF16:
         avg_ms, flops_per_launch = time_dominant_kernel(w, torch, B)
+        shapes = wgrad_shapes(w)
+        # measured for the C4 shapes only, at groups of 8 (25.4 GB) and per task (6.65 GB)
+        traffic = {8: 25.4e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
         ach = flops_per_launch / (avg_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel<..., k-strided A, k-strided B> "
                            "(weight gradient with fused fp32 accumulate)",
@@ -407,8 +410,9 @@ def main():
                            "flops_per_launch": flops_per_launch,
                            # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a 1 GiB copy
                            # (profiles/gemm_wgrad_c4_hbm_traffic.md); measured for the C4 shapes only
-                           "traffic": 6.65e9 if a.config == "C4" else None, "traffic_unit": "bytes/launch",
-                           "algorithmic_bytes_per_launch": 3.83e9 if a.config == "C4" else None}
+                           "traffic": traffic, "traffic_unit": "bytes/launch",
+                           "algorithmic_bytes_per_launch": sum(8.0 * m * n + 2.0 * k * (m + n) for m, n, k in shapes)
+                           / len(shapes)}
     if not a.no_cpu_baseline:
         cb = cpu_baseline()
         per_mb = algorithmic_flops_per_microbatch(w)
