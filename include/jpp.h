@@ -91,6 +91,13 @@ typedef struct {
                        * so the result is still the same for every schedule.  A group occupies g
                        * stash places from its first forward to its last backward
                        * (jpp_schedule_validate counts that).  Not together with remat.         */
+  int32_t embed;      /* 1: the actor's FIRST virtual stage (local index 0) starts with a token
+                       * embedding: its input is int32 token ids [microbatch, seq_len] and
+                       * x = E[ids] with the table "embed.w" [vocab, d_model] (ids outside
+                       * [0, vocab) read as a zero row and get no gradient).  Its backward adds the
+                       * cotangent rows of x to the rows of the table's gradient, in position
+                       * order, and sends nothing.  Needs vocab.  The table's parameter slots
+                       * exist in every virtual stage's buffer and stay unused elsewhere.         */
   int32_t n_virtual;  /* stages owned by this actor                                           */
   int32_t stage_ids[JPP_MAX_VIRTUAL]; /* their global indices (interleaved: v*P + rank)       */
 } jpp_layer_config;
@@ -153,7 +160,9 @@ jpp_status jpp_stage_set_params(jpp_stage* st, int vstage, const void* src, int 
  * [vstage * M + i].  inbox_x[i]: activation received for FWD(i); inbox_cot[i]: cotangent
  * received for BWD(i) and outbox_y[i]: output sent after FWD(i) (entries of the virtual
  * stage that carries the loss head are ignored; the arrays may be NULL when that is the only
- * one); outbox_dx[i]: input cotangent sent after BWD(i).  targets[i] (loss_head only, read
+ * one); outbox_dx[i]: input cotangent sent after BWD(i).  For the virtual stage that carries
+ * the token embedding inbox_x[i] points to int32 token ids [microbatch, seq_len], read in place
+ * by FWD(i) and BWD(i) (they must stay valid for the run), and outbox_dx[i] is ignored.  targets[i] (loss_head only, read
  * for the head's virtual stage): device int32 [microbatch, seq_len] token ids in [0, vocab).
  * The host arrays are copied. */
 jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x,
@@ -273,7 +282,8 @@ jpp_status jpp_pipeline_create(jpp_stage* const* actors, int n_actors, void* are
 void jpp_pipeline_destroy(jpp_pipeline* p);
 
 /* Outer boundary, device pointers, M entries each: x_in[i] input of stage 0, dx_out[i] its
- * cotangent; with a loss head targets[i] (int32 [microbatch, seq_len]); without one cot_in[i]
+ * cotangent (when actor 0 has `embed`: x_in[i] are int32 token ids [microbatch, seq_len] and
+ * dx_out is ignored, may be NULL); with a loss head targets[i] (int32 [microbatch, seq_len]); without one cot_in[i]
  * (cotangent of the last stage's output) and y_out[i] (that output). */
 jpp_status jpp_pipeline_bind(jpp_pipeline* p, const void* const* x_in, void* const* dx_out,
                              const int32_t* const* targets, const void* const* cot_in, void* const* y_out);
@@ -289,6 +299,17 @@ jpp_status jpp_pipeline_bind(jpp_pipeline* p, const void* const* x_in, void* con
  * jpp_stage_zero_grads on every actor's compute stream first). */
 jpp_status jpp_pipeline_run(jpp_pipeline* p, const jpp_task* const* task_lists, const int* n_tasks,
                             void* const* compute_streams, void* const* side_streams);
+
+/* Tied embedding and LM head (Section 3, "Weight Sharing and Gradient Accumulation"): when
+ * actor 0 has `embed` and actor P-1 the loss head, and the caller has set the same values in
+ * "embed.w" of stage 0 and "head.w_head" of the last stage, the two tables are one weight
+ * used twice.  Each run accumulates the partial gradient of each use where it is produced
+ * (the carried states of the commuted loop); this call is the one addition after the loop:
+ * on `stream`, after both actors' runs, both gradient regions become their sum, so that the
+ * same update applied on both actors keeps the two copies bit-identical.  Call it once per
+ * step, before jpp_stage_apply_gradients: the table then crosses between the two actors
+ * once per step, not once per microbatch.  JPP_ESTATE without embed + head. */
+jpp_status jpp_pipeline_sum_tied_gradients(jpp_pipeline* p, void* stream);
 
 /* Waits for everything the last jpp_pipeline_run enqueued. */
 jpp_status jpp_pipeline_sync(jpp_pipeline* p);
@@ -356,6 +377,15 @@ jpp_status jpp_op_act_fwd(int dtype, int act, int rows, int f, const void* h, vo
 /* dh = da * act'(h), shaped like h. */
 jpp_status jpp_op_act_bwd(int dtype, int act, int rows, int f, const void* h, const void* da,
                           void* dh, void* stream);
+
+/* Token embedding.  x[t] = table[ids[t]] for t < rows (table [vocab, d], storage dtype; an id
+ * outside [0, vocab) gives a zero row).  Backward: g_table[v] (fp32 [vocab, d]) += the sum of
+ * dx[t] over the positions with ids[t] == v, in ascending t, one writer per row, no atomics;
+ * rows <= 393216. */
+jpp_status jpp_op_embed_fwd(int dtype, int rows, int d, int vocab, const int32_t* ids, const void* table, void* x,
+                            void* stream);
+jpp_status jpp_op_embed_bwd(int dtype, int rows, int d, int vocab, const int32_t* ids, const void* dx, float* g_table,
+                            void* stream);
 
 #ifdef __cplusplus
 }

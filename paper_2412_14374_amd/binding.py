@@ -31,7 +31,7 @@ class jpp_layer_config(C.Structure):
                 ("d_ffn", C.c_int32), ("seq_len", C.c_int32), ("microbatch", C.c_int32),
                 ("norm", C.c_int32), ("act", C.c_int32), ("use_bias", C.c_int32), ("rope", C.c_int32),
                 ("rope_theta", C.c_float), ("norm_eps", C.c_float), ("loss_head", C.c_int32),
-                ("vocab", C.c_int32), ("remat", C.c_int32), ("wgrad_group", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
+                ("vocab", C.c_int32), ("remat", C.c_int32), ("wgrad_group", C.c_int32), ("embed", C.c_int32), ("n_virtual", C.c_int32), ("stage_ids", C.c_int32 * JPP_MAX_VIRTUAL)]
 
 
 class jpp_optimizer_step(C.Structure):
@@ -71,6 +71,7 @@ _SIGNATURES = {
     "jpp_pipeline_run": (C.c_int, [C.c_void_p, C.POINTER(C.POINTER(jpp_task)), C.POINTER(C.c_int),
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
     "jpp_pipeline_sync": (C.c_int, [C.c_void_p]),
+    "jpp_pipeline_sum_tied_gradients": (C.c_int, [C.c_void_p, C.c_void_p]),
     "jpp_stage_params": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
     "jpp_stage_optimizer_bytes": (C.c_size_t, [C.c_void_p, C.c_int]),
     "jpp_stage_optimizer_bind": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -96,6 +97,8 @@ _SIGNATURES = {
     "jpp_op_colreduce_scratch": (C.c_size_t, [C.c_int, C.c_int]),
     "jpp_op_act_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 3),
     "jpp_op_act_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
+    "jpp_op_embed_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
+    "jpp_op_embed_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
 }
 
 
@@ -132,7 +135,7 @@ def make_config(w):
     for f, _ in jpp_layer_config._fields_:
         if f in ("stage_ids", "n_virtual"):
             continue
-        optional = f in ("remat", "wgrad_group")
+        optional = f in ("remat", "wgrad_group", "embed")
         setattr(c, f, getattr(w, f, 0) if optional else getattr(w, f))
     ids = list(w.stage_ids)
     c.n_virtual = len(ids)
@@ -294,6 +297,10 @@ def jpp_pipeline_sync(h):
     _check(lib().jpp_pipeline_sync(h))
 
 
+def jpp_pipeline_sum_tied_gradients(h, stream):
+    _check(lib().jpp_pipeline_sum_tied_gradients(h, C.c_void_p(stream)))
+
+
 def jpp_stage_params(h, vstage):
     p = C.c_void_p()
     n = C.c_size_t()
@@ -384,3 +391,11 @@ def jpp_op_act_fwd(dtype, act, rows, f, h, a, stream):
 
 def jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream):
     _check(lib().jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream))
+
+
+def jpp_op_embed_fwd(dtype, rows, d, vocab, ids, table, x, stream):
+    _check(lib().jpp_op_embed_fwd(dtype, rows, d, vocab, ids, table, x, stream))
+
+
+def jpp_op_embed_bwd(dtype, rows, d, vocab, ids, dx, g_table, stream):
+    _check(lib().jpp_op_embed_bwd(dtype, rows, d, vocab, ids, dx, g_table, stream))

@@ -80,6 +80,14 @@ hipError_t launch_rope(int dtype, int mb, int seq, int Hq, int Hkv, int hd, void
 // in the storage dtype and *loss = -(1/rows) sum_r log softmax(z_r)[tgt_r] (deterministic).
 hipError_t launch_cross_entropy(int dtype, int rows, int vocab, const float* z, const int32_t* targets,
                                 void* dz, float* row_loss, float* loss, hipStream_t s);
+// Token embedding: x[t] = E[tok[t]] (storage dtype, d a multiple of the 16-byte chunk), and its
+// gradient G[id] += sum_{t: tok[t] == id, ascending} dx[t] in fp32 (deterministic, no atomics).
+hipError_t launch_embed_fwd(int dtype, int rows, int d, int vocab, const int32_t* tok, const void* E, void* x,
+                            hipStream_t s);
+hipError_t launch_embed_bwd(int dtype, int rows, int d, int vocab, const int32_t* tok, const void* dx, float* G,
+                            hipStream_t s);
+// a <- a + b; b <- a + b over n fp32 elements (n a multiple of 4).
+hipError_t launch_tied_sum(float* a, float* b, size_t n, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 // Parameter updates over n elements (n a multiple of 4): w in the storage dtype, g fp32.
 hipError_t launch_sgd(int dtype, void* w, const float* g, size_t n, float lr, float wd, hipStream_t s);

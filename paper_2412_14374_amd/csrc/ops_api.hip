@@ -125,4 +125,23 @@ jpp_status jpp_op_act_bwd(int dtype, int act, int rows, int f, const void* h, co
   return e == hipSuccess ? JPP_OK : fail_hip(e, "activation backward launch");
 }
 
+jpp_status jpp_op_embed_fwd(int dtype, int rows, int d, int vocab, const int32_t* ids, const void* table, void* x,
+                            void* stream) {
+  if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
+  if (rows < 1 || vocab < 1 || d < 1 || d % chunk_of(dtype) != 0)
+    return fail(JPP_EINVAL, "d must be a multiple of the 16-byte chunk");
+  if (!ids || !table || !x) return fail(JPP_EINVAL, "null operand");
+  hipError_t e = launch_embed_fwd(dtype, rows, d, vocab, ids, table, x, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "embedding forward launch");
+}
+
+jpp_status jpp_op_embed_bwd(int dtype, int rows, int d, int vocab, const int32_t* ids, const void* dx, float* g_table,
+                            void* stream) {
+  if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
+  if (rows < 1 || rows > 393216 || vocab < 1 || d < 1) return fail(JPP_EINVAL, "rows must be in [1, 393216]");
+  if (!ids || !dx || !g_table) return fail(JPP_EINVAL, "null operand");
+  hipError_t e = launch_embed_bwd(dtype, rows, d, vocab, ids, dx, g_table, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "embedding backward launch");
+}
+
 }  // extern "C"

@@ -28,7 +28,7 @@ struct jpp_pipeline {
   std::vector<jpp_stage*> actors;
   int P = 0, V = 0, S = 0, M = 0;
   size_t bbytes = 0;
-  bool head = false;
+  bool head = false, embed = false;
   // boundary s (between stage s and s + 1), microbatch i -> index s * M + i
   std::vector<char*> act, cot;
   std::vector<hipEvent_t> act_ready, cot_ready;
@@ -159,6 +159,7 @@ jpp_status jpp_pipeline_create(jpp_stage* const* actors, int n_actors, void* are
       if (c.stage_ids[v] != v * n_actors + r)
         return fail(JPP_EINVAL, "actor r must own the stages r, P + r, 2P + r, ... in that order");
     if (c.loss_head && r != n_actors - 1) return fail(JPP_EINVAL, "only the last actor can carry the loss head");
+    if (c.embed && r != 0) return fail(JPP_EINVAL, "only the first actor can carry the token embedding");
     if (a.running) return fail(JPP_ESTATE, "actor is in the middle of a run");
   }
   const size_t need = jpp_pipeline_arena_bytes(&c0, n_actors, M);
@@ -170,6 +171,7 @@ jpp_status jpp_pipeline_create(jpp_stage* const* actors, int n_actors, void* are
   p->P = n_actors; p->V = V; p->S = V * n_actors; p->M = M;
   p->bbytes = boundary_bytes(c0);
   p->head = actors[n_actors - 1]->cfg.loss_head != 0;
+  p->embed = actors[0]->cfg.embed != 0;
   const size_t nb = (size_t)(p->S - 1) * M;
   p->act.resize(nb); p->cot.resize(nb);
   p->act_ready.assign(nb, nullptr); p->cot_ready.assign(nb, nullptr);
@@ -204,12 +206,12 @@ void jpp_pipeline_destroy(jpp_pipeline* p) {
 
 jpp_status jpp_pipeline_bind(jpp_pipeline* p, const void* const* x_in, void* const* dx_out,
                              const int32_t* const* targets, const void* const* cot_in, void* const* y_out) {
-  if (!p || !x_in || !dx_out) return fail(JPP_EINVAL, "x_in and dx_out are required");
+  if (!p || !x_in || (!dx_out && !p->embed)) return fail(JPP_EINVAL, "x_in and dx_out are required");
   if (p->head && !targets) return fail(JPP_EINVAL, "targets are required: the last stage has a loss head");
   if (!p->head && (!cot_in || !y_out)) return fail(JPP_EINVAL, "cot_in and y_out are required without a loss head");
   const int P = p->P, V = p->V, M = p->M, S = p->S;
   for (int i = 0; i < M; ++i) {
-    if (!x_in[i] || !dx_out[i]) return fail(JPP_EINVAL, "null boundary buffer");
+    if (!x_in[i] || (!p->embed && !dx_out[i])) return fail(JPP_EINVAL, "null boundary buffer");
     if (p->head ? !targets[i] : (!cot_in[i] || !y_out[i])) return fail(JPP_EINVAL, "null boundary buffer");
   }
   for (int r = 0; r < P; ++r) {
@@ -226,7 +228,7 @@ jpp_status jpp_pipeline_bind(jpp_pipeline* p, const void* const* x_in, void* con
         const size_t k = (size_t)v * M + i;
         const size_t below = s > 0 ? (size_t)(s - 1) * M + i : 0, above = (size_t)s * M + i;
         in_x[k] = s == 0 ? x_in[i] : p->act[below];
-        out_dx[k] = s == 0 ? dx_out[i] : (void*)p->cot[below];
+        out_dx[k] = s == 0 ? (p->embed ? nullptr : dx_out[i]) : (void*)p->cot[below];
         if (s > 0) { a->wait_x[k] = p->act_ready[below]; a->signal_dx[k] = p->cot_ready[below]; }
         if (s == S - 1) {
           if (p->head) tg[k] = targets[i];
@@ -331,6 +333,24 @@ jpp_status jpp_pipeline_run(jpp_pipeline* p, const jpp_task* const* task_lists, 
     if (rc != JPP_OK) return abort_run(rc);
   }
   p->ran = true;
+  return JPP_OK;
+}
+
+jpp_status jpp_pipeline_sum_tied_gradients(jpp_pipeline* p, void* stream) {
+  if (!p) return fail(JPP_EINVAL, "null pipeline");
+  jpp_stage* first = p->actors.front();
+  jpp_stage* last = p->actors.back();
+  if (!p->embed || !p->head) return fail(JPP_ESTATE, "tied weights need an embedding on the first stage and a loss head on the last");
+  if (first->cfg.vocab != last->cfg.vocab) return fail(JPP_EINVAL, "embedding and head disagree on vocab");
+  for (jpp_stage* a : p->actors)
+    if (a->running) return fail(JPP_ESTATE, "an actor is in the middle of a run");
+  hipStream_t s = (hipStream_t)stream;
+  // after both actors' last runs (device-side waits)
+  if (first->end_compute.recorded) HIP_TRY(hipStreamWaitEvent(s, first->end_compute.ev, 0));
+  if (last->end_compute.recorded) HIP_TRY(hipStreamWaitEvent(s, last->end_compute.ev, 0));
+  float* g1 = first->grads[0] + first->w_embed;
+  float* g2 = last->grads[p->V - 1] + last->w_head;
+  HIP_TRY(launch_tied_sum(g1, g2, (size_t)first->cfg.vocab * first->cfg.d_model, s));
   return JPP_OK;
 }
 

@@ -469,6 +469,77 @@ __global__ __launch_bounds__(kThreads) void widen_kernel(const T* __restrict__ w
   }
 }
 
+// Token embedding, forward: row t of x is row tok[t] of the table E [vocab, d] (an id outside
+// [0, vocab) gives a zero row).  One workgroup per token, 16-byte chunks.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void embed_fwd_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E,
+                                                             T* __restrict__ x, int d, int vocab) {
+  const int t = blockIdx.x;
+  const int id = tok[t];
+  const int n16 = d * (int)sizeof(T) / 16;
+  const u32x4* src = reinterpret_cast<const u32x4*>(E + (size_t)id * d);
+  u32x4* dst = reinterpret_cast<u32x4*>(x + (size_t)t * d);
+  const bool ok = id >= 0 && id < vocab;
+  for (int c = threadIdx.x; c < n16; c += kThreads) dst[c] = ok ? src[c] : u32x4{0u, 0u, 0u, 0u};
+}
+
+// Token embedding, backward: G[id] += sum over the positions t with tok[t] == id, in
+// ascending t, of dx[t].  One workgroup per position; the workgroup of an id's first
+// occurrence does all the work for that id, every other one leaves at once, so each row of G
+// has a single writer and a fixed order of additions (no float atomics).  The positions of
+// the id are first marked in a bitmap in LDS (rows bits, dynamic), then walked in order.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void embed_bwd_kernel(const int32_t* __restrict__ tok, const T* __restrict__ dx,
+                                                             float* __restrict__ G, int rows, int d, int vocab) {
+  constexpr int kCols = 8;   // columns per thread and pass
+  extern __shared__ uint32_t marks[];
+  __shared__ int seen_before;
+  const int t = blockIdx.x;
+  const int id = tok[t];
+  if (id < 0 || id >= vocab) return;
+  const int nwords = (rows + 31) / 32;
+  for (int w = threadIdx.x; w < nwords; w += kThreads) marks[w] = 0u;
+  if (threadIdx.x == 0) seen_before = 0;
+  __syncthreads();
+  for (int u = threadIdx.x; u < rows; u += kThreads) {
+    if (tok[u] != id) continue;
+    if (u < t) seen_before = 1;   // every writer writes the same value
+    else atomicOr(&marks[u >> 5], 1u << (u & 31));
+  }
+  __syncthreads();
+  if (seen_before) return;
+  for (int c0 = threadIdx.x * kCols; c0 < d; c0 += kThreads * kCols) {
+    float acc[kCols];
+#pragma unroll
+    for (int e = 0; e < kCols; ++e) acc[e] = 0.f;
+    for (int w = t >> 5; w < nwords; ++w) {
+      uint32_t m = marks[w];
+      while (m) {
+        const int u = w * 32 + __builtin_ctz(m);
+        m &= m - 1;
+        const T* r = dx + (size_t)u * d + c0;
+#pragma unroll
+        for (int e = 0; e < kCols; ++e)
+          if (c0 + e < d) acc[e] += to_f32(r[e]);
+      }
+    }
+    float* g = G + (size_t)id * d + c0;
+#pragma unroll
+    for (int e = 0; e < kCols; ++e)
+      if (c0 + e < d) g[e] += acc[e];
+  }
+}
+
+// The final addition of Section 3's loop-commuting rewrite for a weight used by two stages:
+// both partial gradients become their sum.
+__global__ __launch_bounds__(kThreads) void tied_sum_kernel(float* __restrict__ a, float* __restrict__ b, size_t n4) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    const f32x4 s = reinterpret_cast<f32x4*>(a)[i] + reinterpret_cast<f32x4*>(b)[i];
+    reinterpret_cast<f32x4*>(a)[i] = s;
+    reinterpret_cast<f32x4*>(b)[i] = s;
+  }
+}
+
 inline int grid_for(size_t items) {
   size_t g = (items + kThreads - 1) / kThreads;
   const size_t cap = 256 * 16;  // 16 workgroups per CU
@@ -635,6 +706,28 @@ hipError_t launch_widen(int dtype, const void* w, float* master, size_t n, hipSt
   const size_t n4 = n / 4;
   if (dtype == JPP_BF16) widen_kernel<bf16><<<grid_for(n4), kThreads, 0, s>>>((const bf16*)w, master, n4);
   else widen_kernel<float><<<grid_for(n4), kThreads, 0, s>>>((const float*)w, master, n4);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_fwd(int dtype, int rows, int d, int vocab, const int32_t* tok, const void* E, void* x,
+                            hipStream_t s) {
+  if (dtype == JPP_BF16) embed_fwd_kernel<bf16><<<rows, kThreads, 0, s>>>(tok, (const bf16*)E, (bf16*)x, d, vocab);
+  else embed_fwd_kernel<float><<<rows, kThreads, 0, s>>>(tok, (const float*)E, (float*)x, d, vocab);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_bwd(int dtype, int rows, int d, int vocab, const int32_t* tok, const void* dx, float* G,
+                            hipStream_t s) {
+  const size_t lds = (size_t)((rows + 31) / 32) * sizeof(uint32_t);
+  if (lds > 48 * 1024) return hipErrorInvalidValue;   // 393216 tokens per microbatch
+  if (dtype == JPP_BF16) embed_bwd_kernel<bf16><<<rows, kThreads, lds, s>>>(tok, (const bf16*)dx, G, rows, d, vocab);
+  else embed_bwd_kernel<float><<<rows, kThreads, lds, s>>>(tok, (const float*)dx, G, rows, d, vocab);
+  return hipGetLastError();
+}
+
+hipError_t launch_tied_sum(float* a, float* b, size_t n, hipStream_t s) {
+  const size_t n4 = n / 4;
+  tied_sum_kernel<<<grid_for(n4), kThreads, 0, s>>>(a, b, n4);
   return hipGetLastError();
 }
 

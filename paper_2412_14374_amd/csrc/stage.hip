@@ -64,6 +64,8 @@ bool config_ok(const jpp_layer_config* c, int M, int max_in_flight, std::string&
       if (c->stage_ids[a] == c->stage_ids[b]) { why = "duplicate stage id"; return false; }
   if (M < 1 || max_in_flight < 1) { why = "n_microbatches and max_in_flight must be positive"; return false; }
   if (c->loss_head && c->vocab < 1) { why = "loss_head needs vocab"; return false; }
+  if (c->embed != 0 && c->embed != 1) { why = "embed must be 0 or 1"; return false; }
+  if (c->embed && c->vocab < 1) { why = "embed needs vocab"; return false; }
   if (c->remat != 0 && c->remat != 1) { why = "remat must be 0 or 1"; return false; }
   if (c->wgrad_group < 0 || c->wgrad_group > M) { why = "wgrad_group must be in [0, n_microbatches]"; return false; }
   if (c->wgrad_group > 1) {
@@ -78,7 +80,7 @@ bool config_ok(const jpp_layer_config* c, int M, int max_in_flight, std::string&
   if (c->d_ffn % chunk != 0) { why = "d_ffn must be a multiple of the 16-byte chunk"; return false; }
   if (c->dtype == JPP_BF16) {
     const long T = (long)c->seq_len * c->microbatch;
-    if (T % 8 != 0 || c->d_model % 8 != 0 || (c->loss_head && c->vocab % 8 != 0)) {
+    if (T % 8 != 0 || c->d_model % 8 != 0 || ((c->loss_head || c->embed) && c->vocab % 8 != 0)) {
       why = "bf16 mode needs tokens, d_model and vocab to be multiples of 8";
       return false;
     }
@@ -134,6 +136,7 @@ void build_param_table(jpp_stage& st) {
     st.lnf_b = ln ? add("head.lnf_b", m.d, 0) : -1;
     st.w_head = add("head.w_head", m.vocab, m.d);
   }
+  if (c.embed) st.w_embed = add("embed.w", m.vocab, m.d);
   st.pcount = (off + 7) / 8 * 8;
 }
 
@@ -202,6 +205,7 @@ size_t carve(jpp_stage& st, char* base) {
   st.delta = (float*)take((size_t)m.mb * m.Hq * m.seq * 4);
   const size_t widest = std::max<size_t>({(size_t)m.d, (size_t)m.f1, (size_t)m.nqkv});
   st.partial = (float*)take(2 * (size_t)colreduce_blocks(m.T) * widest * 4);
+  st.dx_embed = c.embed ? take(T * m.d * e) : nullptr;
   if (c.loss_head) {
     st.z = (float*)take(T * m.vocab * 4);
     st.row_loss = (float*)take(T * 4);
@@ -298,6 +302,9 @@ hipError_t enqueue_forward(jpp_stage& st, int v, int i, Slot& slot, char* y_out)
   hipStream_t s = st.cs;
   const int dt = c.dtype;
   const HeadView hv = st.head_view(slot, slot.j);
+  if (st.is_embed(v))
+    K_TRY(launch_embed_fwd(dt, m.T, m.d, m.vocab, (const int32_t*)st.inbox_x[(size_t)v * st.M + i],
+                           pptr(st, v, st.w_embed), st.layer_view(slot, 0, false).x, s));
   for (int l = 0; l < m.L; ++l) {
     char* y = (l + 1 < m.L) ? st.layer_view(slot, l + 1, false).x : (st.is_head(v) ? hv.yL : y_out);
     K_TRY(layer_forward(st, s, v, l, st.layer_view(slot, l, false), y));
@@ -328,7 +335,8 @@ hipError_t wgrad(jpp_stage& st, int M, int N, int K, const void* dy, int ldy, co
 // weight-gradient GEMMs on the wgrad stream.  `wg_members`: how many members' worth of rows
 // the weight-gradient GEMMs contract over, starting at the group's first member; 0 = none
 // now (a later member of the group runs them).  Without grouping it is always 1.
-hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in, char* dx_out, int wg_members) {
+hipError_t enqueue_backward(jpp_stage& st, int v, int i, Slot& slot, const char* dy_in, char* dx_out,
+                            int wg_members) {
   const Dims& m = st.dm;
   const jpp_layer_config& c = st.cfg;
   hipStream_t s = st.bs;
@@ -404,6 +412,10 @@ hipError_t enqueue_backward(jpp_stage& st, int v, Slot& slot, const char* dy_in,
     dy = dx;
     cur ^= 1;
   }
+  // an embedding stage: the cotangent of x goes into the rows of the table's gradient
+  if (st.is_embed(v))
+    K_TRY(launch_embed_bwd(dt, m.T, m.d, m.vocab, (const int32_t*)st.inbox_x[(size_t)v * st.M + i], dx_out,
+                           gptr(st, v, st.w_embed), s));
   // The wgrad stream now also follows the whole backward chain: an event recorded on it marks
   // "nothing of this task reads the stash, the cotangent or the workspace any more".
   K_TRY(hipEventRecord(st.b2w.ev, st.bs));
@@ -468,7 +480,9 @@ hipError_t send_and_delete(jpp_stage& st, hipStream_t producer, int b, void* out
 hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes, hipEvent_t produced) {
   if (produced) K_TRY(hipStreamWaitEvent(st.ss, produced, 0));  // the sending actor's copy
   if (slot.freed.recorded) K_TRY(hipStreamWaitEvent(st.ss, slot.freed.ev, 0));
-  K_TRY(hipMemcpyAsync(st.layer_view(slot, 0, false).x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
+  // src == nullptr: an embedding stage, whose forward reads the token ids where they are;
+  // the event still orders the forward after the slot's release
+  if (src) K_TRY(hipMemcpyAsync(st.layer_view(slot, 0, false).x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(slot.rx.ev, st.ss));
   slot.rx_issued = true;
   return hipSuccess;
@@ -589,7 +603,8 @@ jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x, co
   const size_t n = (size_t)V * st->M;
   for (size_t k = 0; k < n; ++k) {
     const bool head = st->is_head((int)(k / st->M));
-    if (!inbox_x[k] || !outbox_dx[k]) return fail(JPP_EINVAL, "null boundary buffer");
+    const bool embed = st->is_embed((int)(k / st->M));
+    if (!inbox_x[k] || (!embed && !outbox_dx[k])) return fail(JPP_EINVAL, "null boundary buffer");
     if (!head && (!inbox_cot[k] || !outbox_y[k])) return fail(JPP_EINVAL, "null boundary buffer");
     if (head && !targets[k]) return fail(JPP_EINVAL, "null targets buffer");
   }
@@ -716,7 +731,7 @@ hipError_t issue_recv(jpp_stage* st, int k, bool ahead) {
     const int sl = gs * st->G + t.i % st->G;
     st->slot_of[key] = sl;
     if (ahead) ++st->prefetched;
-    return issue_recv_x(*st, st->slots[sl], st->inbox_x[key], bbytes,
+    return issue_recv_x(*st, st->slots[sl], st->is_embed(v) ? nullptr : st->inbox_x[key], bbytes,
                         st->wait_x.empty() ? nullptr : st->wait_x[key]);
   }
   if (st->is_head(v)) return hipSuccess;  // a loss-head backward receives nothing
@@ -791,9 +806,12 @@ jpp_status run_step(jpp_stage* st) {
     const int grp = t.i / st->G;
     const size_t gkey = (size_t)v * st->n_groups() + grp;
     const bool completes = ++st->grp_bwd[gkey] == st->group_size(grp);
+    // an embedding stage sends no input cotangent: it stays in a buffer of the backward stream
+    const bool embed = st->is_embed(v);
     int txb = -1;
-    HIP_TRY(acquire_tx(*st, st->bs, txb));
-    e = enqueue_backward(*st, v, slot, dy, st->tx[txb].p, completes ? st->group_size(grp) : 0);
+    if (!embed) HIP_TRY(acquire_tx(*st, st->bs, txb));
+    e = enqueue_backward(*st, v, t.i, slot, dy, embed ? st->dx_embed : st->tx[txb].p,
+                         completes ? st->group_size(grp) : 0);
     if (e != hipSuccess) return fail_hip(e, "backward kernels");
     // enqueue_backward left the wgrad stream behind both the input-gradient chain and the
     // weight gradients of this task: events recorded there cover every reader
@@ -802,8 +820,9 @@ jpp_status run_step(jpp_stage* st) {
       HIP_TRY(hipEventRecord(cb.freed.ev, st->ws));
       cb.freed.recorded = true;
     }
-    HIP_TRY(send_and_delete(*st, st->bs, txb, st->outbox_dx[key], bbytes,
-                            st->signal_dx.empty() ? nullptr : st->signal_dx[key]));
+    if (!embed)
+      HIP_TRY(send_and_delete(*st, st->bs, txb, st->outbox_dx[key], bbytes,
+                              st->signal_dx.empty() ? nullptr : st->signal_dx[key]));
     st->slot_of[key] = -1;
     if (completes) {
       // the group's stash is dead: release its slot; the events protect every member against

@@ -81,7 +81,7 @@ struct jpp_stage {
   // per-layer parameter offsets (elements) by role; -1 if absent
   struct LayerOff { long ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, w1, b1, w2, b2; };
   std::vector<LayerOff> loff;
-  long lnf_g = -1, lnf_b = -1, w_head = -1;
+  long lnf_g = -1, lnf_b = -1, w_head = -1, w_embed = -1;
 
   char* arena = nullptr;
   size_t arena_bytes = 0;
@@ -123,6 +123,7 @@ struct jpp_stage {
   char *dbuf[2] = {nullptr, nullptr}, *da = nullptr, *dh = nullptr, *dn = nullptr, *dx1 = nullptr, *dO = nullptr,
        *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr, *z = nullptr, *row_loss = nullptr;
+  char* dx_embed = nullptr;   // cotangent of the embedded input (embed stage), consumed by the table's gradient
   // GEMM split scratch, one per stream that launches store-mode GEMMs (forward, backward chain)
   char *split_f = nullptr, *split_b = nullptr;
   size_t split_bytes = 0;
@@ -165,6 +166,8 @@ struct jpp_stage {
 
   // The loss head, if configured, belongs to the actor's last virtual stage.
   bool is_head(int v) const { return cfg.loss_head != 0 && v == cfg.n_virtual - 1; }
+  // The token embedding, if configured, belongs to the actor's first virtual stage.
+  bool is_embed(int v) const { return cfg.embed != 0 && v == 0; }
 };
 
 namespace jpp {

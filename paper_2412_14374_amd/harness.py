@@ -75,9 +75,9 @@ class Stage:
         flat = np.zeros(self.pcount, dtype=np.float32)
         for name, shp, off in self.info:
             grp, key = name.split(".", 1)
-            if grp == "head" and "head" not in p:
-                continue            # a virtual stage without the head: its slots stay zero
-            a = p["head"][key] if grp == "head" else p["layers"][int(grp[5:])][key]
+            if grp in ("head", "embed") and grp not in p:
+                continue            # a virtual stage without the head / the embedding: its slots stay zero
+            a = p[grp][key] if grp in ("head", "embed") else p["layers"][int(grp[5:])][key]
             assert tuple(a.shape) == tuple(shp), (name, a.shape, shp)
             flat[off:off + a.size] = a.reshape(-1)
         return flat
@@ -86,11 +86,13 @@ class Stage:
         out = {"layers": [dict() for _ in range(self.w.n_layers)]}
         if self.w.loss_head:
             out["head"] = {}
+        if getattr(self.w, "embed", 0):
+            out["embed"] = {}
         for name, shp, off in self.info:
             grp, key = name.split(".", 1)
             a = flat[off:off + int(np.prod(shp))].reshape(shp)
-            if grp == "head":
-                out["head"][key] = a
+            if grp in ("head", "embed"):
+                out[grp][key] = a
             else:
                 out["layers"][int(grp[5:])][key] = a
         return out
@@ -126,9 +128,16 @@ class Stage:
         g = torch.Generator(device=self.dev)
         g.manual_seed(seed)
         self.in_x, self.in_c, self.out_y, self.out_dx, self.tg = [], [], [], [], []
-        for s in w.stage_ids:
+        for v, s in enumerate(w.stage_ids):
             for i in range(M):
-                if x is not None:
+                if getattr(w, "embed", 0) and v == 0:
+                    # the embedding stage reads int32 token ids
+                    if x is not None:
+                        self.in_x.append(torch.from_numpy(np.ascontiguousarray(x[s][i], dtype=np.int32)).to(self.dev))
+                    else:
+                        self.in_x.append(torch.randint(0, w.vocab, (w.microbatch, w.seq_len), generator=g,
+                                                       device=self.dev, dtype=torch.int32))
+                elif x is not None:
                     self.in_x.append(to_device(x[s][i], w, self.dev))
                 else:
                     self.in_x.append(torch.randn(shp, generator=g, device=self.dev).to(dt))
@@ -223,7 +232,8 @@ class Pipeline:
         self.P, self.V, self.M = w.P, w.V, w.n_microbatches
         self.S = self.P * self.V
         self.task_lists = [list(t) for t in task_lists]
-        self.actors = [Stage(replace(w, rank=r, loss_head=(w.loss_head if r == self.P - 1 else 0)),
+        self.actors = [Stage(replace(w, rank=r, loss_head=(w.loss_head if r == self.P - 1 else 0),
+                                     embed=(w.embed if r == 0 else 0)),
                              tasks=self.task_lists[r], dev=dev) for r in range(self.P)]
         nbytes = B.jpp_pipeline_arena_bytes(self.actors[0].cfg, self.P, self.M)
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
@@ -251,7 +261,11 @@ class Pipeline:
         shp = (w.microbatch, w.seq_len, w.d_model)
         g = torch.Generator(device=self.dev)
         g.manual_seed(seed)
-        self.x_in = [torch.randn(shp, generator=g, device=self.dev).to(dt) for _ in range(self.M)]
+        if w.embed:
+            self.x_in = [torch.randint(0, w.vocab, (w.microbatch, w.seq_len), generator=g, device=self.dev,
+                                       dtype=torch.int32) for _ in range(self.M)]
+        else:
+            self.x_in = [torch.randn(shp, generator=g, device=self.dev).to(dt) for _ in range(self.M)]
         self.dx_out = [torch.zeros(shp, dtype=dt, device=self.dev) for _ in range(self.M)]
         self.tg = self.cot_in = self.y_out = None
         if w.loss_head:
@@ -268,7 +282,10 @@ class Pipeline:
     def bind(self, x0, cot_last=None, targets=None):
         w, dt = self.w, torch_dtype(self.w)
         shp = (w.microbatch, w.seq_len, w.d_model)
-        self.x_in = [to_device(x, w, self.dev) for x in x0]
+        if w.embed:      # x0: int32 token ids
+            self.x_in = [torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(self.dev) for x in x0]
+        else:
+            self.x_in = [to_device(x, w, self.dev) for x in x0]
         self.dx_out = [torch.zeros(shp, dtype=dt, device=self.dev) for _ in range(self.M)]
         self.tg = self.cot_in = self.y_out = None
         if w.loss_head:
@@ -292,6 +309,10 @@ class Pipeline:
     def sync(self):
         B.jpp_pipeline_sync(self.h)
 
+    def sum_tied_gradients(self):
+        """The one addition after the loop for a tied embedding / LM head (on actor 0's compute stream)."""
+        B.jpp_pipeline_sum_tied_gradients(self.h, self.actors[0].compute.cuda_stream)
+
     def results(self):
         """Host float64 results keyed like oracle.pipeline_oracle.run_pipeline's output."""
         self.sync()
@@ -302,6 +323,8 @@ class Pipeline:
                 g = a.unpack_grads(a.grads_tensor(v).cpu().numpy().astype(np.float64))
                 if "head" in g and not (r == self.P - 1 and v == self.V - 1):
                     del g["head"]
+                if "embed" in g and not (r == 0 and v == 0):
+                    del g["embed"]
                 out["grads"][v * self.P + r] = g
         if self.w.loss_head:
             l = self.actors[-1].losses()

@@ -45,6 +45,7 @@ class Workload:
     vocab: int = 0
     remat: int = 0                   # 1: keep only each layer's input, recompute in the backward
     wgrad_group: int = 0             # g > 1: one weight-gradient GEMM per group of g microbatches
+    embed: int = 0                   # 1: the first stage starts with a token embedding [vocab, d_model]
     # schedule: kind, pipeline depth P, this actor's rank, virtual stages V
     sched: int = SCHED_GPIPE
     P: int = 1
@@ -172,3 +173,24 @@ def draw_pipeline_inputs(w, n_stages, layer_shapes, head_shapes=None, seed=SEED,
     else:
         cot_last = [round_to_dtype(rng.standard_normal(shp) * w.cot_std, w.dtype) for _ in range(M)]
     return params, x0, cot_last, targets
+
+
+def draw_tied_inputs(w, n_stages, layer_shapes, head_shapes, seed=SEED, perturb=False, distinct_ids=None):
+    """Draw what a pipeline with a tied embedding / LM head needs, in a fixed order: per stage
+    the layer parameters, the head's norm parameters (head_shapes without w_head), the shared
+    table E [vocab, d_model], then token ids and targets per microbatch.  `distinct_ids`
+    limits the ids to that many values, so that positions collide in the table's gradient
+    (natural text repeats tokens; a uniform draw over a large vocabulary would not).
+    Returns (params_by_stage, E, tokens, targets), floats already on the storage grid."""
+    rng = np.random.default_rng(seed)
+    M = w.n_microbatches
+    params = {}
+    for s in range(n_stages):
+        params[s] = {"layers": [draw_params(layer_shapes, rng, w, perturb) for _ in range(w.n_layers)]}
+    params[n_stages - 1]["head"] = draw_params([(k, shp) for k, shp in head_shapes if k != "w_head"], rng, w, perturb)
+    E = round_to_dtype(rng.standard_normal((w.vocab, w.d_model)) * w.w_std, w.dtype)
+    hi = w.vocab if distinct_ids is None else min(w.vocab, distinct_ids)
+    ids = rng.permutation(w.vocab)[:hi]
+    tokens = [ids[rng.integers(0, hi, size=(w.microbatch, w.seq_len))].astype(np.int32) for _ in range(M)]
+    targets = [rng.integers(0, w.vocab, size=(w.microbatch, w.seq_len)).astype(np.int32) for _ in range(M)]
+    return params, E, tokens, targets
