@@ -294,7 +294,8 @@ def main():
             None: w.sched}[a.schedule]
     # weight-gradient groups: by default 8 microbatches (for C4: P, one run of backwards of a
     # virtual stage in the interleaved schedule); rematerialisation drops what a group keeps
-    group = a.wgrad_group if a.wgrad_group is not None else (1 if a.remat else min(8, w.n_microbatches))
+    # (the whole-pipeline variant holds P actors' stashes in one HBM: per-task weight gradients there)
+    group = a.wgrad_group if a.wgrad_group is not None else (1 if a.remat or a.pipeline else min(8, w.n_microbatches))
     w = replace(w, remat=1 if a.remat else 0, sched=kind, wgrad_group=group)
     if a.kernel_only:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
