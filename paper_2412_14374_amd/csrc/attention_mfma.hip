@@ -152,8 +152,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* 
   __shared__ __attribute__((aligned(1024))) char lds[2 * kTileBytes];
   char* k_tile = lds;
   char* vt_tile = lds + kTileBytes;
-  const int qb = gridDim.x - 1 - blockIdx.x;  // heavy (late) query blocks first
-  const int h = blockIdx.y, b = blockIdx.z;
+  // Heaviest blocks first over the whole launch (a late query block visits the most key
+  // tiles): the block index is the slow grid dimension, (head, batch) the fast one, so the
+  // launch ends with its shortest workgroups instead of a few long ones.
+  const int qb = gridDim.y - 1 - blockIdx.y;
+  const int h = blockIdx.x % Hq, b = blockIdx.x / Hq;
   const int g = h / (Hq / Hkv);
   const int ld = (Hq + 2 * Hkv) * HD;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, l32 = lane & 31, half = lane >> 5;
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
   char* do_tile = lds + kTileBytes;
   char* qt_tile = lds + 2 * kTileBytes;
   char* dot_tile = lds + 3 * kTileBytes;
-  const int kb = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int kb = blockIdx.y, g = blockIdx.x % Hkv, b = blockIdx.x / Hkv;   // early key blocks (most query tiles) first
   const int group = Hq / Hkv;
   const int ld = (Hq + 2 * Hkv) * HD, ldo = Hq * HD;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, l32 = lane & 31, half = lane >> 5;
@@ -431,8 +434,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
   char* k_tile = lds;
   char* v_tile = lds + kTileBytes;
   char* kt_tile = lds + 2 * kTileBytes;
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int qb = gridDim.y - 1 - blockIdx.y;   // heaviest first, as in the forward kernel
+  const int h = blockIdx.x % Hq, b = blockIdx.x / Hq;
   const int g = h / (Hq / Hkv);
   const int ld = (Hq + 2 * Hkv) * HD, ldo = Hq * HD;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, l32 = lane & 31, half = lane >> 5;
@@ -531,7 +534,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
 bool attention_mfma_supported(const AttnDesc& a) { return a.hd == HD; }
 
 hipError_t launch_attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
-  dim3 grid((a.seq + 127) / 128, a.Hq, a.mb);
+  dim3 grid(a.Hq * a.mb, (a.seq + 127) / 128);
   const long long bytes = (long long)a.mb * a.seq * (a.Hq + 2 * a.Hkv) * HD * 2;
   attn_fwd_mfma_kernel<<<grid, kThreads, 0, s>>>((const bf16*)a.qkv, (bf16*)a.out, a.lse, a.seq, a.Hq, a.Hkv, bytes);
   return hipGetLastError();
@@ -545,12 +548,12 @@ hipError_t launch_attention_bwd_mfma(const AttnDesc& a, hipStream_t s) {
                                                                       a.delta, a.mb, a.seq, a.Hq);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  dim3 gk((a.seq + 127) / 128, a.Hkv, a.mb);
+  dim3 gk(a.Hkv * a.mb, (a.seq + 127) / 128);
   attn_bwd_dkv_mfma_kernel<<<gk, kThreads, 0, s>>>((const bf16*)a.qkv, (const bf16*)a.dout, a.lse, a.delta,
                                                    (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes, do_bytes);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  dim3 gq((a.seq + 127) / 128, a.Hq, a.mb);
+  dim3 gq(a.Hq * a.mb, (a.seq + 127) / 128);
   attn_bwd_dq_mfma_kernel<<<gq, kThreads, 0, s>>>((const bf16*)a.qkv, (const bf16*)a.dout, a.lse, a.delta,
                                                   (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes);
   return hipGetLastError();
