@@ -127,21 +127,43 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
 #pragma unroll
     for (int e = 0; e < N; ++e) { pg[j][e] = 0.f; pb[j][e] = 0.f; }
   }
-  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+  // One row's operands in registers.  The next row of this workgroup is fetched while the
+  // current one is reduced and written, so a row costs one memory latency, not three.
+  struct Row { Chunk<T> xs[MAXC], ds[MAXC]; float mean, rstd; };
+  auto fetch = [&](int r, Row& w) {
     const size_t base = (size_t)r * d;
-    const float mean = stats[2 * (size_t)r], rstd = stats[2 * (size_t)r + 1];
-    Chunk<T> xs[MAXC], ds[MAXC];
+    w.mean = stats[2 * (size_t)r];
+    w.rstd = stats[2 * (size_t)r + 1];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+      const int c = threadIdx.x + j * kThreads;
+      if (c < nchunks) {
+        w.xs[j] = load_chunk(x + base + (size_t)c * N);
+        w.ds[j] = load_chunk(dy + base + (size_t)c * N);
+      }
+    }
+  };
+  auto process = [&](int r, const Row& w) {
+    const size_t base = (size_t)r * d;
+    const float mean = w.mean, rstd = w.rstd;
+    // the tensor added to the result is only needed after the reduction: its latency hides there
+    Chunk<T> as[MAXC];
+    if (dx_add != nullptr) {
+#pragma unroll
+      for (int j = 0; j < MAXC; ++j) {
+        const int c = threadIdx.x + j * kThreads;
+        if (c < nchunks) as[j] = load_chunk(dx_add + base + (size_t)c * N);
+      }
+    }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
       const int c = threadIdx.x + j * kThreads;
       if (c < nchunks) {
-        xs[j] = load_chunk(x + base + (size_t)c * N);
-        ds[j] = load_chunk(dy + base + (size_t)c * N);
 #pragma unroll
         for (int e = 0; e < N; ++e) {
-          const float xh = (xs[j].get(e) - mean) * rstd;
-          const float dv = ds[j].get(e);
+          const float xh = (w.xs[j].get(e) - mean) * rstd;
+          const float dv = w.ds[j].get(e);
           const float dxh = dv * gs[j].get(e);
           s1 += dxh;
           s2 += dxh * xh;
@@ -158,18 +180,39 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
       const int c = threadIdx.x + j * kThreads;
       if (c < nchunks) {
         Chunk<T> o;
-        Chunk<T> add = xs[j];
-        if (dx_add != nullptr) add = load_chunk(dx_add + base + (size_t)c * N);
 #pragma unroll
         for (int e = 0; e < N; ++e) {
-          const float xh = (xs[j].get(e) - mean) * rstd;
-          const float dxh = ds[j].get(e) * gs[j].get(e);
+          const float xh = (w.xs[j].get(e) - mean) * rstd;
+          const float dxh = w.ds[j].get(e) * gs[j].get(e);
           float v = rstd * (dxh - m1 - xh * m2);
-          if (dx_add != nullptr) v += add.get(e);
+          if (dx_add != nullptr) v += as[j].get(e);
           o.set(e, v);
         }
         store_chunk(dx + base + (size_t)c * N, o);
       }
+    }
+  };
+  if constexpr (MAXC > 6) {
+    // two rows of this width do not fit the register file: one at a time
+    Row a;
+    for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+      fetch(r, a);
+      process(r, a);
+    }
+  } else {
+    Row a, b;
+    int r = blockIdx.x;
+    if (r < rows) fetch(r, a);
+    while (r < rows) {
+      int nxt = r + gridDim.x;
+      if (nxt < rows) fetch(nxt, b);
+      process(r, a);
+      r = nxt;
+      if (r >= rows) break;
+      nxt = r + gridDim.x;
+      if (nxt < rows) fetch(nxt, a);
+      process(r, b);
+      r = nxt;
     }
   }
 #pragma unroll
@@ -550,7 +593,7 @@ template <typename T>
 int pick_maxc(int d) {
   const int nchunks = d / Chunk<T>::N;
   const int per = (nchunks + kThreads - 1) / kThreads;
-  return per <= 1 ? 1 : per <= 2 ? 2 : per <= 4 ? 4 : 8;
+  return per <= 1 ? 1 : per <= 2 ? 2 : per <= 4 ? 4 : per <= 6 ? 6 : 8;
 }
 
 template <typename T>
@@ -561,6 +604,7 @@ hipError_t norm_fwd_t(int norm, int rows, int d, float eps, const void* x, const
     case 1: norm_fwd_kernel<T, 1><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
     case 2: norm_fwd_kernel<T, 2><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
     case 4: norm_fwd_kernel<T, 4><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
+    case 6: norm_fwd_kernel<T, 6><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
     default: norm_fwd_kernel<T, 8><<<rows, kThreads, 0, s>>>(xp, gp, bp, yp, stats, d, eps, norm); break;
   }
   return hipGetLastError();
@@ -579,6 +623,7 @@ hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamm
     case 1: norm_bwd_kernel<T, 1><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     case 2: norm_bwd_kernel<T, 2><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     case 4: norm_bwd_kernel<T, 4><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    case 6: norm_bwd_kernel<T, 6><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     default: norm_bwd_kernel<T, 8><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
   }
   hipError_t e = hipGetLastError();
