@@ -40,6 +40,8 @@
 //    lane on full rows; the fp32 gradient tile is read with 16-byte loads issued first.
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
 //    works on a contiguous band of tiles and shares operand panels in its own L2.
+#include <cstdlib>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -95,6 +97,8 @@ struct Epilogue {
   // Split tail (see launch_cfg): workgroups with id >= split_first each compute one of
   // split_s k-ranges of a tile and store the fp32 partial tile to split_ws; 0 = no splitting.
   int split_first; int split_s; float* split_ws;
+  // 1: tile_of_square (outputs whose tile counts are multiples of 16 in both directions)
+  int square_map;
 };
 
 struct Operand {
@@ -241,6 +245,20 @@ __device__ inline void tile_of(int pid, int tiles_m, int tiles_n, int& tm, int& 
   tn = in_band / rows_in_band;
 }
 
+// The same for large outputs whose tile counts are multiples of 16 both ways: in every round
+// of 256 workgroups the 8 XCDs work on a 2 x 4 arrangement of 8 x 4 blocks, i.e. together on a
+// 16 x 16 square of tiles, so the chip touches 32 operand panels per round instead of 68 and
+// what one XCD fetched is in the last-level cache for its neighbours; squares are visited
+// along a band of 16 tile-rows, so consecutive rounds keep the band's 16 row panels.
+__device__ inline void tile_of_square(int pid, int tiles_n, int& tm, int& tn) {
+  const int x = pid & 7, r = pid >> 3;
+  const int round = r >> 5, w = r & 31;
+  const int squares_n = tiles_n >> 4;
+  const int sq_m = round / squares_n, sq_n = round % squares_n;
+  tm = sq_m * 16 + (x >> 2) * 8 + (w & 7);
+  tn = sq_n * 16 + (x & 3) * 4 + (w >> 3);
+}
+
 // "s_waitcnt vmcnt(N); s_barrier" with a compiler-level memory barrier and no fence: the
 // fence of __syncthreads() would wait for every outstanding load, which is exactly what the
 // multi-stage ring must not do.
@@ -294,7 +312,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
     nk = (nk < kbeg + per ? nk : kbeg + per) - kbeg;   // > 0: the host sizes split_s so
   }
   int tm, tn;
-  tile_of(pid, tiles_m, tiles_n, tm, tn);
+  if (ep.square_map) tile_of_square(pid, tiles_n, tm, tn);
+  else tile_of(pid, tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -611,7 +630,11 @@ hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   Operand A{(const bf16*)g.A, g.lda, g.M};
   Operand B{(const bf16*)g.B, g.ldb, g.N};
-  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual, 0, 0, nullptr};
+  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual, 0, 0, nullptr, 0};
+  {
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    ep.square_map = BM == 256 && BN == 256 && g.out_mode == OUT_ACC_F32 && tiles_m % 16 == 0 && tiles_n % 16 == 0;
+  }
   int grid = tiles;
   const SplitPlan sp = plan_split<BM, BN, BKT, kWgsPerCu>(g.M, g.N, g.K, g.out_mode);
   const bool split = g.workspace && sp.s >= 2 && sp.bytes <= g.workspace_bytes;

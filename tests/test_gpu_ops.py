@@ -371,6 +371,9 @@ FULL_GEMMS = [
     ("ffn-down dgrad", 2048, 49152, 12288, 0, 1, B.OUT_STORE),
     ("ffn-up wgrad", 49152, 12288, 2048, 1, 1, B.OUT_ACC_F32),
     ("lm-head fwd", 4096, 50304, 4096, 0, 0, B.OUT_STORE_F32),
+    # weight gradients over a group of 8 microbatches (K = 8 * 2048)
+    ("ffn-down wgrad, group of 8", 12288, 49152, 16384, 1, 1, B.OUT_ACC_F32),
+    ("qkv wgrad, group of 4", 36864, 12288, 8192, 1, 1, B.OUT_ACC_F32),
 ]
 
 
@@ -403,6 +406,23 @@ def test_gemm_full_shape_sampled_entries(name, M, N, K, aks, bks, mode):
     tol = 4e-3 if mode == B.OUT_STORE else 1e-5
     assert rel_l2(got, ref) < tol, name
     assert np.all(np.isfinite(got))
+
+
+@pytest.mark.parametrize("M,N", [(49152, 12288), (12288, 49152), (36864, 12288), (12288, 12288), (12288 + 256, 12288),
+                                 (4096, 8192)])
+def test_accumulating_gemm_adds_to_every_tile_exactly_once(M, N):
+    """The workgroup-to-tile maps (one of them only used when both tile counts are multiples
+    of 16) must be bijections: with all-ones operands and K = 64 every element of an
+    accumulating GEMM grows by exactly 64, twice in a row."""
+    K = 64
+    A = torch.ones((K, M), dtype=torch.bfloat16, device=DEV)
+    Bm = torch.ones((K, N), dtype=torch.bfloat16, device=DEV)
+    Cc = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV)
+    for rep in (1, 2):
+        B.jpp_op_gemm(B.JPP_BF16, M, N, K, A.data_ptr(), M, 1, Bm.data_ptr(), N, 1, Cc.data_ptr(), N, B.OUT_ACC_F32,
+                      None, None, stream())
+        torch.cuda.synchronize()
+        assert bool((Cc == 3.0 + 64.0 * rep).all()), (M, N, rep)
 
 
 FULL_ATTENTION = [
