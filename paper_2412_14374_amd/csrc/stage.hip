@@ -484,7 +484,6 @@ hipError_t issue_recv_x(jpp_stage& st, Slot& slot, const void* src, size_t bytes
   // the event still orders the forward after the slot's release
   if (src) K_TRY(hipMemcpyAsync(st.layer_view(slot, 0, false).x, src, bytes, hipMemcpyDeviceToDevice, st.ss));
   K_TRY(hipEventRecord(slot.rx.ev, st.ss));
-  slot.rx_issued = true;
   return hipSuccess;
 }
 
@@ -692,7 +691,6 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
   st->grp_slot.assign((size_t)st->cfg.n_virtual * st->n_groups(), -1);
   st->grp_bwd.assign((size_t)st->cfg.n_virtual * st->n_groups(), 0);
   st->grp_fwd.assign((size_t)st->cfg.n_virtual * st->n_groups(), 0);
-  for (auto& s : st->slots) s.rx_issued = false;
   // staging buffers still pending from the previous run are ordered by the waits above
   st->tx_free.clear(); st->tx_pending.clear();
   for (int k = 0; k < kTxBuffers; ++k) st->tx_free.push_back(k);

@@ -51,7 +51,6 @@ struct Slot {
   Event freed;  // recorded on the wgrad stream when the last reader of the (group) slot is done
   Event rx;     // recorded on the side stream when the received input is in place
   Event fwd_done;  // recorded on the compute stream when the forward that filled the slot is enqueued
-  bool rx_issued = false;
 };
 
 struct TxBuf {
