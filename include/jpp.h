@@ -81,12 +81,12 @@ typedef struct {
                        * bit for bit; the stash shrinks from (8 d + 2 f) T to d T elements per layer */
   int32_t wgrad_group; /* 0 or 1: every backward task adds its own weight gradients.  g > 1: the
                        * microbatches g*k .. g*k+g-1 of a stage form a group (the last one may be
-                       * smaller).  Their backward tasks run the input-gradient chain, the bias and
-                       * norm gradients and the send as usual and keep the operands of the
+                       * smaller).  Their backward tasks run the input-gradient chain, the norm
+                       * gradients and the send as usual and keep the operands of the
                        * weight-gradient GEMMs (activations and cotangents) in the stash; the task
-                       * that completes the group runs one GEMM per weight over all the group's
-                       * tokens, so the fp32 gradient is read and written once per group, not
-                       * once per microbatch.  The sums are those of Section 3.1; only the rounding
+                       * that completes the group runs one GEMM per weight (and one column sum per
+                       * bias) over all the group's tokens, so the fp32 gradient is read and
+                       * written once per group, not once per microbatch.  The sums are those of Section 3.1; only the rounding
                        * order differs from g = 1, and it depends on the microbatch indices alone,
                        * so the result is still the same for every schedule.  A group occupies g
                        * stash places from its first forward to its last backward

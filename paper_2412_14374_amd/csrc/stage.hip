@@ -204,7 +204,8 @@ size_t carve(jpp_stage& st, char* base) {
   st.dO = take(T * m.nq * e); st.dqkv = take(T * m.nqkv * e);
   st.delta = (float*)take((size_t)m.mb * m.Hq * m.seq * 4);
   const size_t widest = std::max<size_t>({(size_t)m.d, (size_t)m.f1, (size_t)m.nqkv});
-  st.partial = (float*)take(2 * (size_t)colreduce_blocks(m.T) * widest * 4);
+  // column sums run over one microbatch's rows (norm gradients) or a whole group's (bias gradients)
+  st.partial = (float*)take(2 * (size_t)colreduce_blocks(m.T * (int)G) * widest * 4);
   st.dx_embed = c.embed ? take(T * m.d * e) : nullptr;
   if (c.loss_head) {
     st.z = (float*)take(T * m.vocab * 4);
@@ -333,8 +334,9 @@ hipError_t wgrad(jpp_stage& st, int M, int N, int K, const void* dy, int ldy, co
 // top layer's cdy), adds this microbatch's parameter gradients to the fp32 buffers and writes
 // the input cotangent to `dx_out`.  The input-gradient chain runs on the backward stream, the
 // weight-gradient GEMMs on the wgrad stream.  `wg_members`: how many members' worth of rows
-// the weight-gradient GEMMs contract over, starting at the group's first member; 0 = none
-// now (a later member of the group runs them).  Without grouping it is always 1.
+// the weight-gradient GEMMs (and the bias gradients, column sums of the same cotangents, on
+// the backward stream) cover, starting at the group's first member; 0 = none now (a later
+// member of the group runs them).  Without grouping it is always 1.
 hipError_t enqueue_backward(jpp_stage& st, int v, int i, Slot& slot, const char* dy_in, char* dx_out,
                             int wg_members) {
   const Dims& m = st.dm;
@@ -383,20 +385,20 @@ hipError_t enqueue_backward(jpp_stage& st, int v, int i, Slot& slot, const char*
     if (c.remat) K_TRY(layer_forward(st, s, v, l, w, nullptr));
     // FFN down projection
     if (wg_members) K_TRY(wgrad(st, m.d, m.f, K, wdy, m.d, g.a, m.f, gptr(st, v, o.w2)));
-    if (o.b2 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dy, m.d, gptr(st, v, o.b2), st.partial, s));
+    if (o.b2 >= 0 && wg_members) K_TRY(launch_bias_grad(dt, K, m.d, wdy, m.d, gptr(st, v, o.b2), st.partial, s));
     K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, st.da, m.f, OUT_STORE, nullptr,
                nullptr));
     K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, w.h, st.da, dh, s));
     // FFN up projection
     if (wg_members) K_TRY(wgrad(st, m.f1, m.d, K, wdh, m.f1, g.n2, m.d, gptr(st, v, o.w1)));
-    if (o.b1 >= 0) K_TRY(launch_bias_grad(dt, m.T, m.f1, dh, m.f1, gptr(st, v, o.b1), st.partial, s));
+    if (o.b1 >= 0 && wg_members) K_TRY(launch_bias_grad(dt, K, m.f1, wdh, m.f1, gptr(st, v, o.b1), st.partial, s));
     K_TRY(gemm(st, s, m.T, m.d, m.f1, dh, m.f1, false, pptr(st, v, o.w1), m.d, true, st.dn, m.d, OUT_STORE,
                nullptr, nullptr));
     K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, w.x1, pptr(st, v, o.ln2_g), (float*)w.stats2,
                           st.dn, dy, dx1, gptr(st, v, o.ln2_g), gptr(st, v, o.ln2_b), st.partial, s));
     // attention output projection
     if (wg_members) K_TRY(wgrad(st, m.d, m.nq, K, wdx1, m.d, g.O, m.nq, gptr(st, v, o.wo)));
-    if (o.bo >= 0) K_TRY(launch_bias_grad(dt, m.T, m.d, dx1, m.d, gptr(st, v, o.bo), st.partial, s));
+    if (o.bo >= 0 && wg_members) K_TRY(launch_bias_grad(dt, K, m.d, wdx1, m.d, gptr(st, v, o.bo), st.partial, s));
     K_TRY(gemm(st, s, m.T, m.nq, m.d, dx1, m.d, false, pptr(st, v, o.wo), m.nq, true, st.dO, m.nq, OUT_STORE,
                nullptr, nullptr));
     AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, w.qkv, w.O, (float*)w.lse, st.dO, dqkv, st.delta};
@@ -404,7 +406,8 @@ hipError_t enqueue_backward(jpp_stage& st, int v, int i, Slot& slot, const char*
     if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, dqkv, st.rope_table, true, s));
     // QKV projection
     if (wg_members) K_TRY(wgrad(st, m.nqkv, m.d, K, wdqkv, m.nqkv, g.n1, m.d, gptr(st, v, o.wqkv)));
-    if (o.bqkv >= 0) K_TRY(launch_bias_grad(dt, m.T, m.nqkv, dqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
+    if (o.bqkv >= 0 && wg_members)
+      K_TRY(launch_bias_grad(dt, K, m.nqkv, wdqkv, m.nqkv, gptr(st, v, o.bqkv), st.partial, s));
     K_TRY(gemm(st, s, m.T, m.d, m.nqkv, dqkv, m.nqkv, false, pptr(st, v, o.wqkv), m.d, true, st.dn, m.d,
                OUT_STORE, nullptr, nullptr));
     K_TRY(launch_norm_bwd(dt, c.norm, m.T, m.d, w.x, pptr(st, v, o.ln1_g), (float*)w.stats1,

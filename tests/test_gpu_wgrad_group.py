@@ -139,7 +139,7 @@ def test_grouped_gradients_bit_identical_across_schedules():
 def test_one_group_does_not_care_about_the_backward_order():
     """With the whole run in one group the weight gradients are one GEMM over the rows in
     microbatch-index order, whichever backward comes last: a reversed backward order gives
-    the weight gradients' bits (bias and norm gradients still add per task, in task order)."""
+    the weight gradients' bits (norm gradients still add per task, in task order)."""
     w = replace(inp.C1, wgrad_group=inp.C1.n_microbatches)
     spec, (params, x, cot, tg) = draw(w, seed=17)
     s0, M = w.stage_ids[0], w.n_microbatches
