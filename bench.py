@@ -408,8 +408,8 @@ def main():
     if w.dtype == inp.DT_BF16:
         avg_ms, flops_per_launch = time_dominant_kernel(w, torch, B)
         shapes = wgrad_shapes(w)
-        # measured for the C4 shapes only, at groups of 8 (25.4 GB) and per task (6.65 GB)
-        traffic = {8: 25.4e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
+        # measured for the C4 shapes only, at groups of 8 (29.8 GB) and per task (6.65 GB)
+        traffic = {8: 29.8e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
         ach = flops_per_launch / (avg_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel<..., k-strided A, k-strided B> "
                            "(weight gradient with fused fp32 accumulate)",
