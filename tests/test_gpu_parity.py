@@ -356,3 +356,51 @@ def test_executor_bookkeeping_and_errors():
     assert err <= 1e-5, (worst, err)
     assert B.jpp_stage_prefetched(st2.h) < 2 * w.n_microbatches - 1
     st2.close()
+
+
+def test_full_size_two_microbatches_equal_one_of_twice_the_size():
+    """Section 3.1 at the benchmark's layer shape: accumulating two microbatches of one sequence
+    each gives the gradient of one microbatch holding both sequences (a sum, no 1/M), and the
+    same outputs and input cotangents per sequence.  The two runs differ in GEMM shapes (hence
+    in tile schedule and in the association of the fp32 sums, and through them in the last bit
+    of some bf16 activations), so they agree to the bf16 tolerance, not bit for bit."""
+    from dataclasses import replace
+    base = replace(inp.C4, sched=inp.SCHED_GPIPE, P=1, V=1, rank=0)
+    wa = replace(base, microbatch=1, n_microbatches=2)
+    wb = replace(base, microbatch=2, n_microbatches=1)
+    a = Stage(wa)
+    a.set_params_random(seed=8)
+    a.bind(seed=9)
+    a.zero_grads()
+    a.run()
+    a.sync()
+    torch.cuda.synchronize()
+    ga = a.grads_tensor(0)
+    b = Stage(wb)
+    B.jpp_stage_set_params(b.h, 0, a.params_tensor(0).data_ptr(), True)
+    b.in_x = [torch.cat([a.in_x[0], a.in_x[1]], dim=0).contiguous()]
+    b.in_c = [torch.cat([a.in_c[0], a.in_c[1]], dim=0).contiguous()]
+    b.out_y = [torch.zeros_like(b.in_x[0])]
+    b.out_dx = [torch.zeros_like(b.in_x[0])]
+    b.tg = []
+    torch.cuda.synchronize()
+    B.jpp_stage_bind_boundary(b.h, [b.in_x[0].data_ptr()], [b.in_c[0].data_ptr()], [b.out_y[0].data_ptr()],
+                              [b.out_dx[0].data_ptr()], None)
+    b.zero_grads()
+    b.run()
+    b.sync()
+    torch.cuda.synchronize()
+    gb = b.grads_tensor(0)
+    assert bool(torch.isfinite(ga).all()) and bool(torch.isfinite(gb).all())
+
+    def rel(x, y):
+        return float((x.double() - y.double()).norm() / y.double().norm())
+
+    for name, shp, off in a.info:
+        n = int(np.prod(shp))
+        assert rel(ga[off:off + n], gb[off:off + n]) < TOL[inp.DT_BF16], name
+    for i in range(2):
+        assert rel(a.out_y[i][0], b.out_y[0][i]) < TOL[inp.DT_BF16]
+        assert rel(a.out_dx[i][0], b.out_dx[0][i]) < TOL[inp.DT_BF16]
+    a.close()
+    b.close()
