@@ -304,7 +304,7 @@ def test_attention_forward_backward(dtype, mb, seq, Hq, Hkv, hd):
 
 @pytest.mark.parametrize("dtype", [inp.DT_F32, inp.DT_BF16])
 @pytest.mark.parametrize("norm", [inp.NORM_LAYERNORM, inp.NORM_RMSNORM])
-@pytest.mark.parametrize("rows,d", [(5, 72), (300, 2048), (64, 12288)])
+@pytest.mark.parametrize("rows,d", [(5, 72), (300, 2048), (64, 12288), (2048, 12288)])
 def test_norm_forward_backward(dtype, norm, rows, d):
     if dtype == inp.DT_F32 and d > 8192:
         pytest.skip("fp32 rows are limited to 8192 columns")
@@ -364,6 +364,32 @@ def test_activation_forward_backward(dtype, act):
 
 
 # ------------------------------------------------------------------ full benchmark shapes
+
+@pytest.mark.parametrize("act", [inp.ACT_GELU, inp.ACT_SWIGLU])
+def test_activation_full_shape_sampled_rows(act):
+    """The element-wise kernels at the C4 FFN shape (2048 x 49152, bf16): 128 sampled rows plus
+    the first and the last against the oracle; rows between them must not be left untouched."""
+    rows, f = 2048, 49152
+    f1 = 2 * f if act == inp.ACT_SWIGLU else f
+    g = torch.Generator(device=DEV)
+    g.manual_seed(17 + act)
+    th = (torch.randn((rows, f1), generator=g, device=DEV) * 2).to(torch.bfloat16)
+    tda = torch.randn((rows, f), generator=g, device=DEV).to(torch.bfloat16)
+    a = torch.full((rows, f), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dh = torch.full((rows, f1), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.jpp_op_act_fwd(inp.DT_BF16, act, rows, f, th.data_ptr(), a.data_ptr(), stream())
+    B.jpp_op_act_bwd(inp.DT_BF16, act, rows, f, th.data_ptr(), tda.data_ptr(), dh.data_ptr(), stream())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(a.float()).all()) and bool(torch.isfinite(dh.float()).all())
+    rng = np.random.default_rng(5)
+    pick = np.unique(np.concatenate([rng.integers(0, rows, 128), [0, rows - 1]]))
+    idx = torch.from_numpy(pick).to(DEV)
+    spec = so.StageSpec(n_layers=1, d_model=8, n_q_heads=1, n_kv_heads=1, head_dim=8, d_ffn=f, seq_len=1,
+                        microbatch=1, act=act)
+    h, da = host(th[idx]), host(tda[idx])
+    assert rel_l2(host(a[idx]), so.act_forward(spec, h)) < 4e-3
+    assert rel_l2(host(dh[idx]), so.act_backward(spec, h, da)) < 4e-3
+
 
 FULL_GEMMS = [
     # the GPT-3-shaped layer's GEMMs at T = 2048 tokens: (M, N, K, a_kstrided, b_kstrided, out_mode)
