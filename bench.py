@@ -4,7 +4,12 @@
 
 A step is one jpp_stage_zero_grads + one jpp_stage_run of the configuration's whole task list
 (all microbatches, all owned stages, forward and backward, gradient accumulation, boundary
-copies), with inputs resident in HBM.  Prints one JSON line (see the design doc for the fields).
+copies), with inputs resident in HBM.  Prints one JSON line: value = algorithmic TFLOP/s of the
+whole step (linear maps 2 T d_in d_out x 3, causal attention at half, x 3; nothing recomputed or
+element-wise is counted), ms_per_step from the host clock around K steps (min and median from
+events on the compute stream), config = the workload and the executor's settings, roofline = the
+dominant kernel (the weight-gradient GEMM) timed alone with events on its own stream against
+the dense bf16 matrix peak, cpu_baseline = the fp64 oracle timed on a bounded sample.
 """
 import argparse
 import json
