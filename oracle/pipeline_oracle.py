@@ -17,7 +17,7 @@ one order in which every task runs after the task that produces its operand, whi
 the paper places the send/receive pairs ("in their topological order", Section 4.2), and
 reports a deadlock when the lists wait for each other in a cycle.
 
-Every function here is pinned by tests/test_oracle_pins.py (pipeline section): against the
+Every function here is pinned by tests/test_pipeline_oracle_pins.py: against the
 single deep stage of oracle/stage_oracle.py, the example of Section 4.2, bitwise schedule
 invariance and hand-made deadlocks.
 """
