@@ -160,13 +160,15 @@ def test_one_group_does_not_care_about_the_backward_order():
             assert rel_l2(b.double().numpy(), a.double().numpy()) < 1e-5, name
 
 
-def test_full_size_c4_groups_are_schedule_invariant():
-    """The benchmark's configuration and launch path with groups of 4 of 8 microbatches:
-    interleaved 1F1B and all-forwards-then-all-backwards give identical bits, and equal the
-    ungrouped run to fp32 rounding."""
-    w = replace(inp.C4, n_microbatches=8, wgrad_group=4)
+@pytest.mark.parametrize("name", ["C4", "C2"])
+def test_full_size_groups_are_schedule_invariant(name):
+    """The benchmark's configurations and launch paths (C4: one compute stream; C2: forward,
+    input-gradient chain and weight gradients on three) with groups of 4 of 8 microbatches:
+    the configuration's own schedule and all-forwards-then-all-backwards give identical bits,
+    and equal the ungrouped run to fp32 rounding."""
+    w = replace(inp.CONFIGS[name], n_microbatches=8, wgrad_group=4)
     M = w.n_microbatches
-    inter = B.jpp_schedule_make(inp.SCHED_INTERLEAVED, w.P, w.rank, w.V, M)
+    inter = B.jpp_schedule_make(w.sched, w.P, w.rank, w.V, M)
     flat = [(i, B.JPP_FWD, s) for s in w.stage_ids for i in range(M)]
     flat += [(i, B.JPP_BWD, s) for s in reversed(w.stage_ids) for i in range(M)]
     outs = []
