@@ -522,8 +522,11 @@ __global__ __launch_bounds__(kThreads) void embed_fwd_kernel(const int32_t* __re
   const int n16 = d * (int)sizeof(T) / 16;
   const u32x4* src = reinterpret_cast<const u32x4*>(E + (size_t)id * d);
   u32x4* dst = reinterpret_cast<u32x4*>(x + (size_t)t * d);
-  const bool ok = id >= 0 && id < vocab;
-  for (int c = threadIdx.x; c < n16; c += kThreads) dst[c] = ok ? src[c] : u32x4{0u, 0u, 0u, 0u};
+  if (id >= 0 && id < vocab) {   // the row is only addressed when the id is inside the table
+    for (int c = threadIdx.x; c < n16; c += kThreads) dst[c] = src[c];
+  } else {
+    for (int c = threadIdx.x; c < n16; c += kThreads) dst[c] = u32x4{0u, 0u, 0u, 0u};
+  }
 }
 
 // Token embedding, backward: G[id] += sum over the positions t with tok[t] == id, in

@@ -55,6 +55,9 @@ TIED = {
     # 2 actors x 2 virtual stages, fp32, few distinct ids: positions collide in the table's gradient
     "gpt-fp32-interleaved": (inp.Workload("t1", inp.DT_F32, 1, 64, 2, 2, 32, 128, 32, 2, 4, loss_head=1, embed=1,
                                           vocab=96, w_std=0.1, P=2, V=2, sched=inp.SCHED_INTERLEAVED), 7),
+    # the same with rematerialisation: the embedding's output is the first layer's kept input
+    "gpt-fp32-interleaved-remat": (inp.Workload("t1r", inp.DT_F32, 1, 64, 2, 2, 32, 128, 32, 2, 4, loss_head=1, embed=1,
+                                                remat=1, vocab=96, w_std=0.1, P=2, V=2, sched=inp.SCHED_INTERLEAVED), 7),
     # a single actor that holds both uses of the table
     "gpt-fp32-one-actor": (inp.Workload("t2", inp.DT_F32, 2, 64, 2, 2, 32, 128, 24, 1, 3, loss_head=1, embed=1,
                                         vocab=40, w_std=0.1, P=1, V=1, sched=inp.SCHED_1F1B), None),
@@ -212,6 +215,8 @@ def test_full_size_embedding_kernels_on_sampled_rows():
     rows, d, vocab = 4096, 4096, 50304
     rng = np.random.default_rng(41)
     ids = np.minimum((rng.pareto(1.1, size=rows) * 3).astype(np.int64), vocab - 1).astype(np.int32)
+    bad = [7, 1000, 4095]                       # ids outside the table: a zero row, no gradient
+    ids[bad] = [-1, vocab, 2 ** 31 - 1]
     g = torch.Generator(device="cuda:0")
     g.manual_seed(3)
     table = (torch.randn((vocab, d), generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
@@ -225,8 +230,11 @@ def test_full_size_embedding_kernels_on_sampled_rows():
     B.jpp_op_embed_fwd(B.JPP_BF16, rows, d, vocab, ids_d.data_ptr(), table.data_ptr(), x.data_ptr(), s)
     B.jpp_op_embed_bwd(B.JPP_BF16, rows, d, vocab, ids_d.data_ptr(), dx.data_ptr(), G.data_ptr(), s)
     torch.cuda.synchronize()
-    assert torch.equal(x.view(torch.int16), table[ids_d.long()].view(torch.int16))
-    counts = np.bincount(ids, minlength=vocab)
+    valid = torch.from_numpy((ids >= 0) & (ids < vocab)).to("cuda:0")
+    assert torch.equal(x[valid].view(torch.int16), table[ids_d[valid].long()].view(torch.int16))
+    assert bool((x[~valid] == 0).all()) and int((~valid).sum()) == len(bad)
+    ids = np.where((ids >= 0) & (ids < vocab), ids, 0 * ids - 1)
+    counts = np.bincount(ids[ids >= 0], minlength=vocab)
     frequent = list(np.argsort(-counts)[:4])
     rare = list(np.flatnonzero(counts == 1)[:4])
     absent = list(np.flatnonzero(counts == 0)[:4])
