@@ -378,6 +378,13 @@ jpp_status jpp_op_act_fwd(int dtype, int act, int rows, int f, const void* h, vo
 jpp_status jpp_op_act_bwd(int dtype, int act, int rows, int f, const void* h, const void* da,
                           void* dh, void* stream);
 
+/* Mean-token cross-entropy of the loss head from fp32 logits z [rows, vocab]: row_loss[r] =
+ * log sum_v exp(z[r, v]) - z[r, targets[r]] (NaN for a target outside [0, vocab)), *loss =
+ * mean of row_loss, dz = (softmax(z) - onehot(targets)) / rows in the storage dtype.  All
+ * device pointers; deterministic. */
+jpp_status jpp_op_cross_entropy(int dtype, int rows, int vocab, const float* z, const int32_t* targets, void* dz,
+                                float* row_loss, float* loss, void* stream);
+
 /* Token embedding.  x[t] = table[ids[t]] for t < rows (table [vocab, d], storage dtype; an id
  * outside [0, vocab) gives a zero row).  Backward: g_table[v] (fp32 [vocab, d]) += the sum of
  * dx[t] over the positions with ids[t] == v, in ascending t, one writer per row, no atomics;

@@ -97,6 +97,7 @@ _SIGNATURES = {
     "jpp_op_colreduce_scratch": (C.c_size_t, [C.c_int, C.c_int]),
     "jpp_op_act_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 3),
     "jpp_op_act_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
+    "jpp_op_cross_entropy": (C.c_int, [C.c_int] * 3 + [C.c_void_p] * 6),
     "jpp_op_embed_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
     "jpp_op_embed_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
 }
@@ -391,6 +392,10 @@ def jpp_op_act_fwd(dtype, act, rows, f, h, a, stream):
 
 def jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream):
     _check(lib().jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream))
+
+
+def jpp_op_cross_entropy(dtype, rows, vocab, z, targets, dz, row_loss, loss, stream):
+    _check(lib().jpp_op_cross_entropy(dtype, rows, vocab, z, targets, dz, row_loss, loss, stream))
 
 
 def jpp_op_embed_fwd(dtype, rows, d, vocab, ids, table, x, stream):

@@ -125,6 +125,15 @@ jpp_status jpp_op_act_bwd(int dtype, int act, int rows, int f, const void* h, co
   return e == hipSuccess ? JPP_OK : fail_hip(e, "activation backward launch");
 }
 
+jpp_status jpp_op_cross_entropy(int dtype, int rows, int vocab, const float* z, const int32_t* targets, void* dz,
+                                float* row_loss, float* loss, void* stream) {
+  if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
+  if (rows < 1 || vocab < 1) return fail(JPP_EINVAL, "sizes must be positive");
+  if (!z || !targets || !dz || !row_loss || !loss) return fail(JPP_EINVAL, "null operand");
+  hipError_t e = launch_cross_entropy(dtype, rows, vocab, z, targets, dz, row_loss, loss, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "cross-entropy launch");
+}
+
 jpp_status jpp_op_embed_fwd(int dtype, int rows, int d, int vocab, const int32_t* ids, const void* table, void* x,
                             void* stream) {
   if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");

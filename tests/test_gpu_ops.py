@@ -363,6 +363,41 @@ def test_activation_forward_backward(dtype, act):
     assert rel_l2(host(dh), so.act_backward(spec, h, da)) < tol
 
 
+@pytest.mark.parametrize("dtype,rows,vocab", [(inp.DT_F32, 7, 1000), (inp.DT_F32, 5, 1001), (inp.DT_F32, 3, 6),
+                                              (inp.DT_BF16, 9, 5024), (inp.DT_BF16, 4, 8), (inp.DT_BF16, 2, 70000),
+                                              (inp.DT_BF16, 4096, 50304)])
+def test_cross_entropy(dtype, rows, vocab):
+    """Loss, per-row losses and dz against the float64 definition; vocabularies that take the
+    register-resident kernel (a multiple of 4, at most 65536) and ones that do not, and the
+    C5 head's own shape (4096 x 50304: 256 sampled rows for dz, every row's loss)."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(rows + vocab)
+    z = torch.randn((rows, vocab), generator=g, device=DEV) * 3
+    tg = torch.randint(0, vocab, (rows,), generator=g, device=DEV, dtype=torch.int32)
+    tdt = torch.bfloat16 if dtype == inp.DT_BF16 else torch.float32
+    dz = torch.full((rows, vocab), float("nan"), dtype=tdt, device=DEV)
+    rl = torch.zeros(rows, dtype=torch.float32, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    B.jpp_op_cross_entropy(dtype, rows, vocab, z.data_ptr(), tg.data_ptr(), dz.data_ptr(), rl.data_ptr(),
+                           loss.data_ptr(), stream())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dz.float()).all())
+    rng = np.random.default_rng(3)
+    pick = np.arange(rows) if rows <= 256 else np.unique(np.concatenate([rng.integers(0, rows, 254), [0, rows - 1]]))
+    idx = torch.from_numpy(pick).to(DEV)
+    zh = host(z[idx])
+    th = tg[idx].cpu().numpy()
+    zs = zh - zh.max(axis=1, keepdims=True)
+    logp = zs - np.log(np.exp(zs).sum(axis=1, keepdims=True))
+    want_rl = -logp[np.arange(len(pick)), th]
+    want_dz = np.exp(logp)
+    want_dz[np.arange(len(pick)), th] -= 1.0
+    want_dz /= rows
+    assert rel_l2(host(rl[idx]), want_rl) < 1e-6
+    assert rel_l2(host(dz[idx]), want_dz) < (1e-5 if dtype == inp.DT_F32 else 4e-3)
+    assert abs(float(loss[0]) - float(rl.double().mean())) <= 1e-6 * abs(float(loss[0]))
+
+
 # ------------------------------------------------------------------ full benchmark shapes
 
 @pytest.mark.parametrize("act", [inp.ACT_GELU, inp.ACT_SWIGLU])
