@@ -358,6 +358,17 @@ jpp_status jpp_op_attention_fwd(int dtype, int mb, int seq, int Hq, int Hkv, int
 jpp_status jpp_op_attention_bwd(int dtype, int mb, int seq, int Hq, int Hkv, int hd,
                                 const void* qkv, const void* out, const float* lse,
                                 const void* dout, void* dqkv, float* delta, void* stream);
+/* The same with a scratch buffer (device, fp32, 16-byte aligned, caller-owned).  Grouped-query
+ * attention in bf16 with head_dim 128 uses it: the query heads of a kv head are then spread
+ * over workgroups, their dK / dV rows go to the scratch and a second kernel sums them in
+ * ascending head order (still no atomics), instead of one workgroup walking the whole group.
+ * jpp_op_attention_bwd_scratch_bytes returns the bytes a shape needs (0: no use for scratch);
+ * with less (or NULL) the call is jpp_op_attention_bwd. */
+size_t jpp_op_attention_bwd_scratch_bytes(int dtype, int mb, int seq, int Hq, int Hkv, int hd);
+jpp_status jpp_op_attention_bwd_ws(int dtype, int mb, int seq, int Hq, int Hkv, int hd,
+                                   const void* qkv, const void* out, const float* lse,
+                                   const void* dout, void* dqkv, float* delta, void* scratch,
+                                   size_t scratch_bytes, void* stream);
 
 /* Norm over the last axis of x [rows, d].  stats: fp32 [2*rows] (mean, rstd; mean = 0 for
  * RMSNorm).  beta may be NULL (RMSNorm). */

@@ -98,6 +98,8 @@ _SIGNATURES = {
     "jpp_op_act_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 3),
     "jpp_op_act_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
     "jpp_op_cross_entropy": (C.c_int, [C.c_int] * 3 + [C.c_void_p] * 6),
+    "jpp_op_attention_bwd_scratch_bytes": (C.c_size_t, [C.c_int] * 6),
+    "jpp_op_attention_bwd_ws": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
     "jpp_op_embed_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
     "jpp_op_embed_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
 }
@@ -392,6 +394,16 @@ def jpp_op_act_fwd(dtype, act, rows, f, h, a, stream):
 
 def jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream):
     _check(lib().jpp_op_act_bwd(dtype, act, rows, f, h, da, dh, stream))
+
+
+def jpp_op_attention_bwd_scratch_bytes(dtype, mb, seq, Hq, Hkv, hd):
+    return lib().jpp_op_attention_bwd_scratch_bytes(dtype, mb, seq, Hq, Hkv, hd)
+
+
+def jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, scratch, scratch_bytes,
+                            stream):
+    _check(lib().jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, scratch,
+                                         scratch_bytes, stream))
 
 
 def jpp_op_cross_entropy(dtype, rows, vocab, z, targets, dz, row_loss, loss, stream):

@@ -297,18 +297,28 @@ __global__ __launch_bounds__(kThreads) void attn_delta_kernel(const bf16* __rest
 //   S = Q K^T, dP = dO V^T  (A = Q / dO row tiles from LDS, B = K / V fragments in registers)
 //   P = exp(S/sqrt(hd) - lse), dS = P (dP - D)
 //   dV^T += dO^T P,  dK^T += Q^T dS  (A = transposed tiles from LDS, B = P / dS from registers)
+// With `partial` (grouped-query attention with a scratch buffer) a workgroup handles ONE query
+// head (grid x = query heads x batch) and stores its unscaled fp32 dK and dV rows to
+// partial[(b * Hq + h) * seq + key][0..127] and, mb * Hq * seq rows further, the dV rows; the
+// group's heads are then summed in ascending order by attn_bwd_dkv_reduce_kernel.  Without
+// it a workgroup walks the whole group of its kv head itself (grid x = kv heads x batch).
 __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
     const bf16* __restrict__ qkv, const bf16* __restrict__ dout, const float* __restrict__ lse,
     const float* __restrict__ delta, bf16* __restrict__ dqkv, int seq, int Hq, int Hkv, long long qkv_bytes,
-    long long dout_bytes) {
+    long long dout_bytes, float* __restrict__ partial, long long partial_dv_offset) {
   __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];
   __shared__ float lse_s[64], delta_s[64];
   char* q_tile = lds;
   char* do_tile = lds + kTileBytes;
   char* qt_tile = lds + 2 * kTileBytes;
   char* dot_tile = lds + 3 * kTileBytes;
-  const int kb = blockIdx.y, g = blockIdx.x % Hkv, b = blockIdx.x / Hkv;   // early key blocks (most query tiles) first
+  // early key blocks (most query tiles) first
+  const int kb = blockIdx.y;
+  const int heads_x = partial ? Hq : Hkv;
+  const int hx = blockIdx.x % heads_x, b = blockIdx.x / heads_x;
   const int group = Hq / Hkv;
+  const int g = partial ? hx / group : hx;
+  const int hh_first = partial ? hx % group : 0, hh_end = partial ? hh_first + 1 : group;
   const int ld = (Hq + 2 * Hkv) * HD, ldo = Hq * HD;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, l32 = lane & 31, half = lane >> 5;
   const int k0 = kb * 128, kw0 = k0 + wave * 32;
@@ -333,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
 
   const int first_tile = k0 / 64;
   const int n_tiles = (seq + 63) / 64;
-  for (int hh = 0; hh < group; ++hh) {
+  for (int hh = hh_first; hh < hh_end; ++hh) {
     const int h = g * group + hh;
     const bf16* qbase = qkv + tok0 * ld + (size_t)h * HD;
     const bf16* dobase = dout + tok0 * ldo + (size_t)h * HD;
@@ -407,6 +417,23 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
       }
     }
   }
+  if (partial) {
+    if (krow < seq) {
+      float* pk = partial + (((size_t)b * Hq + hx) * seq + krow) * HD;
+      float* pv = pk + partial_dv_offset;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          f32x4 a, c;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { a[e] = dk[dt][4 * gq + e]; c[e] = dv[dt][4 * gq + e]; }
+          *reinterpret_cast<f32x4*>(pk + dt * 32 + 8 * gq + 4 * half) = a;
+          *reinterpret_cast<f32x4*>(pv + dt * 32 + 8 * gq + 4 * half) = c;
+        }
+    }
+    return;
+  }
   if (krow < seq) {
     bf16* dkrow = dqkv + (tok0 + krow) * ld + (size_t)(Hq + g) * HD;
     bf16* dvrow = dkrow + (size_t)Hkv * HD;
@@ -420,6 +447,36 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
         *reinterpret_cast<bf16x4*>(dkrow + dt * 32 + 8 * gq + 4 * half) = a;
         *reinterpret_cast<bf16x4*>(dvrow + dt * 32 + 8 * gq + 4 * half) = c;
       }
+  }
+}
+
+// Sums the per-query-head partial dK / dV rows of a kv head in ascending head order, scales dK
+// and rounds into the gradient tensor.  One thread per (token, kv head, 4 columns).
+__global__ __launch_bounds__(kThreads) void attn_bwd_dkv_reduce_kernel(const float* __restrict__ partial,
+                                                                       long long partial_dv_offset,
+                                                                       bf16* __restrict__ dqkv, int mb, int seq, int Hq,
+                                                                       int Hkv) {
+  const int group = Hq / Hkv;
+  const int ld = (Hq + 2 * Hkv) * HD;
+  const float scale = rsqrtf((float)HD);
+  const size_t total = (size_t)mb * seq * Hkv * (HD / 4);
+  for (size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += (size_t)gridDim.x * kThreads) {
+    const int c4 = (int)(idx % (HD / 4));
+    const int g = (int)((idx / (HD / 4)) % Hkv);
+    const size_t tok = idx / ((size_t)(HD / 4) * Hkv);      // b * seq + t
+    const size_t b = tok / seq, t = tok % seq;
+    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    for (int hh = 0; hh < group; ++hh) {
+      const float* pk = partial + ((b * Hq + (size_t)(g * group + hh)) * seq + t) * HD + c4 * 4;
+      sk += *reinterpret_cast<const f32x4*>(pk);
+      sv += *reinterpret_cast<const f32x4*>(pk + partial_dv_offset);
+    }
+    bf16x4 ok, ov;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { ok[e] = (bf16)(sk[e] * scale); ov[e] = (bf16)sv[e]; }
+    bf16* row = dqkv + tok * ld + (size_t)(Hq + g) * HD + c4 * 4;
+    *reinterpret_cast<bf16x4*>(row) = ok;
+    *reinterpret_cast<bf16x4*>(row + (size_t)Hkv * HD) = ov;
   }
 }
 
@@ -533,6 +590,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
 
 bool attention_mfma_supported(const AttnDesc& a) { return a.hd == HD; }
 
+size_t attention_bwd_scratch_bytes(int mb, int seq, int Hq, int Hkv, int hd) {
+  if (hd != HD || Hq <= Hkv) return 0;
+  return (size_t)2 * mb * Hq * seq * HD * sizeof(float);
+}
+
 hipError_t launch_attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
   dim3 grid(a.Hq * a.mb, (a.seq + 127) / 128);
   const long long bytes = (long long)a.mb * a.seq * (a.Hq + 2 * a.Hkv) * HD * 2;
@@ -548,11 +610,25 @@ hipError_t launch_attention_bwd_mfma(const AttnDesc& a, hipStream_t s) {
                                                                       a.delta, a.mb, a.seq, a.Hq);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  dim3 gk(a.Hkv * a.mb, (a.seq + 127) / 128);
+  // Grouped-query attention: a kv head's workgroups walk all its query heads, few and long
+  // workgroups that a causal launch cannot balance (Llama-70B shape: 256 workgroups of 16 to
+  // 512 tiles).  With scratch the query heads are spread over workgroups and summed afterwards.
+  const bool split = a.dkv_partial != nullptr && a.Hq > a.Hkv;
+  const long long dv_off = (long long)a.mb * a.Hq * a.seq * HD;
+  dim3 gk((split ? a.Hq : a.Hkv) * a.mb, (a.seq + 127) / 128);
   attn_bwd_dkv_mfma_kernel<<<gk, kThreads, 0, s>>>((const bf16*)a.qkv, (const bf16*)a.dout, a.lse, a.delta,
-                                                   (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes, do_bytes);
+                                                   (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes, do_bytes,
+                                                   split ? a.dkv_partial : nullptr, dv_off);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (split) {
+    const size_t items = (size_t)a.mb * a.seq * a.Hkv * (HD / 4);
+    const size_t blocks = (items + kThreads - 1) / kThreads;
+    attn_bwd_dkv_reduce_kernel<<<(unsigned)(blocks < 8192 ? blocks : 8192), kThreads, 0, s>>>(
+        a.dkv_partial, dv_off, (bf16*)a.dqkv, a.mb, a.seq, a.Hq, a.Hkv);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   dim3 gq(a.Hq * a.mb, (a.seq + 127) / 128);
   attn_bwd_dq_mfma_kernel<<<gq, kThreads, 0, s>>>((const bf16*)a.qkv, (const bf16*)a.dout, a.lse, a.delta,
                                                   (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes);

@@ -49,7 +49,11 @@ struct AttnDesc {
   const void* dout;  // backward only
   void* dqkv;        // backward only
   float* delta;      // backward only, [mb, Hq, seq]
+  // backward only, optional: fp32 scratch of attention_bwd_scratch_bytes() for grouped-query
+  // attention on the MFMA path (per-query-head partial dK / dV, summed in head order)
+  float* dkv_partial = nullptr;
 };
+size_t attention_bwd_scratch_bytes(int mb, int seq, int Hq, int Hkv, int hd);   // 0: no use for scratch
 hipError_t launch_attention_fwd_generic(int dtype, const AttnDesc& a, hipStream_t s);
 hipError_t launch_attention_bwd_generic(int dtype, const AttnDesc& a, hipStream_t s);
 bool attention_mfma_supported(const AttnDesc& a);

@@ -69,13 +69,27 @@ jpp_status jpp_op_attention_fwd(int dtype, int mb, int seq, int Hq, int Hkv, int
   return e == hipSuccess ? JPP_OK : fail_hip(e, "attention forward launch");
 }
 
+size_t jpp_op_attention_bwd_scratch_bytes(int dtype, int mb, int seq, int Hq, int Hkv, int hd) {
+  if (dtype != JPP_BF16 || mb < 1 || seq < 1 || Hq < 1 || Hkv < 1) return 0;
+  return attention_bwd_scratch_bytes(mb, seq, Hq, Hkv, hd);
+}
+
 jpp_status jpp_op_attention_bwd(int dtype, int mb, int seq, int Hq, int Hkv, int hd, const void* qkv,
                                 const void* out, const float* lse, const void* dout, void* dqkv, float* delta,
                                 void* stream) {
+  return jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, nullptr, 0, stream);
+}
+
+jpp_status jpp_op_attention_bwd_ws(int dtype, int mb, int seq, int Hq, int Hkv, int hd, const void* qkv,
+                                   const void* out, const float* lse, const void* dout, void* dqkv, float* delta,
+                                   void* scratch, size_t scratch_bytes, void* stream) {
   jpp_status rc = attn_check(dtype, mb, seq, Hq, Hkv, hd);
   if (rc != JPP_OK) return rc;
   if (!qkv || !out || !lse || !dout || !dqkv || !delta) return fail(JPP_EINVAL, "null operand");
+  if (scratch && ((uintptr_t)scratch % 16) != 0) return fail(JPP_EINVAL, "scratch must be 16-byte aligned");
   AttnDesc a{mb, seq, Hq, Hkv, hd, qkv, const_cast<void*>(out), const_cast<float*>(lse), dout, dqkv, delta};
+  const size_t need = jpp_op_attention_bwd_scratch_bytes(dtype, mb, seq, Hq, Hkv, hd);
+  if (scratch && need > 0 && scratch_bytes >= need) a.dkv_partial = (float*)scratch;
   hipError_t e = (dtype == JPP_BF16 && attention_mfma_supported(a))
                      ? launch_attention_bwd_mfma(a, (hipStream_t)stream)
                      : launch_attention_bwd_generic(dtype, a, (hipStream_t)stream);

@@ -203,6 +203,10 @@ size_t carve(jpp_stage& st, char* base) {
   st.da = take(T * m.f * e); st.dh = take(T * m.f1 * e); st.dn = take(T * m.d * e); st.dx1 = take(T * m.d * e);
   st.dO = take(T * m.nq * e); st.dqkv = take(T * m.nqkv * e);
   st.delta = (float*)take((size_t)m.mb * m.Hq * m.seq * 4);
+  {
+    const size_t need = c.dtype == JPP_BF16 ? attention_bwd_scratch_bytes(m.mb, m.seq, m.Hq, m.Hkv, m.hd) : 0;
+    st.dkv_partial = need ? (float*)take(need) : nullptr;
+  }
   const size_t widest = std::max<size_t>({(size_t)m.d, (size_t)m.f1, (size_t)m.nqkv});
   // column sums run over one microbatch's rows (norm gradients) or a whole group's (bias gradients)
   st.partial = (float*)take(2 * (size_t)colreduce_blocks(m.T * (int)G) * widest * 4);
@@ -402,6 +406,7 @@ hipError_t enqueue_backward(jpp_stage& st, int v, int i, Slot& slot, const char*
     K_TRY(gemm(st, s, m.T, m.nq, m.d, dx1, m.d, false, pptr(st, v, o.wo), m.nq, true, st.dO, m.nq, OUT_STORE,
                nullptr, nullptr));
     AttnDesc a{m.mb, m.seq, m.Hq, m.Hkv, m.hd, w.qkv, w.O, (float*)w.lse, st.dO, dqkv, st.delta};
+    a.dkv_partial = st.dkv_partial;
     K_TRY(attention_bwd(st, s, a));
     if (c.rope) K_TRY(launch_rope(dt, m.mb, m.seq, m.Hq, m.Hkv, m.hd, dqkv, st.rope_table, true, s));
     // QKV projection

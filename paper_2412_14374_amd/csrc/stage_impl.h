@@ -122,6 +122,7 @@ struct jpp_stage {
   char *dbuf[2] = {nullptr, nullptr}, *da = nullptr, *dh = nullptr, *dn = nullptr, *dx1 = nullptr, *dO = nullptr,
        *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr, *z = nullptr, *row_loss = nullptr;
+  float* dkv_partial = nullptr;   // scratch of the grouped-query attention backward (null: not needed)
   char* dx_embed = nullptr;   // cotangent of the embedded input (embed stage), consumed by the table's gradient
   // GEMM split scratch, one per stream that launches store-mode GEMMs (forward, backward chain)
   char *split_f = nullptr, *split_b = nullptr;

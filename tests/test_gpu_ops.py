@@ -300,6 +300,24 @@ def test_attention_forward_backward(dtype, mb, seq, Hq, Hkv, hd):
             assert np.abs(g[:, sl]).max() < 1e-5, name
             continue
         assert rel_l2(g[:, sl], dref[:, sl]) < (1e-5 if dtype == inp.DT_F32 else 1.5e-2), name
+    # grouped-query shapes on the matrix-core path: the variant that spreads a kv head's query
+    # heads over workgroups and sums their dK / dV in head order afterwards
+    need = B.jpp_op_attention_bwd_scratch_bytes(dtype, mb, seq, Hq, Hkv, hd)
+    assert (need > 0) == (dtype == inp.DT_BF16 and hd == 128 and Hq > Hkv)
+    if need:
+        scratch = torch.full((need // 4,), float("nan"), dtype=torch.float32, device=DEV)
+        dqkv2 = torch.zeros((T, nqkv), dtype=tdt, device=DEV)
+        B.jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                  tdo.data_ptr(), dqkv2.data_ptr(), delta.data_ptr(), scratch.data_ptr(), need, stream())
+        torch.cuda.synchronize()
+        g2 = host(dqkv2)
+        assert np.array_equal(g2[:, :nq], g[:, :nq])            # dQ does not depend on it
+        for name, sl in (("dk", slice(nq, nq + nkv)), ("dv", slice(nq + nkv, nqkv))):
+            if np.linalg.norm(dref[:, sl]) == 0.0:
+                assert np.abs(g2[:, sl]).max() < 1e-5, name
+                continue
+            assert rel_l2(g2[:, sl], dref[:, sl]) < 1.5e-2, name
+            assert rel_l2(g2[:, sl], g[:, sl]) < 8e-3, name     # same sums, another association, bf16 rounding
 
 
 @pytest.mark.parametrize("dtype", [inp.DT_F32, inp.DT_BF16])
@@ -509,8 +527,11 @@ def test_attention_full_shape_sampled_heads(name, mb, seq, Hq, Hkv, kv_heads):
     dqkv = torch.zeros_like(tq)
     delta = torch.zeros((mb, Hq, seq), dtype=torch.float32, device=DEV)
     B.jpp_op_attention_fwd(inp.DT_BF16, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(), stream())
-    B.jpp_op_attention_bwd(inp.DT_BF16, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                           tdo.data_ptr(), dqkv.data_ptr(), delta.data_ptr(), stream())
+    # as the executor calls it: with the scratch a grouped-query shape asks for
+    need = B.jpp_op_attention_bwd_scratch_bytes(inp.DT_BF16, mb, seq, Hq, Hkv, hd)
+    scratch = torch.full((max(need // 4, 4),), float("nan"), dtype=torch.float32, device=DEV)
+    B.jpp_op_attention_bwd_ws(inp.DT_BF16, mb, seq, Hq, Hkv, hd, tq.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                              tdo.data_ptr(), dqkv.data_ptr(), delta.data_ptr(), scratch.data_ptr(), need, stream())
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out.float()).all()) and bool(torch.isfinite(dqkv.float()).all())
     for kv in kv_heads:
