@@ -12,15 +12,23 @@
 // unrounded fp32 accumulator is added to the fp32 gradient.
 //
 // Design (one workgroup = one BM x BN tile of C):
-//  * LDS is a ring of NS stages of BKT k-columns each and every stage is filled HBM -> LDS
-//    directly (buffer_load ... lds: no VGPRs, no ds_write).  The default is 256 x 256 x 64
-//    with two stages and eight waves: a 64-wide stage makes every row of a k-contiguous tile
-//    one full 128-byte cache line (32-wide stages fetch every line twice and lose more than
-//    their deeper prefetch gains), and 256 x 256 is the largest tile whose accumulators fit
-//    the register file -- measured on MI355X the CU-side fill rate (about 20-25 bytes per
-//    clock per CU from L2) is what bounds this kernel, so bytes per flop matter most.
-//  * Every wave instruction of such a load fills 1 KiB of LDS in lane order; bank-conflict
-//    freedom is obtained by XOR-swizzling WHICH global 16-byte chunk each lane fetches.
+//  * The default is a 256 x 256 x 64 tile, eight waves (wave tile 128 x 64), two LDS stages
+//    of 64 KB.  A 64-wide stage makes every row of a k-contiguous tile one full 128-byte
+//    cache line (32-wide stages fetch every line twice and lose more than a deeper ring
+//    gains), and 256 x 256 is the largest tile whose accumulators fit the register file --
+//    the CU-side fill rate from L2 bounds this kernel, so bytes per flop matter most.
+//  * Two loaders fill the stages.  The default ("register-staged", VG = true): every thread
+//    fetches its 16-byte chunks of k-tile kt+2 into registers while tile kt is multiplied and
+//    writes them to the free stage one iteration later, one chunk between two MFMA groups, so
+//    a load has a whole iteration to arrive.  The other (VG = false, kept as forced
+//    variants) fills a ring of NS stages HBM -> LDS directly (buffer_load ... lds: no VGPRs,
+//    no ds_write); every wave instruction of such a load fills 1 KiB of LDS in lane order,
+//    so the swizzle is applied to WHICH global chunk each lane fetches.  Its loads are inline
+//    assembly and the cross-wave hand-over is an explicit "s_waitcnt vmcnt(loads still
+//    allowed in flight); s_barrier": the compiler's wait-count pass cannot tell the stages
+//    apart and would wait for every load in flight.  It is slower on every shape measured.
+//  * LDS layouts, the same for both loaders, bank-conflict free by an XOR swizzle of the
+//    16-byte chunk index:
 //      k-contiguous tile: LDS [rows][BKT] bf16; fragment = one 16-byte read per lane.
 //      k-strided tile:    LDS [BKT][rows] bf16, as in memory; fragment = two
 //                         ds_read_b64_tr_b16 per lane (the CDNA4 transposing LDS read: lane i
@@ -28,12 +36,9 @@
 //                         4j + (i >> 2), j = 0..3, that the group's lanes address).
 //    Both give lane (row = lane % 32, half = lane / 32) the 8 k-values 16*kk + 8*half + 0..7,
 //    so the MFMA loop is the same for all four layout combinations.
-//  * The loads are inline assembly and the cross-wave hand-over is an explicit
-//    "s_waitcnt vmcnt(loads still allowed in flight); s_barrier": the compiler's wait-count
-//    pass cannot tell the stages apart and would wait for every load in flight.
-//  * Loads and fragment reads are issued between groups of MFMAs (one 32-row block each), so
-//    that their issue slots hide behind the matrix pipe; fragments are double-buffered in
-//    registers and the last k-step of a stage is split around the barrier.
+//  * Loads, LDS writes and fragment reads are issued between groups of MFMAs (one 32-row
+//    block each), so that their issue slots hide behind the matrix pipe; fragments are
+//    double-buffered in registers and the last k-step of a stage is split around the barrier.
 //  * Rows beyond the matrix read as zero through the buffer range check, the contiguous
 //    dimension is predicated, so M, N, K need only be multiples of 8.
 //  * Epilogue: accumulators go through LDS so that every global access is 8 or 16 bytes per
@@ -284,7 +289,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
   static_assert(NS >= 2 && NS <= kMaxStages, "2..5 stages");
   static_assert(MI % NI == 0 && MI % 2 == 0, "wave tile: rows a multiple of columns, at least 64 rows");
 
-  // One __shared__ array per stage (distinct objects: see the header comment).
+  // One __shared__ array per stage: distinct objects, so that the compiler's alias analysis
+  // can tell a stage that is being filled from the one that is being read.
   __shared__ __attribute__((aligned(1024))) char stage0[kStage];
   __shared__ __attribute__((aligned(1024))) char stage1[kStage];
   __shared__ __attribute__((aligned(1024))) char stage2[NS > 2 ? kStage : 16];
