@@ -19,17 +19,18 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 
-// Reduces two values at once over the workgroup.
-__device__ inline void block_sum2(float& a, float& b, float* red /* >= 2*kWaves */) {
+// Reduces two values at once over a workgroup of NW waves.
+template <int NW = kWaves>
+__device__ inline void block_sum2(float& a, float& b, float* red /* >= 2*NW */) {
   a = wave_sum(a);
   b = wave_sum(b);
   const int w = threadIdx.x / kWave;
   __syncthreads();
-  if ((threadIdx.x & (kWave - 1)) == 0) { red[w] = a; red[kWaves + w] = b; }
+  if ((threadIdx.x & (kWave - 1)) == 0) { red[w] = a; red[NW + w] = b; }
   __syncthreads();
   float ta = 0.f, tb = 0.f;
 #pragma unroll
-  for (int i = 0; i < kWaves; ++i) { ta += red[i]; tb += red[kWaves + i]; }
+  for (int i = 0; i < NW; ++i) { ta += red[i]; tb += red[NW + i]; }
   a = ta; b = tb;
 }
 
@@ -111,12 +112,17 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const T* __restrict_
 // A workgroup owns the rows {b, b + nblk, ...}; it keeps per-column partial sums of
 // dgamma/dbeta in registers and writes them to partial[b, :]; a second kernel adds the
 // nblk partials in ascending order into the fp32 gradient (no atomics).
-template <typename T, int MAXC>
-__global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
+// NT threads per workgroup.  The narrow form (256 threads, up to 8 chunks per thread) fetches
+// dx_add when a row is processed; the wide form (512 threads, for rows of 1024 chunks and more)
+// has the registers to fetch it with the row, one row ahead, so that nothing a row needs is
+// still on its way when the row's turn comes.
+template <typename T, int MAXC, int NT = kThreads, bool WIDE = false>
+__global__ __launch_bounds__(NT) void norm_bwd_kernel(
     const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
     const T* __restrict__ dy, const T* __restrict__ dx_add, T* __restrict__ dx,
     float* __restrict__ partial_g, float* __restrict__ partial_b, int rows, int d, int norm) {
-  __shared__ float red[2 * kWaves];
+  constexpr int NW = NT / kWave;
+  __shared__ float red[2 * NW];
   constexpr int N = Chunk<T>::N;
   const int nchunks = d / N;
   const float inv_d = 1.f / (float)d;
@@ -124,24 +130,27 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
   Chunk<T> gs[MAXC];
 #pragma unroll
   for (int j = 0; j < MAXC; ++j) {
-    const int c = threadIdx.x + j * kThreads;
+    const int c = threadIdx.x + j * NT;
     if (c < nchunks) gs[j] = load_chunk(gamma + (size_t)c * N);
 #pragma unroll
     for (int e = 0; e < N; ++e) { pg[j][e] = 0.f; pb[j][e] = 0.f; }
   }
   // One row's operands in registers.  The next row of this workgroup is fetched while the
   // current one is reduced and written, so a row costs one memory latency, not three.
-  struct Row { Chunk<T> xs[MAXC], ds[MAXC]; float mean, rstd; };
+  struct Row { Chunk<T> xs[MAXC], ds[MAXC], as[WIDE ? MAXC : 1]; float mean, rstd; };
   auto fetch = [&](int r, Row& w) {
     const size_t base = (size_t)r * d;
     w.mean = stats[2 * (size_t)r];
     w.rstd = stats[2 * (size_t)r + 1];
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-      const int c = threadIdx.x + j * kThreads;
+      const int c = threadIdx.x + j * NT;
       if (c < nchunks) {
         w.xs[j] = load_chunk(x + base + (size_t)c * N);
         w.ds[j] = load_chunk(dy + base + (size_t)c * N);
+        if constexpr (WIDE) {
+          if (dx_add != nullptr) w.as[j] = load_chunk(dx_add + base + (size_t)c * N);
+        }
       }
     }
   };
@@ -150,17 +159,20 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
     const float mean = w.mean, rstd = w.rstd;
     // the tensor added to the result is only needed after the reduction: its latency hides there
     Chunk<T> as[MAXC];
-    if (dx_add != nullptr) {
+    if constexpr (WIDE) {
+#pragma unroll
+      for (int j = 0; j < MAXC; ++j) as[j] = w.as[j];
+    } else if (dx_add != nullptr) {
 #pragma unroll
       for (int j = 0; j < MAXC; ++j) {
-        const int c = threadIdx.x + j * kThreads;
+        const int c = threadIdx.x + j * NT;
         if (c < nchunks) as[j] = load_chunk(dx_add + base + (size_t)c * N);
       }
     }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-      const int c = threadIdx.x + j * kThreads;
+      const int c = threadIdx.x + j * NT;
       if (c < nchunks) {
 #pragma unroll
         for (int e = 0; e < N; ++e) {
@@ -174,12 +186,12 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
         }
       }
     }
-    block_sum2(s1, s2, red);
+    block_sum2<NW>(s1, s2, red);
     const float m1 = (norm == JPP_LAYERNORM) ? s1 * inv_d : 0.f;
     const float m2 = s2 * inv_d;
 #pragma unroll
     for (int j = 0; j < MAXC; ++j) {
-      const int c = threadIdx.x + j * kThreads;
+      const int c = threadIdx.x + j * NT;
       if (c < nchunks) {
         Chunk<T> o;
 #pragma unroll
@@ -219,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
   }
 #pragma unroll
   for (int j = 0; j < MAXC; ++j) {
-    const int c = threadIdx.x + j * kThreads;
+    const int c = threadIdx.x + j * NT;
     if (c < nchunks) {
       const size_t o = (size_t)blockIdx.x * d + (size_t)c * N;
 #pragma unroll
@@ -233,16 +245,22 @@ __global__ __launch_bounds__(kThreads) void norm_bwd_kernel(
 
 // g[col] += sum_b partial[b, col].  32 columns x 8 row groups per workgroup: group q adds the
 // partial rows q, q+8, ... in ascending order, then the 8 group sums are added in ascending
-// order: a fixed association, independent of timing.
+// order: a fixed association, independent of timing.  A launch with gridDim.y = 2 finishes a
+// second (partial2, g2) pair of the same shape in its y = 1 workgroups.
 constexpr int kFinCols = 32, kFinGroups = kThreads / kFinCols;
 __global__ __launch_bounds__(kThreads) void colreduce_finish_kernel(const float* __restrict__ partial,
-                                                                    int nblk, int n, float* __restrict__ g) {
+                                                                    int nblk, int n, float* __restrict__ g,
+                                                                    const float* __restrict__ partial2 = nullptr,
+                                                                    float* __restrict__ g2 = nullptr) {
   __shared__ float red[kFinGroups][kFinCols];
+  if (blockIdx.y == 1) { partial = partial2; g = g2; }
   const int c = threadIdx.x % kFinCols, q = threadIdx.x / kFinCols;
   const int col = blockIdx.x * kFinCols + c;
   float acc = 0.f;
-  if (col < n)
+  if (col < n) {
+#pragma unroll 8
     for (int b = q; b < nblk; b += kFinGroups) acc += partial[(size_t)b * n + col];
+  }
   red[q][c] = acc;
   __syncthreads();
   if (q == 0 && col < n) {
@@ -682,6 +700,15 @@ hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamm
   float* pb = (norm == JPP_LAYERNORM && g_beta) ? partial + (size_t)nblk * d : nullptr;
   const T* xp = (const T*)x; const T* gp = (const T*)gamma; const T* dyp = (const T*)dy;
   const T* ap = (const T*)dx_add; T* dxp = (T*)dx;
+  // wide form: rows of 1024 chunks and more whose two rows in flight fit the registers
+  // (24 elements per thread and row: bf16 up to 12288 columns, fp32 up to 8192)
+  const int nchunks = d / Chunk<T>::N;
+  const int per = (nchunks + 511) / 512;
+  if (nchunks >= 1024 && per * Chunk<T>::N <= 24) {
+    if (per <= 2) norm_bwd_kernel<T, 2, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+    else if (per == 3) norm_bwd_kernel<T, 3, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+    else norm_bwd_kernel<T, 4, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+  } else
   switch (pick_maxc<T>(d)) {
     case 1: norm_bwd_kernel<T, 1><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     case 2: norm_bwd_kernel<T, 2><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
@@ -692,8 +719,7 @@ hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamm
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int fin = (d + kFinCols - 1) / kFinCols;
-  colreduce_finish_kernel<<<fin, kThreads, 0, s>>>(pg, nblk, d, g_gamma);
-  if (pb) colreduce_finish_kernel<<<fin, kThreads, 0, s>>>(pb, nblk, d, g_beta);
+  colreduce_finish_kernel<<<dim3(fin, pb ? 2 : 1), kThreads, 0, s>>>(pg, nblk, d, g_gamma, pb, g_beta);
   return hipGetLastError();
 }
 

@@ -322,7 +322,10 @@ def test_attention_forward_backward(dtype, mb, seq, Hq, Hkv, hd):
 
 @pytest.mark.parametrize("dtype", [inp.DT_F32, inp.DT_BF16])
 @pytest.mark.parametrize("norm", [inp.NORM_LAYERNORM, inp.NORM_RMSNORM])
-@pytest.mark.parametrize("rows,d", [(5, 72), (300, 2048), (64, 12288), (2048, 12288)])
+@pytest.mark.parametrize("rows,d", [(5, 72), (300, 2048), (64, 12288), (2048, 12288),
+                                    # rows of 1024 chunks and more take the 512-thread backward form:
+                                    # exact multiples, ragged last chunks per thread, no added tensor (odd rows)
+                                    (40, 8192), (33, 8200), (300, 6144), (17, 12280), (600, 4096)])
 def test_norm_forward_backward(dtype, norm, rows, d):
     if dtype == inp.DT_F32 and d > 8192:
         pytest.skip("fp32 rows are limited to 8192 columns")
@@ -344,9 +347,13 @@ def test_norm_forward_backward(dtype, norm, rows, d):
     gg = torch.ones(d, dtype=torch.float32, device=DEV)
     gb = torch.ones(d, dtype=torch.float32, device=DEV)
     part = torch.zeros(B.jpp_op_colreduce_scratch(rows, d), dtype=torch.float32, device=DEV)
+    with_add = rows % 2 == 0
     B.jpp_op_norm_bwd(dtype, norm, rows, d, tx.data_ptr(), tg.data_ptr(), stats.data_ptr(), tdy.data_ptr(),
-                      tadd.data_ptr(), dx.data_ptr(), gg.data_ptr(), gb.data_ptr(), part.data_ptr(), stream())
+                      tadd.data_ptr() if with_add else None, dx.data_ptr(), gg.data_ptr(), gb.data_ptr(),
+                      part.data_ptr(), stream())
     torch.cuda.synchronize()
+    if not with_add:
+        add = 0.0
     yr, xhat, rstd = so.norm_forward(spec, x, g, b if norm == inp.NORM_LAYERNORM else 0.0)
     dxr, dgr, dbr = so.norm_backward(spec, dy, xhat, rstd, g)
     tol = 1e-5 if dtype == inp.DT_F32 else 6e-3
