@@ -313,70 +313,82 @@ __device__ inline float gelu_tanh_grad(float h) {
 }
 __device__ inline float sigmoidf(float t) { return 1.f / (1.f + __expf(-t)); }
 
-template <typename T>
+// A thread owns one 16-byte column chunk and walks the rows kActRows at a time: the loads of
+// the rows of one step are all issued before the first is used, and no index is divided.
+constexpr int kActRows = 4;
+
+template <typename T, int ACT>
 __global__ __launch_bounds__(kThreads) void act_fwd_kernel(const T* __restrict__ h, T* __restrict__ a,
-                                                           int rows, int f, int act) {
+                                                           int rows, int f) {
   constexpr int N = Chunk<T>::N;
-  const int cpr = f / N;  // chunks per output row
-  const size_t total = (size_t)rows * cpr;
-  for (size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
-       idx += (size_t)gridDim.x * kThreads) {
-    const size_t r = idx / cpr;
-    const int c = (int)(idx - r * cpr);
-    Chunk<T> o;
-    if (act == JPP_SWIGLU) {
-      const Chunk<T> g = load_chunk(h + r * 2 * f + (size_t)c * N);
-      const Chunk<T> u = load_chunk(h + r * 2 * f + f + (size_t)c * N);
+  const int c = blockIdx.x * kThreads + threadIdx.x;   // chunk of the output row
+  if (c * N >= f) return;
+  const size_t hld = ACT == JPP_SWIGLU ? 2 * (size_t)f : (size_t)f;
+  for (int r0 = blockIdx.y * kActRows; r0 < rows; r0 += gridDim.y * kActRows) {
+    Chunk<T> v[kActRows], u[kActRows];
 #pragma unroll
-      for (int e = 0; e < N; ++e) { const float t = g.get(e); o.set(e, t * sigmoidf(t) * u.get(e)); }
-    } else {
-      const Chunk<T> v = load_chunk(h + r * f + (size_t)c * N);
-      if (act == JPP_GELU) {
-#pragma unroll
-        for (int e = 0; e < N; ++e) o.set(e, gelu_erf(v.get(e)));
-      } else {
-#pragma unroll
-        for (int e = 0; e < N; ++e) o.set(e, gelu_tanh(v.get(e)));
+    for (int j = 0; j < kActRows; ++j) {
+      if (r0 + j < rows) {
+        v[j] = load_chunk(h + (size_t)(r0 + j) * hld + (size_t)c * N);
+        if (ACT == JPP_SWIGLU) u[j] = load_chunk(h + (size_t)(r0 + j) * hld + f + (size_t)c * N);
       }
     }
-    store_chunk(a + r * f + (size_t)c * N, o);
+#pragma unroll
+    for (int j = 0; j < kActRows; ++j) {
+      if (r0 + j < rows) {
+        Chunk<T> o;
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+          const float t = v[j].get(e);
+          if (ACT == JPP_SWIGLU) o.set(e, t * sigmoidf(t) * u[j].get(e));
+          else if (ACT == JPP_GELU) o.set(e, gelu_erf(t));
+          else o.set(e, gelu_tanh(t));
+        }
+        store_chunk(a + (size_t)(r0 + j) * f + (size_t)c * N, o);
+      }
+    }
   }
 }
 
-template <typename T>
+template <typename T, int ACT>
 __global__ __launch_bounds__(kThreads) void act_bwd_kernel(const T* __restrict__ h, const T* __restrict__ da,
-                                                           T* __restrict__ dh, int rows, int f, int act) {
+                                                           T* __restrict__ dh, int rows, int f) {
   constexpr int N = Chunk<T>::N;
-  const int cpr = f / N;
-  const size_t total = (size_t)rows * cpr;
-  for (size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
-       idx += (size_t)gridDim.x * kThreads) {
-    const size_t r = idx / cpr;
-    const int c = (int)(idx - r * cpr);
-    const Chunk<T> d = load_chunk(da + r * f + (size_t)c * N);
-    if (act == JPP_SWIGLU) {
-      const Chunk<T> g = load_chunk(h + r * 2 * f + (size_t)c * N);
-      const Chunk<T> u = load_chunk(h + r * 2 * f + f + (size_t)c * N);
-      Chunk<T> og, ou;
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c * N >= f) return;
+  const size_t hld = ACT == JPP_SWIGLU ? 2 * (size_t)f : (size_t)f;
+  for (int r0 = blockIdx.y * kActRows; r0 < rows; r0 += gridDim.y * kActRows) {
+    Chunk<T> d[kActRows], v[kActRows], u[kActRows];
 #pragma unroll
-      for (int e = 0; e < N; ++e) {
-        const float t = g.get(e), sg = sigmoidf(t), dv = d.get(e);
-        og.set(e, dv * u.get(e) * sg * (1.f + t * (1.f - sg)));
-        ou.set(e, dv * t * sg);
+    for (int j = 0; j < kActRows; ++j) {
+      if (r0 + j < rows) {
+        d[j] = load_chunk(da + (size_t)(r0 + j) * f + (size_t)c * N);
+        v[j] = load_chunk(h + (size_t)(r0 + j) * hld + (size_t)c * N);
+        if (ACT == JPP_SWIGLU) u[j] = load_chunk(h + (size_t)(r0 + j) * hld + f + (size_t)c * N);
       }
-      store_chunk(dh + r * 2 * f + (size_t)c * N, og);
-      store_chunk(dh + r * 2 * f + f + (size_t)c * N, ou);
-    } else {
-      const Chunk<T> v = load_chunk(h + r * f + (size_t)c * N);
-      Chunk<T> o;
-      if (act == JPP_GELU) {
+    }
 #pragma unroll
-        for (int e = 0; e < N; ++e) o.set(e, d.get(e) * gelu_erf_grad(v.get(e)));
-      } else {
+    for (int j = 0; j < kActRows; ++j) {
+      if (r0 + j < rows) {
+        T* out = dh + (size_t)(r0 + j) * hld + (size_t)c * N;
+        if (ACT == JPP_SWIGLU) {
+          Chunk<T> og, ou;
 #pragma unroll
-        for (int e = 0; e < N; ++e) o.set(e, d.get(e) * gelu_tanh_grad(v.get(e)));
+          for (int e = 0; e < N; ++e) {
+            const float t = v[j].get(e), sg = sigmoidf(t), dv = d[j].get(e);
+            og.set(e, dv * u[j].get(e) * sg * (1.f + t * (1.f - sg)));
+            ou.set(e, dv * t * sg);
+          }
+          store_chunk(out, og);
+          store_chunk(out + f, ou);
+        } else {
+          Chunk<T> o;
+#pragma unroll
+          for (int e = 0; e < N; ++e)
+            o.set(e, d[j].get(e) * (ACT == JPP_GELU ? gelu_erf_grad(v[j].get(e)) : gelu_tanh_grad(v[j].get(e))));
+          store_chunk(out, o);
+        }
       }
-      store_chunk(dh + r * f + (size_t)c * N, o);
     }
   }
 }
@@ -763,24 +775,46 @@ hipError_t launch_bias_grad(int dtype, int rows, int n, const void* dy, int ld, 
   return hipGetLastError();
 }
 
-hipError_t launch_act_fwd(int dtype, int act, int rows, int f, const void* h, void* a, hipStream_t s) {
+namespace {
+// x: 256 chunks of a row per workgroup; y: as many row groups as keep about 16 workgroups per CU
+dim3 act_grid(int dtype, int rows, int f) {
   const int N = dtype == JPP_BF16 ? 8 : 4;
-  const int grid = grid_for((size_t)rows * (f / N));
-  if (dtype == JPP_BF16)
-    act_fwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)h, (bf16*)a, rows, f, act);
-  else
-    act_fwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)h, (float*)a, rows, f, act);
+  const int gx = (f / N + kThreads - 1) / kThreads;
+  int gy = (rows + kActRows - 1) / kActRows;
+  const int cap = (256 * 16 + gx - 1) / gx;
+  if (gy > cap) gy = cap;
+  return dim3(gx, gy < 1 ? 1 : gy);
+}
+
+template <typename T>
+void act_fwd_t(int act, int rows, int f, const void* h, void* a, dim3 grid, hipStream_t s) {
+  const T* hp = (const T*)h; T* ap = (T*)a;
+  if (act == JPP_SWIGLU) act_fwd_kernel<T, JPP_SWIGLU><<<grid, kThreads, 0, s>>>(hp, ap, rows, f);
+  else if (act == JPP_GELU) act_fwd_kernel<T, JPP_GELU><<<grid, kThreads, 0, s>>>(hp, ap, rows, f);
+  else act_fwd_kernel<T, JPP_GELU_TANH><<<grid, kThreads, 0, s>>>(hp, ap, rows, f);
+}
+
+template <typename T>
+void act_bwd_t(int act, int rows, int f, const void* h, const void* da, void* dh, dim3 grid, hipStream_t s) {
+  const T* hp = (const T*)h; const T* dp = (const T*)da; T* op = (T*)dh;
+  if (act == JPP_SWIGLU) act_bwd_kernel<T, JPP_SWIGLU><<<grid, kThreads, 0, s>>>(hp, dp, op, rows, f);
+  else if (act == JPP_GELU) act_bwd_kernel<T, JPP_GELU><<<grid, kThreads, 0, s>>>(hp, dp, op, rows, f);
+  else act_bwd_kernel<T, JPP_GELU_TANH><<<grid, kThreads, 0, s>>>(hp, dp, op, rows, f);
+}
+}  // namespace
+
+hipError_t launch_act_fwd(int dtype, int act, int rows, int f, const void* h, void* a, hipStream_t s) {
+  const dim3 grid = act_grid(dtype, rows, f);
+  if (dtype == JPP_BF16) act_fwd_t<bf16>(act, rows, f, h, a, grid, s);
+  else act_fwd_t<float>(act, rows, f, h, a, grid, s);
   return hipGetLastError();
 }
 
 hipError_t launch_act_bwd(int dtype, int act, int rows, int f, const void* h, const void* da, void* dh,
                           hipStream_t s) {
-  const int N = dtype == JPP_BF16 ? 8 : 4;
-  const int grid = grid_for((size_t)rows * (f / N));
-  if (dtype == JPP_BF16)
-    act_bwd_kernel<bf16><<<grid, kThreads, 0, s>>>((const bf16*)h, (const bf16*)da, (bf16*)dh, rows, f, act);
-  else
-    act_bwd_kernel<float><<<grid, kThreads, 0, s>>>((const float*)h, (const float*)da, (float*)dh, rows, f, act);
+  const dim3 grid = act_grid(dtype, rows, f);
+  if (dtype == JPP_BF16) act_bwd_t<bf16>(act, rows, f, h, da, dh, grid, s);
+  else act_bwd_t<float>(act, rows, f, h, da, dh, grid, s);
   return hipGetLastError();
 }
 

@@ -368,8 +368,8 @@ def test_norm_forward_backward(dtype, norm, rows, d):
 
 @pytest.mark.parametrize("dtype", [inp.DT_F32, inp.DT_BF16])
 @pytest.mark.parametrize("act", [inp.ACT_GELU, inp.ACT_GELU_TANH, inp.ACT_SWIGLU])
-def test_activation_forward_backward(dtype, act):
-    rows, f = 77, 520
+@pytest.mark.parametrize("rows,f", [(77, 520), (9, 4104)])   # ragged row groups; several column blocks, ragged last
+def test_activation_forward_backward(dtype, act, rows, f):
     rng = np.random.default_rng(act)
     spec = so.StageSpec(n_layers=1, d_model=8, n_q_heads=1, n_kv_heads=1, head_dim=8, d_ffn=f, seq_len=1,
                         microbatch=1, act=act)
