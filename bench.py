@@ -186,10 +186,14 @@ def bench_kernels(w, torch, B, inp):
     ms = timed(lambda: B.jpp_op_attention_fwd(B.JPP_BF16, mb, seq, Hq, Hkv, hd, qkv.data_ptr(), out.data_ptr(),
                                               lse.data_ptr(), strm))
     emit("attention fwd", f"mb{mb} seq{seq} Hq{Hq} Hkv{Hkv} hd{hd}", ms, fl, "mfma")
-    ms = timed(lambda: B.jpp_op_attention_bwd(B.JPP_BF16, mb, seq, Hq, Hkv, hd, qkv.data_ptr(), out.data_ptr(),
-                                              lse.data_ptr(), do.data_ptr(), dqkv.data_ptr(), delta.data_ptr(), strm))
+    # with the scratch the executor gives it (grouped-query shapes spread a kv head's query heads)
+    need = B.jpp_op_attention_bwd_scratch_bytes(B.JPP_BF16, mb, seq, Hq, Hkv, hd)
+    scr = torch.empty(max(need // 4, 4), dtype=torch.float32, device=dev)
+    ms = timed(lambda: B.jpp_op_attention_bwd_ws(B.JPP_BF16, mb, seq, Hq, Hkv, hd, qkv.data_ptr(), out.data_ptr(),
+                                                 lse.data_ptr(), do.data_ptr(), dqkv.data_ptr(), delta.data_ptr(),
+                                                 scr.data_ptr() if need else None, need, strm))
     emit("attention bwd (delta + dK/dV + dQ kernels)", f"mb{mb} seq{seq} Hq{Hq} Hkv{Hkv} hd{hd}", ms, 2 * fl, "mfma")
-    del qkv, do, out, lse, dqkv, delta
+    del qkv, do, out, lse, dqkv, delta, scr
     x = torch.randn(T, d, device=dev).to(bf)
     y, dy, dx = torch.zeros_like(x), torch.randn(T, d, device=dev).to(bf), torch.zeros_like(x)
     gam, bet = torch.ones(d, dtype=bf, device=dev), torch.zeros(d, dtype=bf, device=dev)
@@ -212,6 +216,31 @@ def bench_kernels(w, torch, B, inp):
     emit("activation fwd", f"{T}x{f}", ms, (6.0 if swiglu else 4.0) * T * f, "hbm")
     ms = timed(lambda: B.jpp_op_act_bwd(B.JPP_BF16, w.act, T, f, h.data_ptr(), da.data_ptr(), dh.data_ptr(), strm))
     emit("activation bwd", f"{T}x{f}", ms, (10.0 if swiglu else 6.0) * T * f, "hbm")
+    del h, a_, da, dh
+    if w.loss_head:
+        # the last stage's head: logits (fp32), cross-entropy with its gradient (bf16), the two backward GEMMs
+        V = w.vocab
+        nf = torch.randn(T, d, device=dev).to(bf)
+        Wh = (torch.randn(V, d, device=dev) * 0.02).to(bf)
+        z = torch.zeros(T, V, dtype=torch.float32, device=dev)
+        dz = torch.zeros(T, V, dtype=bf, device=dev)
+        dn = torch.zeros(T, d, dtype=bf, device=dev)
+        G = torch.zeros(V, d, dtype=torch.float32, device=dev)
+        tgt = torch.randint(0, V, (T,), dtype=torch.int32, device=dev)
+        row_loss, loss = torch.zeros(T, dtype=torch.float32, device=dev), torch.zeros(1, dtype=torch.float32, device=dev)
+
+        def gemm(M, N, K, A, lda, aks, Bm, ldb, bks, Cc, mode):
+            need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, mode)
+            ws = torch.empty(max(need // 4, 4), dtype=torch.float32, device=dev)
+            return timed(lambda: B.jpp_op_gemm_ws(B.JPP_BF16, M, N, K, A.data_ptr(), lda, aks, Bm.data_ptr(), ldb, bks,
+                                                  Cc.data_ptr(), N, mode, None, None, ws.data_ptr() if need else None,
+                                                  need, strm))
+        emit("gemm head fwd (fp32 logits)", f"{T}x{V}x{d}", gemm(T, V, d, nf, d, 0, Wh, d, 0, z, 1), 2.0 * T * V * d, "mfma")
+        ms = timed(lambda: B.jpp_op_cross_entropy(B.JPP_BF16, T, V, z.data_ptr(), tgt.data_ptr(), dz.data_ptr(),
+                                                  row_loss.data_ptr(), loss.data_ptr(), strm))
+        emit("cross-entropy (loss + dz)", f"{T}x{V}", ms, 6.0 * T * V, "hbm")
+        emit("gemm head dgrad", f"{T}x{d}x{V}", gemm(T, d, V, dz, V, 0, Wh, d, 1, dn, 0), 2.0 * T * V * d, "mfma")
+        emit("gemm head wgrad", f"{V}x{d}x{T}", gemm(V, d, T, dz, V, 1, nf, d, 1, G, 2), 2.0 * T * V * d, "mfma")
 
 
 def bench_pipeline(a, w, torch, B, inp):
