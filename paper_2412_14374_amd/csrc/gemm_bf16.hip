@@ -16,7 +16,7 @@
 //    of 64 KB.  A 64-wide stage makes every row of a k-contiguous tile one full 128-byte
 //    cache line (32-wide stages fetch every line twice and lose more than a deeper ring
 //    gains), and 256 x 256 is the largest tile whose accumulators fit the register file --
-//    the CU-side fill rate from L2 bounds this kernel, so bytes per flop matter most.
+//    the L2 -> CU path is the busiest resource beside the matrix pipe, so bytes per flop matter most.
 //  * Two loaders fill the stages.  The default ("register-staged", VG = true): every thread
 //    fetches its 16-byte chunks of k-tile kt+2 into registers while tile kt is multiplied and
 //    writes them to the free stage one iteration later, one chunk between two MFMA groups, so
