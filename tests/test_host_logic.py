@@ -188,3 +188,15 @@ def test_pipeline_merge_order_matches_the_oracle_and_reports_deadlocks():
     with pytest.raises(B.JppError) as e:
         B.jpp_pipeline_merge_order(2, 2, 1, [[(0, "fwd", 1)], good1])      # stage 1 is not actor 0's
     assert e.value.status == B.JPP_ESCHED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one stage on one GPU: --gpus above 1 ends with a message and a
+    non-zero status before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
