@@ -413,9 +413,17 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
               const int grp = kk * MI + i;
               if (kk == KSTEPS - 1 && i == MI / 2) {
                 __syncthreads();  // tile kt+1 is complete in `nxt`; nobody reads `cur` any more
-#pragma unroll
-                for (int ii = 0; ii < MI; ++ii) read_frag_part(nxt, 0, 0, ii);
               }
+              // A group's memory work sits between its MFMAs, not in front of them: the wave
+              // issues an MFMA, then its LDS write and global load (or fragment reads) while the
+              // matrix pipe works on it, then the next MFMA.  After the barrier the fragments of
+              // the next tile's first k-step are fetched the same way, spread over the two
+              // groups that remain (set 0; the last k-step multiplies from set 1).
+              static_assert((KSTEPS - 1) % 2 == 1, "the last k-step must use fragment set 1");
+              const bool after_barrier = kk == KSTEPS - 1 && i >= MI / 2;
+              __builtin_amdgcn_sched_barrier(0);
+              acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][0], acc[i][0], 0, 0, 0);
+              __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
               for (int idx = 0; idx < L; ++idx) {
                 if (idx * kBefore / L == grp) {   // chunks spread evenly over the groups before the barrier
@@ -423,10 +431,21 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
                   vload(kt + 2, idx);
                 }
               }
+              if (after_barrier && i == MI / 2) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j) bfr[0][j] = TB::frag(nxt, b_base[j], 0);
+              }
+              __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+              for (int j = 1; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+              __builtin_amdgcn_sched_barrier(0);
               if (kk + 1 < KSTEPS) read_frag_part(cur, kk + 1, (kk + 1) & 1, i);
-              __builtin_amdgcn_sched_barrier(0);
-              mfma_row(kk & 1, i);
-              __builtin_amdgcn_sched_barrier(0);
+              if (after_barrier) {
+                const int first = (i - MI / 2) * 2;      // two A fragments per group after the barrier
+#pragma unroll
+                for (int ii = first; ii < first + 2 && ii < MI; ++ii) af[0][ii] = TA::frag(nxt, a_base[ii], 0);
+              }
             }
           }
         }
