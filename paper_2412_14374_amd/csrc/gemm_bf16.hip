@@ -36,9 +36,12 @@
 //                         4j + (i >> 2), j = 0..3, that the group's lanes address).
 //    Both give lane (row = lane % 32, half = lane / 32) the 8 k-values 16*kk + 8*half + 0..7,
 //    so the MFMA loop is the same for all four layout combinations.
-//  * Loads, LDS writes and fragment reads are issued between groups of MFMAs (one 32-row
-//    block each), so that their issue slots hide behind the matrix pipe; fragments are
-//    double-buffered in registers and the last k-step of a stage is split around the barrier.
+//  * Loads, LDS writes and fragment reads are issued between the single MFMAs of a group (one
+//    32-row block): MFMA, the group's LDS write and global load, MFMA, the group's fragment
+//    reads -- a wave's memory instructions then issue while the matrix pipe works on that
+//    wave's own MFMA, which measures 3 % faster than memory work in front of each group.
+//    Fragments are double-buffered in registers and the last k-step of a stage is split around
+//    the barrier; the next stage's first fragments are spread over the groups behind it.
 //  * Rows beyond the matrix read as zero through the buffer range check, the contiguous
 //    dimension is predicated, so M, N, K need only be multiples of 8.
 //  * Epilogue: accumulators go through LDS so that every global access is 8 or 16 bytes per
