@@ -37,9 +37,10 @@
 //    Both give lane (row = lane % 32, half = lane / 32) the 8 k-values 16*kk + 8*half + 0..7,
 //    so the MFMA loop is the same for all four layout combinations.
 //  * Loads, LDS writes and fragment reads are issued between the single MFMAs of a group (one
-//    32-row block): MFMA, the group's LDS write and global load, MFMA, the group's fragment
-//    reads -- a wave's memory instructions then issue while the matrix pipe works on that
-//    wave's own MFMA, which measures 3 % faster than memory work in front of each group.
+//    32-row block): MFMA, the group's LDS write, MFMA, the global load that refills the
+//    register just written and the group's fragment reads -- a wave's memory instructions
+//    then issue while the matrix pipe works on that wave's own MFMA, which measures 4 % faster
+//    than memory work in front of each group.
 //    Fragments are double-buffered in registers and the last k-step of a stage is split around
 //    the barrier; the next stage's first fragments are spread over the groups behind it.
 //  * Rows beyond the matrix read as zero through the buffer range check, the contiguous
@@ -418,8 +419,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
                 __syncthreads();  // tile kt+1 is complete in `nxt`; nobody reads `cur` any more
               }
               // A group's memory work sits between its MFMAs, not in front of them: the wave
-              // issues an MFMA, then its LDS write and global load (or fragment reads) while the
-              // matrix pipe works on it, then the next MFMA.  After the barrier the fragments of
+              // issues an MFMA, then its LDS write while the matrix pipe works on it, then the
+              // next MFMA, then the global load and the fragment reads.  The LDS write and the
+              // load that refills its register are in different gaps, so the load is not held
+              // up behind the write's wait for the register.  After the barrier the fragments of
               // the next tile's first k-step are fetched the same way, spread over the two
               // groups that remain (set 0; the last k-step multiplies from set 1).
               static_assert((KSTEPS - 1) % 2 == 1, "the last k-step must use fragment set 1");
@@ -428,12 +431,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
               acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][0], acc[i][0], 0, 0, 0);
               __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-              for (int idx = 0; idx < L; ++idx) {
-                if (idx * kBefore / L == grp) {   // chunks spread evenly over the groups before the barrier
-                  vstore(nxt, idx);
-                  vload(kt + 2, idx);
-                }
-              }
+              for (int idx = 0; idx < L; ++idx)
+                if (idx * kBefore / L == grp) vstore(nxt, idx);   // chunks spread evenly over the groups before the barrier
               if (after_barrier && i == MI / 2) {
 #pragma unroll
                 for (int j = 0; j < NI; ++j) bfr[0][j] = TB::frag(nxt, b_base[j], 0);
@@ -443,6 +442,9 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
               for (int j = 1; j < NI; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
               __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+              for (int idx = 0; idx < L; ++idx)
+                if (idx * kBefore / L == grp) vload(kt + 2, idx);  // the slot just written is reloaded
               if (kk + 1 < KSTEPS) read_frag_part(cur, kk + 1, (kk + 1) & 1, i);
               if (after_barrier) {
                 const int first = (i - MI / 2) * 2;      // two A fragments per group after the barrier
