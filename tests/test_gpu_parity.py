@@ -38,15 +38,32 @@ def rel_l2(a, b):
     return np.linalg.norm(a - b) / nb if nb > 0 else np.linalg.norm(a)
 
 
+# Element-wise bound next to the norm: a relative L2 norm over a whole tensor cannot see one
+# wrong 8-wide chunk or one wrong tile-edge row of a large gradient.  Per tensor,
+# max |gpu - oracle| <= ELEM_TOL * max |oracle|.  bf16: every stored intermediate carries a
+# relative rounding of 2^-9 and about ten of them compound, with random signs, along a
+# layer's forward and backward, so an element is off by a few 2^-9 of the tensor's scale;
+# 8 * 2^-9 leaves room for the largest of 10^5..10^7 elements.  fp32: the same count of
+# roundings at 2^-24, times sqrt(K) for the fp32 accumulation over K <= 2048 terms.
+ELEM_TOL = {inp.DT_F32: 2e-5, inp.DT_BF16: 8 * 2.0 ** -9}
+
+
 def compare(w, got, ref):
+    """Worst relative L2 error over all tensors; asserts the element-wise bound on the way."""
     worst = ("", 0.0)
+    worst_elem = ("", 0.0)
     def upd(name, a, b):
-        nonlocal worst
+        nonlocal worst, worst_elem
+        a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
         assert a.shape == b.shape, name
         assert np.all(np.isfinite(a)), name
         e = rel_l2(a, b)
         if e > worst[1]:
             worst = (name, e)
+        scale = float(np.max(np.abs(b)))
+        ee = float(np.max(np.abs(a - b))) / scale if scale > 0 else float(np.max(np.abs(a)))
+        if ee > worst_elem[1]:
+            worst_elem = (name, ee)
     for s in w.stage_ids:
         for i in range(w.n_microbatches):
             if w.loss_head:
@@ -60,6 +77,8 @@ def compare(w, got, ref):
         if w.loss_head:
             for k, v in ref["grads"][s]["head"].items():
                 upd(f"G[{s}].head.{k}", got["grads"][s]["head"][k], v)
+    print("worst element-wise error / max|oracle|:", worst_elem)
+    assert worst_elem[1] <= ELEM_TOL[w.dtype], worst_elem
     return worst
 
 
@@ -164,6 +183,168 @@ def test_bf16_twins_match_oracle(name):
     print(name, "twin worst", worst, err)
     assert err <= TOL[w.dtype], (worst, err)
     st.close()
+
+
+def raw_outputs(st, w):
+    """The bits a run left behind: gradients per virtual stage, outputs, input cotangents, losses."""
+    st.sync()
+    torch.cuda.synchronize()
+    return ([st.grads_tensor(v).cpu() for v in range(len(w.stage_ids))],
+            [t.cpu().clone() for t in st.out_y], [t.cpu().clone() for t in st.out_dx],
+            st.losses() if w.loss_head else None)
+
+
+def assert_same_bits(a, b):
+    for x, y in zip(a[0], b[0]):
+        assert torch.equal(x.view(torch.int32), y.view(torch.int32))
+    for k in (1, 2):
+        for x, y in zip(a[k], b[k]):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+    if a[3] is not None:
+        assert np.array_equal(a[3], b[3])
+
+
+STREAM_MODE_CASES = {**{n: (TWINS[n], 5) for n in TWINS},
+                     **{"fp32-" + n: (None, 11) for n in FP32_VARIANTS}}
+
+
+@pytest.mark.parametrize("name", sorted(STREAM_MODE_CASES))
+def test_every_stream_mode_matches_oracle_with_identical_bits(name):
+    """jpp_set_stream_mode: the backward's input-gradient chain and weight gradients on two
+    library-owned streams (0), on one (1), or everything on the caller's compute stream (2,
+    what the large benchmark configurations run in).  Every mode against the oracle, and the
+    three modes against each other bit for bit: which stream a kernel runs on must not
+    change what it computes (Section 2.2.1: any order that honours the dependencies)."""
+    from dataclasses import replace
+    w, seed = STREAM_MODE_CASES[name]
+    if w is None:
+        w = replace(inp.C1, name=name, **FP32_VARIANTS[name[5:]])
+    if name == "C4":
+        w = replace(w, P=2, rank=0)
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec),
+                                               so.head_param_shapes(spec) if w.loss_head else None,
+                                               seed=seed, perturb=True)
+    ref, bits = None, []
+    try:
+        for mode in (0, 1, 2):
+            B.jpp_set_stream_mode(mode)
+            st = Stage(w)
+            assert B.jpp_stage_stream_mode(st.h) == mode
+            st.set_params_host(params)
+            st.bind(x, cot, tg)
+            st.zero_grads()
+            st.run()
+            got = st.results()
+            if ref is None:
+                ref = so.run_task_list(spec, params, oracle_tasks(st.tasks), x, cot, tg)
+            worst, err = compare(w, got, ref)
+            print(name, "mode", mode, "worst", worst, err)
+            assert err <= TOL[w.dtype], (mode, worst, err)
+            assert B.jpp_stage_peak_in_flight(st.h) == ref["peak_live"]
+            bits.append(raw_outputs(st, w))
+            st.close()
+    finally:
+        B.jpp_set_stream_mode(-1)
+    assert_same_bits(bits[0], bits[1])
+    assert_same_bits(bits[0], bits[2])
+
+
+# The executor configuration of the headline benchmark, at sizes the oracle can run: the
+# interleaved 1F1B list of rank 0 of 8 actors with 2 virtual stages and 32 microbatches (128
+# tasks), weight-gradient groups of 8 (groups completing across virtual stages, 40 stash
+# places with the prefetch), everything on the compute stream, and for bf16 the benchmark's
+# 256 x 256 x 64 GEMM kernel forced onto the small matrices (ragged tiles everywhere).
+BENCH_LIST = dict(sched=inp.SCHED_INTERLEAVED, P=8, rank=0, V=2, wgrad_group=8)
+BENCH_LIST_CASES = {
+    # (workload, forced GEMM variant)
+    "fp32": (inp.Workload("bench-list-fp32", inp.DT_F32, 1, 64, 2, 2, 32, 256, 24, 1, 32, cot_std=1.0, w_std=0.05,
+                          **BENCH_LIST), 0),
+    "bf16": (inp.Workload("bench-list-bf16", inp.DT_BF16, 1, 256, 2, 2, 128, 640, 72, 1, 32, **BENCH_LIST), 6),
+}
+
+
+@pytest.mark.parametrize("name", sorted(BENCH_LIST_CASES))
+def test_benchmark_task_list_and_grouping_match_oracle(name):
+    w, variant = BENCH_LIST_CASES[name]
+    assert (w.P, w.rank, w.V, w.n_microbatches, w.wgrad_group) == (inp.C4.P, inp.C4.rank, inp.C4.V,
+                                                                    inp.C4.n_microbatches, 8)
+    try:
+        B.jpp_set_stream_mode(2)
+        B.jpp_set_gemm_variant(variant)
+        st, got, ref = run_both_grouped(w, seed=31)
+        assert B.jpp_stage_stream_mode(st.h) == 2
+        assert len(st.tasks) == 128
+        worst, err = compare(w, got, ref)
+        print(name, "benchmark list worst", worst, err)
+        assert err <= TOL[w.dtype], (worst, err)
+        # 32 stash places: four groups of 8 alive at once (the validator's count), 8 more for
+        # the prefetch that opens the next group
+        assert B.jpp_schedule_validate(st.cfg, st.M, st.tasks) == 32
+        assert B.jpp_stage_peak_in_flight(st.h) == 32
+        assert st.max_in_flight == 40
+        st.close()
+    finally:
+        B.jpp_set_stream_mode(-1)
+        B.jpp_set_gemm_variant(0)
+
+
+def run_both_grouped(w, seed):
+    """run_both for a stage with weight-gradient groups: the library's stash count includes the
+    groups' hold, which the oracle (whose sums have no groups) does not model."""
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec),
+                                               so.head_param_shapes(spec) if w.loss_head else None,
+                                               seed=seed, perturb=True)
+    st = Stage(w)
+    st.set_params_host(params)
+    st.bind(x, cot, tg)
+    st.zero_grads()
+    st.run()
+    got = st.results()
+    ref = so.run_task_list(spec, params, oracle_tasks(st.tasks), x, cot, tg)
+    return st, got, ref
+
+
+@pytest.mark.parametrize("name", sorted(TWINS))
+def test_bf16_twins_on_the_large_tile_kernel_match_oracle(name):
+    """The twins again with the 256 x 256 x 64 register-staged GEMM (the kernel the
+    benchmark-sized stages use) forced onto every product, on one stream: ragged 256-tiles,
+    the tail split where the scratch allows it."""
+    from dataclasses import replace
+    w = TWINS[name]
+    if name == "C4":
+        w = replace(w, P=2, rank=0)
+    try:
+        B.jpp_set_stream_mode(2)
+        B.jpp_set_gemm_variant(6)
+        st, got, ref = run_both(w, perturb=True, seed=5)
+        worst, err = compare(w, got, ref)
+        print(name, "twin, large tiles, worst", worst, err)
+        assert err <= TOL[w.dtype], (worst, err)
+        st.close()
+    finally:
+        B.jpp_set_stream_mode(-1)
+        B.jpp_set_gemm_variant(0)
+
+
+def test_wide_twin_runs_the_benchmark_kernels_and_matches_oracle():
+    """A GPT layer wide enough that the library picks, by itself, what it picks for the
+    benchmark configurations: the 256 x 256 x 64 kernel for the feed-forward products (6 x 48 =
+    288 tiles: one full round and a tail of 32 tiles that is split along k), the square tile
+    map for the fp32-accumulating weight gradients (48 x 16 and 16 x 48 tiles), and a group of
+    two microbatches, all on one compute stream.  Compared with the oracle element by element."""
+    w = inp.Workload("wide-twin", inp.DT_BF16, 1, 4096, 2, 2, 128, 12288, 1536, 1, 2, wgrad_group=2)
+    try:
+        B.jpp_set_stream_mode(2)     # two heads only: the attention projection is too small for the automatic choice
+        st, got, ref = run_both_grouped(w, seed=41)
+        assert B.jpp_stage_stream_mode(st.h) == 2
+        worst, err = compare(w, got, ref)
+        print("wide twin worst", worst, err)
+        assert err <= TOL[w.dtype], (worst, err)
+        st.close()
+    finally:
+        B.jpp_set_stream_mode(-1)
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C5"])

@@ -370,6 +370,27 @@ def test_gelu_and_silu_values():
     assert np.allclose(so.act_forward(sw, np.array([1.0, 2.0])), [2 * 0.731058578630005], atol=1e-14)
 
 
+def test_gelu_tanh_values():
+    """The tanh form 0.5 t (1 + tanh(sqrt(2/pi) (t + 0.044715 t^3))), pinned by values that do
+    not come from this repository: at t = 1 the argument is 0.7978845608 * 1.044715 =
+    0.8335619..., tanh of it 0.6823839812, so gelu_tanh(1) = 0.8411919906; the identity
+    gelu_tanh(t) - gelu_tanh(-t) = t (tanh is odd) gives the value at -1; the library's
+    float64 implementation covers a grid, and its autograd the derivative.  A mistyped
+    0.044715 or sqrt(2/pi), or the erf form in its place (0.8413447 at 1), fails here."""
+    torch = pytest.importorskip("torch")
+    w = tiny("gelu_tanh")
+    spec = spec_of(w)
+    got = so.act_forward(spec, np.array([0.0, 1.0, -1.0]))
+    assert np.allclose(got, [0.0, 0.8411919906, 0.8411919906 - 1.0], atol=2e-10)
+    assert abs(got[1] - 0.841344746068543) > 1e-4          # not the erf form
+    t = np.linspace(-6.0, 6.0, 241)
+    tt = torch.tensor(t, dtype=torch.float64, requires_grad=True)
+    lib = torch.nn.functional.gelu(tt, approximate="tanh")
+    assert np.allclose(so.act_forward(spec, t), lib.detach().numpy(), atol=1e-14)
+    lib.sum().backward()
+    assert np.allclose(so.act_backward(spec, t, np.ones_like(t)), tt.grad.numpy(), atol=1e-13)
+
+
 def test_cross_entropy_closed_forms():
     w = tiny("head", vocab=50304 // 64)            # 786
     spec, params, x, _, tg = draw(w, perturb=False)
