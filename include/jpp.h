@@ -370,6 +370,21 @@ jpp_status jpp_op_attention_bwd_ws(int dtype, int mb, int seq, int Hq, int Hkv, 
                                    const void* dout, void* dqkv, float* delta, void* scratch,
                                    size_t scratch_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): jpp_op_attention_bwd without the `delta` argument.
+ * The fp32 scratch [mb, Hq, seq] lives in a device array that is part of the library itself
+ * (JPP_STATIC_SCRATCH_BYTES per GPU, held from the moment the library is loaded on that GPU to
+ * the end of the process); the call allocates and frees nothing, on the device or through any
+ * library.  JPP_EINVAL, with nothing launched, when 4 * mb * Hq * seq exceeds
+ * JPP_STATIC_SCRATCH_BYTES.  dqkv gets the bits that jpp_op_attention_bwd writes.  All calls
+ * on one GPU share the one array (each call overwrites what it reads, nothing has to be
+ * cleared): calls that may overlap on a GPU (different streams, different threads) race on it
+ * and must be serialised by the caller. */
+#define JPP_STATIC_SCRATCH_BYTES (4u << 20)
+jpp_status jpp_op_attention_bwd_static(int dtype, int mb, int seq, int Hq, int Hkv, int hd,
+                                       const void* qkv, const void* out, const float* lse,
+                                       const void* dout, void* dqkv, void* stream);
+
 /* Norm over the last axis of x [rows, d].  stats: fp32 [2*rows] (mean, rstd; mean = 0 for
  * RMSNorm).  beta may be NULL (RMSNorm). */
 jpp_status jpp_op_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x,

@@ -100,6 +100,7 @@ _SIGNATURES = {
     "jpp_op_cross_entropy": (C.c_int, [C.c_int] * 3 + [C.c_void_p] * 6),
     "jpp_op_attention_bwd_scratch_bytes": (C.c_size_t, [C.c_int] * 6),
     "jpp_op_attention_bwd_ws": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
+    "jpp_op_attention_bwd_static": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 6),
     "jpp_op_embed_fwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
     "jpp_op_embed_bwd": (C.c_int, [C.c_int] * 4 + [C.c_void_p] * 4),
 }
@@ -404,6 +405,13 @@ def jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dq
                             stream):
     _check(lib().jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, scratch,
                                          scratch_bytes, stream))
+
+
+JPP_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def jpp_op_attention_bwd_static(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, stream):
+    _check(lib().jpp_op_attention_bwd_static(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, stream))
 
 
 def jpp_op_cross_entropy(dtype, rows, vocab, z, targets, dz, row_loss, loss, stream):

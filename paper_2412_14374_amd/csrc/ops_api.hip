@@ -1,12 +1,43 @@
 // C entry points for single operations (see include/jpp.h): argument checks, then the same
 // launchers the stage executor uses.
+#include <mutex>
+
 #include "internal.h"
 
 using namespace jpp;
 
+// Scratch of jpp_op_attention_bwd_static, the entry point for callers that cannot allocate:
+// JPP_STATIC_SCRATCH_BYTES of device memory that exist in every GPU the library is loaded on
+// from load time to the end of the process.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address kernels are given is the one looked up per device below.
+static __device__ __align__(256) float scratch[JPP_STATIC_SCRATCH_BYTES / sizeof(float)];
+
 namespace {
 bool dtype_ok(int dtype) { return dtype == JPP_F32 || dtype == JPP_BF16; }
 int chunk_of(int dtype) { return dtype == JPP_BF16 ? 8 : 4; }
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU
+// holds its own copy of the array at its own address).  No allocation.
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+jpp_status static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(JPP_EDEVICE, "device index beyond the static scratch table");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+    if (!p) return fail(JPP_EDEVICE, "hipGetSymbolAddress returned a null address for the static scratch");
+    g_scratch_ptr[dev] = (float*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return JPP_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -94,6 +125,24 @@ jpp_status jpp_op_attention_bwd_ws(int dtype, int mb, int seq, int Hq, int Hkv, 
                      ? launch_attention_bwd_mfma(a, (hipStream_t)stream)
                      : launch_attention_bwd_generic(dtype, a, (hipStream_t)stream);
   return e == hipSuccess ? JPP_OK : fail_hip(e, "attention backward launch");
+}
+
+jpp_status jpp_op_attention_bwd_static(int dtype, int mb, int seq, int Hq, int Hkv, int hd, const void* qkv,
+                                       const void* out, const float* lse, const void* dout, void* dqkv,
+                                       void* stream) {
+  jpp_status rc = attn_check(dtype, mb, seq, Hq, Hkv, hd);
+  if (rc != JPP_OK) return rc;
+  // delta holds one float per (batch, query head, position)
+  const unsigned long long need = 4ull * (unsigned long long)mb * (unsigned long long)Hq * (unsigned long long)seq;
+  if (need > JPP_STATIC_SCRATCH_BYTES)
+    return fail(JPP_EINVAL, "jpp_op_attention_bwd_static: mb * Hq * seq = " +
+                                std::to_string((unsigned long long)mb * Hq * seq) + " exceeds the static scratch of " +
+                                std::to_string(JPP_STATIC_SCRATCH_BYTES / 4) + " floats; use jpp_op_attention_bwd");
+  float* delta = nullptr;
+  rc = static_scratch(&delta);
+  if (rc != JPP_OK) return rc;
+  // every element of delta that the kernels read is written first by the same call: nothing to clear
+  return jpp_op_attention_bwd_ws(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, dout, dqkv, delta, nullptr, 0, stream);
 }
 
 jpp_status jpp_op_norm_fwd(int dtype, int norm, int rows, int d, float eps, const void* x, const void* gamma,
