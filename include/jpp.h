@@ -155,7 +155,9 @@ size_t jpp_stage_param_count(const jpp_stage* st); /* elements per virtual stage
  * a host or a device pointer (src_on_device).  Synchronous. */
 jpp_status jpp_stage_set_params(jpp_stage* st, int vstage, const void* src, int src_on_device);
 
-/* Boundary buffers, caller-owned, all device pointers to [microbatch, seq_len, d_model]
+/* Section 4.2: a stage receives its input activation from the previous stage and its output's
+ * cotangent from the next one, and sends its output and its input's cotangent the other way; on
+ * one GPU the peers are buffers.  Boundary buffers, caller-owned, all device pointers to [microbatch, seq_len, d_model]
  * tensors of the storage dtype; each host array has n_virtual * M entries indexed
  * [vstage * M + i].  inbox_x[i]: activation received for FWD(i); inbox_cot[i]: cotangent
  * received for BWD(i) and outbox_y[i]: output sent after FWD(i) (entries of the virtual
@@ -169,7 +171,9 @@ jpp_status jpp_stage_bind_boundary(jpp_stage* st, const void* const* inbox_x,
                                    const void* const* inbox_cot, void* const* outbox_y,
                                    void* const* outbox_dx, const int32_t* const* targets);
 
-/* grads <- 0 and losses <- 0 for all virtual stages, enqueued on `stream`. */
+/* Section 3.1: the accumulation loop starts from zero gradients (`grads = 0`, then every
+ * backward adds its microbatch's share).  grads <- 0 and losses <- 0 for all virtual stages,
+ * enqueued on `stream`. */
 jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream);
 
 /* Executes the task list (host array, read during the call only) in the order given:
@@ -191,7 +195,8 @@ jpp_status jpp_stage_zero_grads(jpp_stage* st, void* stream);
 jpp_status jpp_stage_run(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* compute_stream,
                          void* side_stream);
 
-/* Synchronises the streams of the last run and returns a borrowed device pointer to the
+/* Section 3.1: what the accumulation loop returns, the gradients summed over the microbatches
+ * (no 1/M).  Synchronises the streams of the last run and returns a borrowed device pointer to the
  * flat fp32 gradient buffer of local virtual stage `vstage` (param_count elements, same
  * offsets as the parameters).  Valid until zero_grads / destroy. */
 jpp_status jpp_stage_grads(jpp_stage* st, int vstage, const float** grads_dev, size_t* n_elems);
@@ -249,7 +254,6 @@ int jpp_stage_stream_mode(const jpp_stage* st);
 int jpp_stage_peak_in_flight(const jpp_stage* st);   /* stash slots high-water mark            */
 int jpp_stage_pending_peak(const jpp_stage* st);     /* pending-deletion queue high-water mark */
 int jpp_stage_prefetched(const jpp_stage* st);       /* receives issued ahead of their consumer */
-int jpp_stage_host_syncs(const jpp_stage* st);       /* host-side waits inside the last run (0) */
 
 const char* jpp_last_error(void);
 

@@ -79,7 +79,6 @@ _SIGNATURES = {
     "jpp_stage_peak_in_flight": (C.c_int, [C.c_void_p]),
     "jpp_stage_pending_peak": (C.c_int, [C.c_void_p]),
     "jpp_stage_prefetched": (C.c_int, [C.c_void_p]),
-    "jpp_stage_host_syncs": (C.c_int, [C.c_void_p]),
     "jpp_last_error": (C.c_char_p, []),
     "jpp_set_gemm_variant": (None, [C.c_int]),
     "jpp_set_stream_mode": (None, [C.c_int]),
@@ -335,10 +334,6 @@ def jpp_stage_pending_peak(h):
 
 def jpp_stage_prefetched(h):
     return lib().jpp_stage_prefetched(h)
-
-
-def jpp_stage_host_syncs(h):
-    return lib().jpp_stage_host_syncs(h)
 
 
 def jpp_set_stream_mode(mode):

@@ -263,7 +263,7 @@ jpp_status jpp_pipeline_run(jpp_pipeline* p, const jpp_task* const* task_lists, 
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     HIP_TRY(hipStreamIsCapturing((hipStream_t)compute_streams[r], &cap));
     if (cap != hipStreamCaptureStatusNone)
-      return fail(JPP_ESTATE, "jpp_pipeline_run cannot be recorded into a HIP graph (jpp_stage_run can)");
+      return fail(JPP_ESTATE, "jpp_pipeline_run cannot be recorded into a HIP graph");
   }
   // everything that can be refused is checked before anything is enqueued
   for (int r = 0; r < P; ++r) {

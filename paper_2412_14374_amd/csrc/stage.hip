@@ -549,9 +549,8 @@ jpp_status jpp_stage_create(const jpp_layer_config* cfg, int n_microbatches, int
   for (auto& t : st->cot) { mk(t.freed); mk(t.rx); }
   mk(st->end_compute); mk(st->end_side); mk(st->run_start); mk(st->b2w); mk(st->w_layer); mk(st->w_task);
   mk(st->b_end); mk(st->w_end);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->bs_own, hipStreamNonBlocking);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->ws_own, hipStreamNonBlocking);
-  st->bs = st->bs_own; st->ws = st->ws_own;
+  // the two library-owned streams are created by the first run that uses them (stream modes
+  // 0 and 1): a stage that computes on the caller's stream alone takes no hardware queue
   if (e == hipSuccess && cfg->rope) {
     e = launch_rope_table(st->rope_table, cfg->seq_len, cfg->head_dim, cfg->rope_theta, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -684,6 +683,8 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
   st->cs = cs; st->ss = ss;
   // which streams carry the backward (benchmarking knob; the default is three-way overlap)
   const int mode = jpp_stage_stream_mode(st);
+  if (mode != 2 && !st->bs_own) HIP_TRY(hipStreamCreateWithFlags(&st->bs_own, hipStreamNonBlocking));
+  if (mode == 0 && !st->ws_own) HIP_TRY(hipStreamCreateWithFlags(&st->ws_own, hipStreamNonBlocking));
   st->bs = mode == 2 ? cs : st->bs_own;
   st->ws = mode == 2 ? cs : (mode == 1 ? st->bs_own : st->ws_own);
   // the internal streams start after everything already queued on the compute stream
@@ -693,7 +694,7 @@ jpp_status run_begin(jpp_stage* st, const jpp_task* tasks, int n_tasks, void* co
   HIP_TRY(hipStreamWaitEvent(st->ws, st->run_start.ev, 0));
   HIP_TRY(hipStreamWaitEvent(ss, st->run_start.ev, 0));
   st->w_task.recorded = false;
-  st->peak_in_flight = 0; st->pending_peak = 0; st->prefetched = 0; st->host_syncs = 0;
+  st->peak_in_flight = 0; st->pending_peak = 0; st->prefetched = 0;
   st->free_slots.clear();
   for (int k = (int)st->slots.size() / st->G - 1; k >= 0; --k) st->free_slots.push_back(k);
   st->grp_slot.assign((size_t)st->cfg.n_virtual * st->n_groups(), -1);
@@ -964,6 +965,5 @@ int jpp_stage_stream_mode(const jpp_stage* st) {
 int jpp_stage_peak_in_flight(const jpp_stage* st) { return st ? st->peak_in_flight : -1; }
 int jpp_stage_pending_peak(const jpp_stage* st) { return st ? st->pending_peak : -1; }
 int jpp_stage_prefetched(const jpp_stage* st) { return st ? st->prefetched : -1; }
-int jpp_stage_host_syncs(const jpp_stage* st) { return st ? st->host_syncs : -1; }
 
 }  // extern "C"

@@ -140,7 +140,7 @@ struct jpp_stage {
   hipStream_t bs = nullptr, ws = nullptr;   // backward chain, weight-gradient GEMMs: chosen per run, see jpp_set_stream_mode
   hipStream_t bs_own = nullptr, ws_own = nullptr;   // the two library-owned streams
   Event end_compute, end_side, run_start, b2w, w_layer, w_task, b_end, w_end;
-  int peak_in_flight = 0, pending_peak = 0, prefetched = 0, host_syncs = 0;
+  int peak_in_flight = 0, pending_peak = 0, prefetched = 0;
   std::vector<int> free_slots;      // free group slots
   std::vector<int> grp_slot, grp_fwd, grp_bwd;  // per (v, group): its group slot (-1: none), forwards / backwards enqueued
   std::vector<int> tx_free;

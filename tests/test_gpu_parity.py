@@ -45,11 +45,12 @@ def rel_l2(a, b):
 # branch adds about five more stored tensors, whose errors add with random signs, so the
 # error of an element grows like sqrt(layers) * a few 2^-9 of the tensor's scale, and the
 # largest of 10^5..10^7 elements lies four to five standard deviations out: 6 * 2^-9 *
-# sqrt(layers) (measured: 0.0066-0.0085 with one layer, 0.008-0.0126 with two, 0.014 with
+# sqrt(layers), and never below 8 * 2^-9 (tensors of a handful of elements, whose largest
+# value is no outlier, reach 0.0125) (measured: 0.0066-0.0085 with one layer, 0.008-0.0126 with two, 0.014 with
 # four; a wrong chunk or row is off by the tensor's own scale, two orders above).  fp32: the
 # same count at 2^-24 times sqrt(K) for the accumulation over K <= 2048 terms (measured: up to 2e-6).
 def elem_tol(w):
-    return 2e-5 if w.dtype == inp.DT_F32 else 6 * 2.0 ** -9 * float(np.sqrt(w.n_layers))
+    return 2e-5 if w.dtype == inp.DT_F32 else max(8.0, 6.0 * float(np.sqrt(w.n_layers))) * 2.0 ** -9
 
 
 def compare(w, got, ref):
@@ -510,7 +511,6 @@ def test_executor_bookkeeping_and_errors():
     st.run()
     st.sync()
     assert B.jpp_stage_peak_in_flight(st.h) == 3            # min(P - rank, M)
-    assert B.jpp_stage_host_syncs(st.h) == 0
     # every receive except the very first is issued ahead of its consumer when a slot is spare
     assert B.jpp_stage_prefetched(st.h) == 2 * w.n_microbatches - 1
     assert 0 <= B.jpp_stage_pending_peak(st.h) <= 3
@@ -541,6 +541,51 @@ def test_executor_bookkeeping_and_errors():
     assert err <= 1e-5, (worst, err)
     assert B.jpp_stage_prefetched(st2.h) < 2 * w.n_microbatches - 1
     st2.close()
+
+
+def test_run_returns_while_earlier_work_is_still_executing():
+    """Section 4.4: the whole task list is dispatched in one call with no host round trip.  The
+    compute stream is first given about a tenth of a second of unrelated work (large GEMMs
+    through the same library), then the stage's step is enqueued behind it: zero_grads and all
+    the tasks of a 1F1B list, on all the streams a run uses.  When jpp_stage_run returns, the
+    event recorded in front of it must still be pending: a host-side wait for the stream, for
+    an event of this run or for the device anywhere inside the run would have outlasted it."""
+    from dataclasses import replace
+    w = replace(inp.C1, sched=inp.SCHED_1F1B, P=4, rank=1, n_microbatches=8)
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec), None)
+    n = 8192
+    a = torch.randn((n, n), device="cuda:0").to(torch.bfloat16)
+    b = torch.randn((n, n), device="cuda:0").to(torch.bfloat16)
+    c = torch.zeros((n, n), dtype=torch.bfloat16, device="cuda:0")
+    try:
+        for mode in (0, 2):
+            B.jpp_set_stream_mode(mode)
+            st = Stage(w)
+            st.set_params_host(params)
+            st.bind(x, cot, tg)
+            st.zero_grads()
+            st.run()                # first run: creates the library's streams, loads the kernels
+            st.sync()
+            torch.cuda.synchronize()
+            cs = st.compute.cuda_stream
+            for _ in range(100):    # 100 x 1.1 TFLOP: about 0.1 s on the compute stream
+                B.jpp_op_gemm(B.JPP_BF16, n, n, n, a.data_ptr(), n, 0, b.data_ptr(), n, 0, c.data_ptr(), n,
+                              B.OUT_STORE, None, None, cs)
+            before = torch.cuda.Event()
+            before.record(st.compute)
+            st.zero_grads()
+            st.run()
+            still_busy = not before.query()
+            st.sync()
+            assert still_busy, f"stream mode {mode}: jpp_stage_run came back only after the work queued before it"
+            got = st.results()
+            ref = so.run_task_list(spec, params, oracle_tasks(st.tasks), x, cot, tg)
+            worst, err = compare(w, got, ref)
+            assert err <= TOL[w.dtype], (worst, err)
+            st.close()
+    finally:
+        B.jpp_set_stream_mode(-1)
 
 
 def test_full_size_two_microbatches_equal_one_of_twice_the_size():

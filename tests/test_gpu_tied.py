@@ -118,8 +118,6 @@ def test_tied_pipeline_matches_oracle(name):
     # fp32 partial sums added once: exactly the fp32 sum of what was there before
     want = (got["grads"][0]["embed"]["w"].astype(np.float32) + got["grads"][S - 1]["head"]["w_head"].astype(np.float32))
     assert np.array_equal(a.astype(np.float32), want)
-    for act in pipe.actors:
-        assert B.jpp_stage_host_syncs(act.h) == 0
     pipe.close()
 
 
