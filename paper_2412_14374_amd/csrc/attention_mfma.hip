@@ -17,8 +17,21 @@
 //  * the per-row rescale of the output accumulator is a per-lane scalar multiply.
 // The k index of an MFMA may be permuted freely as long as both operands agree; the B
 // operand taken from an accumulator holds, per 16 keys, keys {0-3, 8-11} in lanes 0-31 and
-// {4-7, 12-15} in lanes 32-63, so transposed operand tiles are stored in LDS with that
-// order inside each group of 16 and are read with one 16-byte load per lane.
+// {4-7, 12-15} in lanes 32-63.
+//
+// Tiles.  Every operand tile (64 rows of one head: K, V, Q or dO) is staged ONCE, as it lies in
+// memory ([row][128 d], 256 bytes per row), by HBM -> LDS direct loads into one of two tile
+// sets: the next step's tiles arrive while the current step is multiplied, no register and no
+// second pass over the tile is spent on staging, and a step has one barrier.  The two operand
+// shapes an MFMA wants are both read from that one tile:
+//  * rows along the MFMA's M index (S = Q K^T, dP = dO V^T): one 16-byte read per lane;
+//  * the head dimension along M (O^T += V^T P^T, dV^T += dO^T P, dK^T += Q^T dS, dQ^T += K^T dS^T):
+//    two transposing reads per lane (ds_read_b64_tr_b16: lane i of a 16-lane group receives
+//    element (i & 3) of the 8-byte runs that lanes 4j + (i >> 2), j = 0..3, address), each
+//    returning 4 consecutive tile rows for the lane's d, which is the key order above.
+// The 16-byte chunk c of row r is stored at chunk c ^ swz16(r): 16 consecutive rows reading
+// one logical chunk (first shape) hit 16 different bank quads, and the 4 rows x 64 bytes that
+// 32 lanes read together in the second shape go to four different 64-byte bank groups.
 //
 // Determinism: the backward uses two kernels (one owns dK/dV rows, one owns dQ rows);
 // nothing is accumulated with atomics.
@@ -31,20 +44,17 @@ namespace {
 
 constexpr int HD = 128;
 constexpr int kThreads = 256;
-constexpr uint32_t kOOB = 0x7FFFFFFFu;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_t;
 
-constexpr int kTileBytes = 64 * HD * 2;
-constexpr f32x16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // a 64-row tile of one head: 16 KiB in either layout
+constexpr int kTileBytes = 64 * HD * 2;   // a 64-row tile of one head: 16 KiB
+constexpr f32x16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, long long bytes) {
-  const uint32_t n = bytes > 0x7FFFFF00LL ? 0x7FFFFF00u : (bytes < 0 ? 0u : (uint32_t)bytes);
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)n, 0x00020000);
-}
-
-__device__ inline int swz7(int row) { return (row ^ (row >> 3)) & 7; }
+// chunk swizzle of a tile row: bits 0-1 of the row go to bits 2-3 of the chunk index, bits 2-3
+// to bits 0-1 (a bijection of 0..15 for 16 consecutive rows)
+__device__ inline int swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
 // 2^x by the hardware instruction alone (arguments here are <= 0 or masked; results below the
 // normal range flush to zero, which is what the sums want).  The library exp2f wraps the same
@@ -52,80 +62,109 @@ __device__ inline int swz7(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- tile staging ------------------------------------------------------------------------
-// "Row" tile: [64 rows][128 d], 256 bytes per row (one line of the 64 x 4-byte LDS banks), 16-byte
-// chunk c stored at c ^ (row & 15): 16 consecutive rows reading the same logical chunk hit 16
-// different bank quads.
-// Filled HBM -> LDS directly: each wave instruction fills 4 rows (1 KiB) in lane order.
-// `base` points at (row 0, d 0) of the tile in global memory, `ld` is the row pitch in
-// elements, rows >= valid read as zero.
-__device__ inline void load_row_tile(char* tile, const bf16* base, int ld, int valid, long long bytes_left) {
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
-  const auto rs = make_rsrc(base, bytes_left);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int blk = wave * 4 + i;               // 4-row block index, 16 per tile
-    const int row = blk * 4 + (lane >> 4);
-    const int c = (lane & 15) ^ (row & 15);
-    const uint32_t off = row < valid ? (uint32_t)(row * ld + c * 8) * 2u : kOOB;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + blk * 1024), 16, (int)off, 0, 0, 0);
-  }
+// Raw buffer descriptor (base, stride 0, num_records = bytes, untyped 32-bit format) in scalar
+// registers, for the HBM -> LDS loads below.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ inline i32x4 make_rsrc_s(const void* p, long long bytes) {
+  const uint32_t n = bytes > 0x7FFFFF00LL ? 0x7FFFFF00u : (bytes < 0 ? 0u : (uint32_t)bytes);
+  const unsigned long long a = (unsigned long long)p;
+  i32x4 r;
+  r[0] = (int)(uint32_t)a;
+  r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
+  r[2] = (int)n;
+  r[3] = 0x00020000;
+  return r;
+}
+// 16 bytes per lane, HBM -> LDS without passing through registers: the wave's 64 lanes fill the
+// 1 KiB at LDS byte address `lds_addr` in lane order; lanes whose byte offset `voff` is outside
+// the descriptor's range store zeros.  Inline assembly on purpose: the compiler's wait-count
+// pass makes every LDS read that follows such a load wait for ALL loads in flight (it cannot
+// tell the tile set being filled from the one being read), which would put the whole memory
+// latency back in front of every step.  The one wait a step needs is in step_barrier().
+__device__ inline void dma16(const i32x4& rsrc, uint32_t lds_addr, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rsrc)
+               : "memory", "m0");
+}
+__device__ inline uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(size_t)(__attribute__((address_space(3))) const char*)p;
+}
+// The barrier between two steps: this wave's loads into LDS have landed and its LDS writes are
+// done (the counters), then every wave's (the barrier).  Also a compiler-level memory barrier.
+__device__ inline void step_barrier() {
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// "Transposed" tile: [128 d][64 rows], 128 bytes per d, rows permuted inside each group of 16
-// (bits 2 and 3 of the row index swapped), 16-byte chunk c stored at c ^ swz7(d).
-// A thread loads 4 rows x 8 d (four 16-byte loads) into registers; from there the block is
-// written as four 16-byte chunks of a row tile (store_rows) or, transposed in registers, as
-// eight 8-byte runs of 4 rows of a transposed tile (store).  Issuing the loads of the next
-// tile before the current one is multiplied hides the memory latency behind the MFMAs.
-struct TransposedStage {
-  u32x4 regs[4];
-  __device__ inline void issue(const bf16* base, int ld, int valid, long long bytes_left) {
-    const auto rs = make_rsrc(base, bytes_left);
-    const int db = threadIdx.x & 15, rg = threadIdx.x >> 4;  // d block (8 wide), row group (4 rows)
+// Makes the compiler wait HERE for the load that produces `v` (an empty statement that reads
+// it).  Used on the fragments fetched before a step loop: a load still pending at the loop's
+// entry would otherwise be waited for with vmcnt(0) at its first use inside the loop, in every
+// iteration, and that wait would also cover the HBM -> LDS loads issued just before it.
+__device__ inline void settle(const bf16x8& v) { asm volatile("" ::"v"(v)); }
+__device__ inline void settle(float v) { asm volatile("" ::"v"(v)); }
+// Keeps an accumulator tile in the accumulation half of the register file at this point.
+__device__ inline void pin_agpr(f32x16& v) { asm volatile("" : "+a"(v)); }
+
+// Fills tiles HBM -> LDS: each wave instruction fills 4 rows (1 KiB) of the tile in lane order,
+// so the swizzle is applied to WHICH chunk of the row a lane fetches.  The per-lane byte
+// offsets depend only on the row pitch and are computed once; a tile then costs a few scalar
+// instructions (its descriptor) and four loads per thread, in flight until the next
+// step_barrier().  Rows at and beyond `valid` read as zero: the descriptor ends with row
+// valid - 1, and the hardware returns zero beyond a descriptor's range.
+struct TileLoader {
+  uint32_t voff[4];
+  int ld;
+  __device__ inline void init(int ld_elems) {
+    ld = ld_elems;
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int row = rg * 4 + j;
-      const uint32_t off = row < valid ? (uint32_t)(row * ld + db * 8) * 2u : kOOB;
-      regs[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+    for (int i = 0; i < 4; ++i) {
+      const int row = (wave * 4 + i) * 4 + (lane >> 4);
+      const int c = (lane & 15) ^ swz16(row);
+      voff[i] = (uint32_t)(row * ld + c * 8) * 2u;
     }
   }
-  __device__ inline void store_rows(char* tile) const {
-    const int db = threadIdx.x & 15, rg = threadIdx.x >> 4;
+  // `base`: (row 0, d 0) of the tile in global memory; 1 <= valid rows (more than 64 count as 64)
+  __device__ inline void issue(char* tile, const bf16* base, int valid) const {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int rows = valid < 64 ? valid : 64;
+    const i32x4 rs = make_rsrc_s(base, ((long long)(rows - 1) * ld + HD) * 2);
+    const uint32_t t0 = lds_addr_of(tile) + wave * 4096;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int row = rg * 4 + j;
-      *reinterpret_cast<u32x4*>(tile + row * 256 + ((db ^ (row & 15)) << 4)) = regs[j];
-    }
-  }
-  __device__ inline void store(char* tile) const {
-    const int db = threadIdx.x & 15, rg = threadIdx.x >> 4;
-    const int o16 = (rg & 3) * 4;                               // row offset inside its group of 16
-    const int pos16 = (o16 & 3) | ((o16 & 8) >> 1) | ((o16 & 4) << 1);
-    const int chunk = (rg >> 2) * 2 + (pos16 >> 3);
-    const int half8 = (pos16 >> 2) & 1;
-#pragma unroll
-    for (int dd = 0; dd < 8; ++dd) {
-      const int w = dd >> 1;
-      const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-      u32x2 v;
-      v[0] = __builtin_amdgcn_perm(regs[1][w], regs[0][w], sel);
-      v[1] = __builtin_amdgcn_perm(regs[3][w], regs[2][w], sel);
-      const int d = db * 8 + dd;
-      *reinterpret_cast<u32x2*>(tile + d * 128 + ((chunk ^ swz7(d)) << 4) + half8 * 8) = v;
-    }
+    for (int i = 0; i < 4; ++i) dma16(rs, t0 + i * 1024, voff[i]);
   }
 };
 
-// A operand from a row tile: rows mt*32 + l32, k = d chunk (2*kd + half).
+// A operand with tile rows along M: rows mt*32 + l32, k = d chunk (2*kd + half).
 __device__ inline bf16x8 row_frag(const char* tile, int mt, int kd, int l32, int half) {
   const int row = mt * 32 + l32;
-  return *reinterpret_cast<const bf16x8*>(tile + row * 256 + (((kd * 2 + half) ^ (row & 15)) << 4));
+  return *reinterpret_cast<const bf16x8*>(tile + row * 256 + (((kd * 2 + half) ^ swz16(row)) << 4));
 }
-// A operand from a transposed tile: rows (d) dt*32 + l32, k = the 16 tile-rows of step s in
-// the permuted order described above.
-__device__ inline bf16x8 trans_frag(const char* tile, int dt, int s, int l32, int half) {
-  const int d = dt * 32 + l32;
-  return *reinterpret_cast<const bf16x8*>(tile + d * 128 + (((s * 2 + half) ^ swz7(d)) << 4));
+
+// A operand with the head dimension along M, read from the same tile by transposing reads.
+// For lane (l32, half), M row d = 32 dt + l32 and k-step s (16 tile rows) the operand holds
+// tile rows 16 s + 4 half + 0..3 and 16 s + 8 + 4 half + 0..3 (the order of an accumulator
+// used as B operand).  The lane ADDRESSES, per read, the 8-byte run (tile row 16 s + 4 half
+// [+ 8] + (r >> 2), d = 32 dt + (l32 & 16) + 4 (r & 3) .. + 3), r = l32 & 15.
+// TransOffsets holds the byte offsets of those runs for s = 0 (a step of s adds 16 rows).
+struct TransOffsets { int lo[4], hi[4]; };
+__device__ inline TransOffsets trans_offsets(int l32, int half) {
+  TransOffsets o;
+  const int r = l32 & 15;
+  const int row_lo = 4 * half + (r >> 2), row_hi = row_lo + 8;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    const int d = 32 * dt + (l32 & 16) + 4 * (r & 3);
+    o.lo[dt] = row_lo * 256 + (((d >> 3) ^ swz16(row_lo)) << 4) + (d & 4) * 2;
+    o.hi[dt] = row_hi * 256 + (((d >> 3) ^ swz16(row_hi)) << 4) + (d & 4) * 2;
+  }
+  return o;
+}
+__device__ inline bf16x8 trans_frag(const char* tile, const TransOffsets& o, int dt, int s) {
+  const char* p = tile + s * (16 * 256);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(p + o.lo[dt]));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t)(p + o.hi[dt]));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
 }
 // B operand straight from global memory: row `row` (zero if not valid), d = 16*kd + 8*half ..
 __device__ inline bf16x8 global_frag(const bf16* base, int ld, int row, bool valid, int kd, int half) {
@@ -145,13 +184,13 @@ __device__ inline bf16x8 acc_frag(const f32x16& a, int s2) {
 
 // ---- forward -------------------------------------------------------------------------------
 // One workgroup: 128 queries of one (b, h); wave w owns queries [32w, 32w+32).  KV tiles of 64.
+//   S^T = K Q^T (A = K rows from LDS, B = Q fragments in registers), online softmax along the
+//   lanes, O^T += V^T P^T (A = V read transposed from LDS, B = P from the accumulator registers).
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv,
                                                                  bf16* __restrict__ out,
                                                                  float* __restrict__ lse, int seq, int Hq,
-                                                                 int Hkv, long long total_bytes) {
-  __shared__ __attribute__((aligned(1024))) char lds[2 * kTileBytes];
-  char* k_tile = lds;
-  char* vt_tile = lds + kTileBytes;
+                                                                 int Hkv) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];   // two sets of (K, V)
   // Heaviest blocks first over the whole launch (a late query block visits the most key
   // tiles): the block index is the slow grid dimension, (head, batch) the fast one, so the
   // launch ends with its shortest workgroups instead of a few long ones.
@@ -166,11 +205,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* 
   const bf16* kbase = qkv + tok0 * ld + (size_t)(Hq + g) * HD;
   const bf16* vbase = kbase + (size_t)Hkv * HD;
   const float sl2 = rsqrtf((float)HD) * kLog2e;
+  const TransOffsets to = trans_offsets(l32, half);
 
   bf16x8 qf[8];
   const int qrow = qw0 + l32;
 #pragma unroll
   for (int kd = 0; kd < 8; ++kd) qf[kd] = global_frag(qbase, ld, qrow, qrow < seq, kd, half);
+#pragma unroll
+  for (int kd = 0; kd < 8; ++kd) settle(qf[kd]);
 
   f32x16 o[4];
 #pragma unroll
@@ -181,30 +223,46 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* 
 
   const int q_end = min(q0 + 128, seq);      // keys needed: 0 .. q_end-1
   const int n_tiles = (q_end + 63) / 64;
-  TransposedStage ks, vs;
-  auto fetch = [&](int t) {
+  TileLoader loader;
+  loader.init(ld);
+  auto issue = [&](int t) {
     const int kv0 = t * 64;
-    const long long left_k = total_bytes - (long long)((kbase + (size_t)kv0 * ld) - qkv) * 2;
-    ks.issue(kbase + (size_t)kv0 * ld, ld, seq - kv0, left_k);
-    vs.issue(vbase + (size_t)kv0 * ld, ld, seq - kv0, left_k - (long long)Hkv * HD * 2);
+    char* set = lds + (t & 1) * (2 * kTileBytes);
+    loader.issue(set, kbase + (size_t)kv0 * ld, seq - kv0);
+    loader.issue(set + kTileBytes, vbase + (size_t)kv0 * ld, seq - kv0);
   };
-  fetch(0);
+  issue(0);
   for (int t = 0; t < n_tiles; ++t) {
     const int kv0 = t * 64;
-    __syncthreads();                          // every wave is done with the previous tile
-    ks.store_rows(k_tile);
-    vs.store(vt_tile);
-    __syncthreads();
-    if (t + 1 < n_tiles) fetch(t + 1);        // in flight while this tile is multiplied
+    // tile t has landed for every wave, and every wave is done with tile t-1, whose set the
+    // loads issued next overwrite while this tile is multiplied
+    step_barrier();
+    if (t + 1 < n_tiles) issue(t + 1);
+    const char* k_tile = lds + (t & 1) * (2 * kTileBytes);
+    const char* v_tile = k_tile + kTileBytes;
     if (kv0 > qw0 + 31) continue;             // every key of this tile is in this wave's future
+    // Every MFMA multiplies a fragment requested from LDS kAhead MFMAs earlier (a ring of
+    // kAhead + 1 fragments); scheduling barriers keep the requests in front.
+    constexpr int kAhead = 4, kRing = kAhead + 1;
+    bf16x8 ring[kRing];
     f32x16 s[2];
+    {
+      // S^T of the tile's two key halves, their k-steps interleaved: item n = (k-step n / 2, half n % 2)
+      auto frag = [&](int n) { return row_frag(k_tile, n & 1, n >> 1, l32, half); };
 #pragma unroll
-    for (int i = 0; i < 2; ++i) s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, 0, l32, half), qf[0], kZero16, 0, 0, 0);
+      for (int n = 0; n < kAhead; ++n) ring[n] = frag(n);
 #pragma unroll
-    for (int kd = 1; kd < 8; ++kd)
+      for (int n = 0; n < 16; ++n) {
+        if (n + kAhead < 16) ring[(n + kAhead) % kRing] = frag(n + kAhead);
+        __builtin_amdgcn_sched_barrier(0);
+        s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[n % kRing], qf[n >> 1], n < 2 ? kZero16 : s[n & 1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // the first transposed V fragments: requested now, they arrive during the softmax
+    auto tfrag = [&](int m) { return trans_frag(v_tile, to, m & 3, m >> 2); };
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, kd, l32, half), qf[kd], s[i], 0, 0, 0);
+    for (int m = 0; m < kAhead; ++m) ring[m] = tfrag(m);
     // s[i][r] = q(qw0 + l32) . k(kv0 + 32 i + 8 (r/4) + 4 half + r%4), unscaled
     if (kv0 + 63 > qw0) {                     // only tiles that cross the diagonal need the mask
 #pragma unroll
@@ -241,12 +299,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* 
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
     }
+    bf16x8 pf[4];
 #pragma unroll
-    for (int sk = 0; sk < 4; ++sk) {
-      const bf16x8 pf = acc_frag(s[sk >> 1], sk & 1);
+    for (int sk = 0; sk < 4; ++sk) pf[sk] = acc_frag(s[sk >> 1], sk & 1);
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trans_frag(vt_tile, dt, sk, l32, half), pf, o[dt], 0, 0, 0);
+    for (int m = 0; m < 16; ++m) {             // item m = (k-step m / 4, d block m % 4)
+      if (m + kAhead < 16) ring[(m + kAhead) % kRing] = tfrag(m + kAhead);
+      __builtin_amdgcn_sched_barrier(0);
+      o[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[m % kRing], pf[m >> 2], o[m & 3], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   const float ltot = l + __shfl_xor(l, 32, 64);
@@ -291,12 +352,119 @@ __global__ __launch_bounds__(kThreads) void attn_delta_kernel(const bf16* __rest
   }
 }
 
+// ---- backward: one step of the dK/dV kernel ------------------------------------------------
+// 64 queries against this wave's 32 keys, in two halves of 32 queries (one accumulator tile
+// each) so that the VALU work of one half runs in the shadow of the other half's MFMAs:
+//   A(0);  A(1) with softmax(0) between its MFMAs;  C(0) with softmax(1) between its MFMAs;  C(1)
+// A(i): S_i = Q_i K^T, dP_i = dO_i V^T (16 MFMAs); softmax(i): P_i = exp2(S_i sl2 - lse),
+// dS_i = P_i (dP_i - D); C(i): dV^T += dO_i^T P_i, dK^T += Q_i^T dS_i (16 MFMAs).
+// A wave has its SIMD to itself (the dK / dV accumulators fill half of the register file), so
+// nothing hides an LDS read that is waited for right before its MFMA: every fragment is
+// requested two MFMA pairs ahead (a ring of three), and scheduling barriers pin the order
+// "MFMA, one softmax element, MFMA, one softmax element".  On the tiles that cross the diagonal
+// (`diag`, uniform over the wave) P and dS of a half are masked in a pass of their own before
+// the half's C phase: query 32 i + 8 (r / 4) + (r % 4) + 4 half of the tile is hidden from this
+// lane's key when that index, without the lane's 4 half, is below `first_q`.
+__device__ __forceinline__ void dkv_step(const char* q_tile, const char* do_tile, const float* lse_j,
+                                         const float* delta_j, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
+                                         f32x16 (&dk)[4], f32x16 (&dv)[4], const TransOffsets& to, int l32, int half,
+                                         bool diag, int first_q, float sl2) {
+  f32x16 s[2], dp[2];
+  // row statistics of queries 32 i + 8 c + 4 half + 0..3, fetched from LDS one group of four
+  // elements ahead of their use (all of them up front would cost 64 registers that the
+  // accumulators need)
+  f32x4 lse_v[2][4], delta_v[2][4];
+  auto load_stat = [&](int i, int c) {
+    lse_v[i][c] = *reinterpret_cast<const f32x4*>(lse_j + 32 * i + 8 * c + 4 * half);
+    delta_v[i][c] = *reinterpret_cast<const f32x4*>(delta_j + 32 * i + 8 * c + 4 * half);
+  };
+  // element r of half i: s <- P, dp <- dS
+  auto soft = [&](int i, int r) {
+    float p = fast_exp2(__builtin_fmaf(s[i][r], sl2, -lse_v[i][r >> 2][r & 3]));
+    s[i][r] = p;
+    dp[i][r] = p * (dp[i][r] - delta_v[i][r >> 2][r & 3]);
+  };
+  // fragment rings: a fragment is requested kAhead MFMA pairs before the pair that uses it
+  constexpr int kAhead = 4, kRing = kAhead + 1;
+  bf16x8 fq[kRing], fd[kRing];
+  auto mask = [&](int i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (32 * i + 8 * (r >> 2) + (r & 3) < first_q) { s[i][r] = 0.f; dp[i][r] = 0.f; }
+  };
+  // A(i); `between(n)` runs after MFMA n of the phase, n = 0..15
+  auto phase_a = [&](int i, auto&& between) {
+#pragma unroll
+    for (int kd = 0; kd < kAhead; ++kd) {
+      fq[kd] = row_frag(q_tile, i, kd, l32, half);
+      fd[kd] = row_frag(do_tile, i, kd, l32, half);
+    }
+#pragma unroll
+    for (int kd = 0; kd < 8; ++kd) {
+      if (kd + kAhead < 8) {
+        fq[(kd + kAhead) % kRing] = row_frag(q_tile, i, kd + kAhead, l32, half);
+        fd[(kd + kAhead) % kRing] = row_frag(do_tile, i, kd + kAhead, l32, half);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[kd % kRing], kf[kd], kd == 0 ? kZero16 : s[i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      between(2 * kd);
+      __builtin_amdgcn_sched_barrier(0);
+      dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[kd % kRing], vf[kd], kd == 0 ? kZero16 : dp[i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      between(2 * kd + 1);
+    }
+  };
+  // C(i): k-steps 2 i and 2 i + 1 (the 16 queries each of P_i / dS_i), four d blocks each
+  auto phase_c = [&](int i, auto&& between) {
+#pragma unroll
+    for (int m = 0; m < kAhead; ++m) {
+      fd[m] = trans_frag(do_tile, to, m & 3, 2 * i + (m >> 2));
+      fq[m] = trans_frag(q_tile, to, m & 3, 2 * i + (m >> 2));
+    }
+    bf16x8 pf, dsf;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int dt = m & 3, s2 = m >> 2;
+      if (m + kAhead < 8) {
+        fd[(m + kAhead) % kRing] = trans_frag(do_tile, to, (m + kAhead) & 3, 2 * i + ((m + kAhead) >> 2));
+        fq[(m + kAhead) % kRing] = trans_frag(q_tile, to, (m + kAhead) & 3, 2 * i + ((m + kAhead) >> 2));
+      }
+      if (dt == 0) { pf = acc_frag(s[i], s2); dsf = acc_frag(dp[i], s2); }
+      __builtin_amdgcn_sched_barrier(0);
+      dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[m % kRing], pf, dv[dt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      between(2 * m);
+      __builtin_amdgcn_sched_barrier(0);
+      dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[m % kRing], dsf, dk[dt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      between(2 * m + 1);
+    }
+  };
+  phase_a(0, [&](int) {});
+  load_stat(0, 0);
+  phase_a(1, [&](int n) {
+    if (n % 4 == 0 && n < 12) load_stat(0, n / 4 + 1);
+    soft(0, n);
+  });
+  load_stat(1, 0);
+  if (diag) mask(0);
+  phase_c(0, [&](int n) {
+    if (n % 4 == 0 && n < 12) load_stat(1, n / 4 + 1);
+    soft(1, n);
+  });
+  if (diag) mask(1);
+  phase_c(1, [&](int) {});
+}
+
 // ---- backward: dK, dV ----------------------------------------------------------------------
 // One workgroup: 128 keys of one (b, kv head); wave w owns keys [32w, 32w+32).  For every query
 // head of the group (ascending) and every 64-query tile at or below the diagonal:
-//   S = Q K^T, dP = dO V^T  (A = Q / dO row tiles from LDS, B = K / V fragments in registers)
+//   S = Q K^T, dP = dO V^T  (A = Q / dO rows from LDS, B = K / V fragments in registers)
 //   P = exp(S/sqrt(hd) - lse), dS = P (dP - D)
-//   dV^T += dO^T P,  dK^T += Q^T dS  (A = transposed tiles from LDS, B = P / dS from registers)
+//   dV^T += dO^T P,  dK^T += Q^T dS  (A = the same Q / dO tiles read transposed, B = P / dS
+//   from the accumulator registers)
+// The (head, tile) steps form one sequence whose tiles alternate between two LDS sets.
 // With `partial` (grouped-query attention with a scratch buffer) a workgroup handles ONE query
 // head (grid x = query heads x batch) and stores its unscaled fp32 dK and dV rows to
 // partial[(b * Hq + h) * seq + key][0..127] and, mb * Hq * seq rows further, the dV rows; the
@@ -304,14 +472,10 @@ __global__ __launch_bounds__(kThreads) void attn_delta_kernel(const bf16* __rest
 // it a workgroup walks the whole group of its kv head itself (grid x = kv heads x batch).
 __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
     const bf16* __restrict__ qkv, const bf16* __restrict__ dout, const float* __restrict__ lse,
-    const float* __restrict__ delta, bf16* __restrict__ dqkv, int seq, int Hq, int Hkv, long long qkv_bytes,
-    long long dout_bytes, float* __restrict__ partial, long long partial_dv_offset) {
-  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];
-  __shared__ float lse_s[64], delta_s[64];
-  char* q_tile = lds;
-  char* do_tile = lds + kTileBytes;
-  char* qt_tile = lds + 2 * kTileBytes;
-  char* dot_tile = lds + 3 * kTileBytes;
+    const float* __restrict__ delta, bf16* __restrict__ dqkv, int seq, int Hq, int Hkv,
+    float* __restrict__ partial, long long partial_dv_offset) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];   // two sets of (Q, dO)
+  __shared__ float lse_s[2][64], delta_s[2][64];
   // early key blocks (most query tiles) first
   const int kb = blockIdx.y;
   const int heads_x = partial ? Hq : Hkv;
@@ -327,6 +491,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
   const bf16* vbase = kbase + (size_t)Hkv * HD;
   const float scale = rsqrtf((float)HD);
   const float sl2 = scale * kLog2e;
+  const TransOffsets to = trans_offsets(l32, half);
 
   bf16x8 kf[8], vf[8];
   const int krow = kw0 + l32;
@@ -335,87 +500,72 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
     kf[kd] = global_frag(kbase, ld, krow, krow < seq, kd, half);
     vf[kd] = global_frag(vbase, ld, krow, krow < seq, kd, half);
   }
+#pragma unroll
+  for (int kd = 0; kd < 8; ++kd) { settle(kf[kd]); settle(vf[kd]); }
+  // The accumulators start as the result of an MFMA (0 * 0 + 0) rather than of a zero fill, and
+  // are pinned once: they then live in the accumulation registers from here to the epilogue.  A
+  // tile that ordinary arithmetic defines is kept in architectural registers instead and copied,
+  // sixteen registers in and sixteen out, around every MFMA that adds to it.
   f32x16 dk[4], dv[4];
+  {
+    bf16x8 z;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+    for (int e = 0; e < 8; ++e) z[e] = (bf16)0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+    for (int dt = 0; dt < 4; ++dt) {
+      dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(z, z, kZero16, 0, 0, 0);
+      dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(z, z, kZero16, 0, 0, 0);
+      pin_agpr(dk[dt]);
+      pin_agpr(dv[dt]);
+    }
+  }
 
   const int first_tile = k0 / 64;
   const int n_tiles = (seq + 63) / 64;
-  for (int hh = hh_first; hh < hh_end; ++hh) {
-    const int h = g * group + hh;
+  const int per_head = n_tiles - first_tile;             // >= 1: k0 < seq
+  const int n_steps = (hh_end - hh_first) * per_head;
+  // step j -> (query head, query tile); starts the loads of its tiles into set j & 1 and
+  // fetches (first wave) the tile's row statistics into registers
+  float lse_r = INFINITY, delta_r = 0.f;
+  TileLoader q_loader, do_loader;
+  q_loader.init(ld);
+  do_loader.init(ldo);
+  auto issue = [&](int j) {
+    const int h = g * group + hh_first + j / per_head;
+    const int qt0 = (first_tile + j % per_head) * 64;
     const bf16* qbase = qkv + tok0 * ld + (size_t)h * HD;
     const bf16* dobase = dout + tok0 * ldo + (size_t)h * HD;
-    const float* lrow = lse + ((size_t)b * Hq + h) * seq;
-    const float* drow = delta + ((size_t)b * Hq + h) * seq;
-    for (int t = first_tile; t < n_tiles; ++t) {
-      const int qt0 = t * 64;
-      __syncthreads();
-      const long long left_q = qkv_bytes - (long long)((qbase + (size_t)qt0 * ld) - qkv) * 2;
-      const long long left_do = dout_bytes - (long long)((dobase + (size_t)qt0 * ldo) - dout) * 2;
-      load_row_tile(q_tile, qbase + (size_t)qt0 * ld, ld, seq - qt0, left_q);
-      load_row_tile(do_tile, dobase + (size_t)qt0 * ldo, ldo, seq - qt0, left_do);
-      TransposedStage sq, sd;
-      sq.issue(qbase + (size_t)qt0 * ld, ld, seq - qt0, left_q);
-      sd.issue(dobase + (size_t)qt0 * ldo, ldo, seq - qt0, left_do);
-      if (threadIdx.x < 64) {
-        const int q = qt0 + threadIdx.x;
-        lse_s[threadIdx.x] = q < seq ? lrow[q] * kLog2e : INFINITY;  // +inf makes P = 0 beyond the end
-        delta_s[threadIdx.x] = q < seq ? drow[q] : 0.f;
-      }
-      sq.store(qt_tile);
-      sd.store(dot_tile);
-      __syncthreads();
-      if (qt0 + 63 < kw0) continue;            // every query of this tile precedes this wave's keys
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(q_tile, i, 0, l32, half), kf[0], kZero16, 0, 0, 0);
-        dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(do_tile, i, 0, l32, half), vf[0], kZero16, 0, 0, 0);
-      }
-#pragma unroll
-      for (int kd = 1; kd < 8; ++kd)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(q_tile, i, kd, l32, half), kf[kd], s[i], 0, 0, 0);
-          dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(do_tile, i, kd, l32, half), vf[kd], dp[i], 0, 0, 0);
-        }
-      // s[i][r]: query qt0 + 32 i + 8 (r/4) + 4 half + r%4, key kw0 + l32
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int ql = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-          s[i][r] = fast_exp2(__builtin_fmaf(s[i][r], sl2, -lse_s[ql]));
-        }
-      if (qt0 < kw0 + 31) {                    // only tiles that cross the diagonal need the mask
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int ql = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (qt0 + ql < krow) s[i][r] = 0.f;
-          }
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int ql = 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-          dp[i][r] = s[i][r] * (dp[i][r] - delta_s[ql]);
-        }
-#pragma unroll
-      for (int sk = 0; sk < 4; ++sk) {
-        const bf16x8 pf = acc_frag(s[sk >> 1], sk & 1);
-        const bf16x8 dsf = acc_frag(dp[sk >> 1], sk & 1);
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trans_frag(dot_tile, dt, sk, l32, half), pf, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trans_frag(qt_tile, dt, sk, l32, half), dsf, dk[dt], 0, 0, 0);
-        }
-      }
+    if (threadIdx.x < 64) {
+      const int q = qt0 + (int)threadIdx.x;
+      const size_t row = ((size_t)b * Hq + h) * seq;
+      lse_r = q < seq ? lse[row + q] : INFINITY;            // +inf makes P = 0 beyond the end
+      delta_r = q < seq ? delta[row + q] : 0.f;
     }
+    char* set = lds + (j & 1) * (2 * kTileBytes);
+    q_loader.issue(set, qbase + (size_t)qt0 * ld, seq - qt0);
+    do_loader.issue(set + kTileBytes, dobase + (size_t)qt0 * ldo, seq - qt0);
+  };
+  auto publish = [&](int j) {
+    // (the scaling waits for the load: here, a step after it was issued, not in issue())
+    if (threadIdx.x < 64) { lse_s[j & 1][threadIdx.x] = lse_r * kLog2e; delta_s[j & 1][threadIdx.x] = delta_r; }
+  };
+  issue(0);
+  publish(0);
+  for (int j = 0; j < n_steps; ++j) {
+    const int qt0 = (first_tile + j % per_head) * 64;
+    // the tiles and statistics of step j are in place for every wave, and every wave is done
+    // with step j-1, whose set and statistics the next step's loads and publish overwrite
+    step_barrier();
+    if (j + 1 < n_steps) issue(j + 1);
+    const char* q_tile = lds + (j & 1) * (2 * kTileBytes);
+    const char* do_tile = q_tile + kTileBytes;
+    const float* lse_j = lse_s[j & 1];
+    const float* delta_j = delta_s[j & 1];
+    if (qt0 + 63 >= kw0) {                     // else every query of this tile precedes this wave's keys
+      // query qt0 + ql is masked for key krow when qt0 + ql < krow; only tiles that cross the diagonal have such pairs
+      dkv_step(q_tile, do_tile, lse_j, delta_j, kf, vf, dk, dv, to, l32, half, qt0 < kw0 + 31, krow - qt0 - 4 * half, sl2);
+    }
+    if (j + 1 < n_steps) publish(j + 1);
   }
   if (partial) {
     if (krow < seq) {
@@ -482,15 +632,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_reduce_kernel(const flo
 
 // ---- backward: dQ --------------------------------------------------------------------------
 // One workgroup: 128 queries of one (b, h); wave w owns queries [32w, 32w+32).  KV tiles of 64:
-//   S^T = K Q^T, dP^T = V dO^T (A = K / V row tiles from LDS, B = Q / dO fragments in registers)
-//   dS^T = P^T (dP^T - D);  dQ^T += K^T dS^T (A = transposed K tile)
+//   S^T = K Q^T, dP^T = V dO^T (A = K / V rows from LDS, B = Q / dO fragments in registers)
+//   dS^T = P^T (dP^T - D);  dQ^T += K^T dS^T (A = the K tile read transposed)
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
     const bf16* __restrict__ qkv, const bf16* __restrict__ dout, const float* __restrict__ lse,
-    const float* __restrict__ delta, bf16* __restrict__ dqkv, int seq, int Hq, int Hkv, long long qkv_bytes) {
-  __shared__ __attribute__((aligned(1024))) char lds[3 * kTileBytes];
-  char* k_tile = lds;
-  char* v_tile = lds + kTileBytes;
-  char* kt_tile = lds + 2 * kTileBytes;
+    const float* __restrict__ delta, bf16* __restrict__ dqkv, int seq, int Hq, int Hkv) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];   // two sets of (K, V)
   const int qb = gridDim.y - 1 - blockIdx.y;   // heaviest first, as in the forward kernel
   const int h = blockIdx.x % Hq, b = blockIdx.x / Hq;
   const int g = h / (Hq / Hkv);
@@ -504,6 +651,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
   const bf16* vbase = kbase + (size_t)Hkv * HD;
   const float scale = rsqrtf((float)HD);
   const float sl2 = scale * kLog2e;
+  const TransOffsets to = trans_offsets(l32, half);
 
   const int qrow = qw0 + l32;
   const bool q_ok = qrow < seq;
@@ -515,6 +663,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
   }
   const float lse2 = q_ok ? lse[((size_t)b * Hq + h) * seq + qrow] * kLog2e : INFINITY;
   const float dlt = q_ok ? delta[((size_t)b * Hq + h) * seq + qrow] : 0.f;
+#pragma unroll
+  for (int kd = 0; kd < 8; ++kd) { settle(qf[kd]); settle(dof[kd]); }
+  settle(lse2);
+  settle(dlt);
   f32x16 dq[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -523,53 +675,69 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
 
   const int q_end = min(q0 + 128, seq);
   const int n_tiles = (q_end + 63) / 64;
+  TileLoader loader;
+  loader.init(ld);
+  auto issue = [&](int t) {
+    const int kv0 = t * 64;
+    char* set = lds + (t & 1) * (2 * kTileBytes);
+    loader.issue(set, kbase + (size_t)kv0 * ld, seq - kv0);
+    loader.issue(set + kTileBytes, vbase + (size_t)kv0 * ld, seq - kv0);
+  };
+  issue(0);
   for (int t = 0; t < n_tiles; ++t) {
     const int kv0 = t * 64;
-    __syncthreads();
-    const long long left_k = qkv_bytes - (long long)((kbase + (size_t)kv0 * ld) - qkv) * 2;
-    load_row_tile(k_tile, kbase + (size_t)kv0 * ld, ld, seq - kv0, left_k);
-    load_row_tile(v_tile, vbase + (size_t)kv0 * ld, ld, seq - kv0, left_k - (long long)Hkv * HD * 2);
-    TransposedStage ks;
-    ks.issue(kbase + (size_t)kv0 * ld, ld, seq - kv0, left_k);
-    ks.store(kt_tile);
-    __syncthreads();
+    step_barrier();                             // tile t in place, tile t-1's set free for tile t+1
+    if (t + 1 < n_tiles) issue(t + 1);
+    const char* k_tile = lds + (t & 1) * (2 * kTileBytes);
+    const char* v_tile = k_tile + kTileBytes;
     if (kv0 > qw0 + 31) continue;
-    f32x16 s[2], dp[2];
+    const bool diag = kv0 + 63 > qw0;          // only tiles that cross the diagonal need the mask
+    // The tile's 64 keys in two halves of 32 (one accumulator tile of S^T and of dP^T each).
+    // Every MFMA multiplies a fragment requested from LDS kAhead MFMAs earlier (a ring of
+    // kAhead + 1 fragments); scheduling barriers keep the requests in front.  What a wave
+    // still waits for, the other workgroup's wave on its SIMD fills.
+    constexpr int kAhead = 4, kRing = kAhead + 1;
+    bf16x8 ring[kRing];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, 0, l32, half), qf[0], kZero16, 0, 0, 0);
-      dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(v_tile, i, 0, l32, half), dof[0], kZero16, 0, 0, 0);
-    }
+      f32x16 s, dp;
+      // S^T_i and dP^T_i, their k-steps interleaved: item n = (k-step n / 2, S or dP)
+      auto frag = [&](int n) { return row_frag((n & 1) ? v_tile : k_tile, i, n >> 1, l32, half); };
 #pragma unroll
-    for (int kd = 1; kd < 8; ++kd)
+      for (int n = 0; n < kAhead; ++n) ring[n] = frag(n);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(k_tile, i, kd, l32, half), qf[kd], s[i], 0, 0, 0);
-        dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(v_tile, i, kd, l32, half), dof[kd], dp[i], 0, 0, 0);
+      for (int n = 0; n < 16; ++n) {
+        if (n + kAhead < 16) ring[(n + kAhead) % kRing] = frag(n + kAhead);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[n % kRing], dof[n >> 1], n == 1 ? kZero16 : dp, 0, 0, 0);
+        else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[n % kRing], qf[n >> 1], n == 0 ? kZero16 : s, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // the transposed K fragments of this half's two k-steps: requested now, they arrive while
+      // the exponentials are computed
+      auto tfrag = [&](int m) { return trans_frag(k_tile, to, m & 3, 2 * i + (m >> 2)); };
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int m = 0; m < kAhead; ++m) ring[m] = tfrag(m);
+      // s[r]: key kv0 + 32 i + 8 (r/4) + 4 half + r%4, query qw0 + l32
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[i][r] = fast_exp2(__builtin_fmaf(s[i][r], sl2, -lse2));
-    if (kv0 + 63 > qw0) {                     // only tiles that cross the diagonal need the mask
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int r = 0; r < 16; ++r) s[r] = fast_exp2(__builtin_fmaf(s[r], sl2, -lse2));
+      if (diag) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = kv0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (key > qrow) s[i][r] = 0.f;
+          if (key > qrow) s[r] = 0.f;
         }
-    }
+      }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int r = 0; r < 16; ++r) s[r] *= dp[r] - dlt;        // dS^T = P^T (dP^T - D)
+      const bf16x8 b0 = acc_frag(s, 0), b1 = acc_frag(s, 1);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dp[i][r] = s[i][r] * (dp[i][r] - dlt);
-#pragma unroll
-    for (int sk = 0; sk < 4; ++sk) {
-      const bf16x8 dsf = acc_frag(dp[sk >> 1], sk & 1);
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(trans_frag(kt_tile, dt, sk, l32, half), dsf, dq[dt], 0, 0, 0);
+      for (int m = 0; m < 8; ++m) {
+        if (m + kAhead < 8) ring[(m + kAhead) % kRing] = tfrag(m + kAhead);
+        __builtin_amdgcn_sched_barrier(0);
+        dq[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[m % kRing], m < 4 ? b0 : b1, dq[m & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
   if (q_ok) {
@@ -597,14 +765,11 @@ size_t attention_bwd_scratch_bytes(int mb, int seq, int Hq, int Hkv, int hd) {
 
 hipError_t launch_attention_fwd_mfma(const AttnDesc& a, hipStream_t s) {
   dim3 grid(a.Hq * a.mb, (a.seq + 127) / 128);
-  const long long bytes = (long long)a.mb * a.seq * (a.Hq + 2 * a.Hkv) * HD * 2;
-  attn_fwd_mfma_kernel<<<grid, kThreads, 0, s>>>((const bf16*)a.qkv, (bf16*)a.out, a.lse, a.seq, a.Hq, a.Hkv, bytes);
+  attn_fwd_mfma_kernel<<<grid, kThreads, 0, s>>>((const bf16*)a.qkv, (bf16*)a.out, a.lse, a.seq, a.Hq, a.Hkv);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_bwd_mfma(const AttnDesc& a, hipStream_t s) {
-  const long long qkv_bytes = (long long)a.mb * a.seq * (a.Hq + 2 * a.Hkv) * HD * 2;
-  const long long do_bytes = (long long)a.mb * a.seq * a.Hq * HD * 2;
   const size_t rows = (size_t)a.mb * a.seq * a.Hq;
   attn_delta_kernel<<<(unsigned)((rows + 15) / 16), kThreads, 0, s>>>((const bf16*)a.out, (const bf16*)a.dout,
                                                                       a.delta, a.mb, a.seq, a.Hq);
@@ -617,7 +782,7 @@ hipError_t launch_attention_bwd_mfma(const AttnDesc& a, hipStream_t s) {
   const long long dv_off = (long long)a.mb * a.Hq * a.seq * HD;
   dim3 gk((split ? a.Hq : a.Hkv) * a.mb, (a.seq + 127) / 128);
   attn_bwd_dkv_mfma_kernel<<<gk, kThreads, 0, s>>>((const bf16*)a.qkv, (const bf16*)a.dout, a.lse, a.delta,
-                                                   (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes, do_bytes,
+                                                   (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv,
                                                    split ? a.dkv_partial : nullptr, dv_off);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -631,7 +796,7 @@ hipError_t launch_attention_bwd_mfma(const AttnDesc& a, hipStream_t s) {
   }
   dim3 gq(a.Hq * a.mb, (a.seq + 127) / 128);
   attn_bwd_dq_mfma_kernel<<<gq, kThreads, 0, s>>>((const bf16*)a.qkv, (const bf16*)a.dout, a.lse, a.delta,
-                                                  (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv, qkv_bytes);
+                                                  (bf16*)a.dqkv, a.seq, a.Hq, a.Hkv);
   return hipGetLastError();
 }
 
