@@ -91,35 +91,228 @@ def time_dominant_kernel(w, torch, B, reps=3):
     return avg_ms, total_flops / n
 
 
-def cpu_baseline():
-    """The fp64 oracle, as it stands, on one microbatch (forward + backward) of one layer of a
-    two-thirds-width twin of the GPT-3-shaped stage: d_model 8192, 64 heads of 128, FFN 32768, seq 2048
-    (about 10 algorithmic TFLOP, 10-30 s of host time)."""
-    import numpy as np
-    from oracle import stage_oracle as so
-    from paper_2412_14374_amd import inputs as inp
-    w = inp.shrunk_twin(inp.C4, d_model=8192, seq_len=2048, d_ffn=32768, n_q_heads=64, n_microbatches=1)
-    spec = so.StageSpec(n_layers=1, d_model=w.d_model, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
-                        head_dim=w.head_dim, d_ffn=w.d_ffn, seq_len=w.seq_len, microbatch=w.microbatch)
-    rng = np.random.default_rng(0)
-    p = {k: rng.standard_normal(s) * 0.02 for k, s in so.layer_param_shapes(spec)}
-    x = rng.standard_normal((1, w.seq_len, w.d_model))
-    c = rng.standard_normal((1, w.seq_len, w.d_model))
-    t0 = time.perf_counter()
-    y, cache = so.layer_forward(spec, p, x)
-    so.layer_backward(spec, p, cache, c)
-    dt = time.perf_counter() - t0
-    flops = so.algorithmic_flops_per_microbatch(spec)
+class ClockSampler:
+    """Shader clock and board power read from the driver's sysfs files every 50 ms while a timed
+    region runs (the matrix pipes' clock under load is far below the nominal 2.4 GHz and differs
+    from box to box, so a rate means little without it).  Everything is None when the files
+    cannot be read."""
+
+    def __init__(self):
+        import glob
+        import threading
+        self.sclk = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))[:1]
+        self.power = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))[:1]
+        self.mhz, self.watts = [], []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._loop, daemon=True)
+
+    def _read(self):
+        try:
+            for line in open(self.sclk[0]):
+                if "*" in line:
+                    self.mhz.append(float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip()))
+            if self.power:
+                self.watts.append(float(open(self.power[0]).read()) / 1e6)
+        except Exception:
+            pass
+
+    def _loop(self):
+        while not self._stop.is_set():
+            self._read()
+            self._stop.wait(0.05)
+
+    def __enter__(self):
+        if self.sclk:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self.sclk:
+            self._thread.join()
+
+    def summary(self):
+        if not self.mhz:
+            return None
+        out = {"sclk_mhz_min": min(self.mhz), "sclk_mhz_mean": sum(self.mhz) / len(self.mhz),
+               "sclk_mhz_max": max(self.mhz), "samples": len(self.mhz), "nominal_mhz": 2400,
+               "source": "sysfs pp_dpm_sclk / hwmon power1_input, sampled every 50 ms over the timed steps"}
+        if self.watts:
+            out["power_w_mean"] = sum(self.watts) / len(self.watts)
+            out["power_w_max"] = max(self.watts)
+        return out
+
+
+def run_stage(w, steps, warmup, torch, B, inp, Stage, opt_kind=None, optimizer_name=None):
+    """K timed steps of one configuration (a step = jpp_stage_zero_grads + jpp_stage_run of the
+    whole task list, inputs resident in HBM).  Returns the figures of the bench line's top level."""
+    task_list = None
+    if w.sched == inp.SCHED_GPIPE and w.V > 1:
+        # GPipe on a circular placement: every forward of every owned stage, then every backward
+        task_list = [(i, B.JPP_FWD, s) for s in w.stage_ids for i in range(w.n_microbatches)]
+        task_list += [(i, B.JPP_BWD, s) for s in reversed(w.stage_ids) for i in range(w.n_microbatches)]
+    st = Stage(w, tasks=task_list)
+    streams = 3 - B.jpp_stage_stream_mode(st.h)
+    arena_gb = B.jpp_stage_arena_bytes(st.cfg, st.M, st.max_in_flight) / 1e9
+    stash_slots = st.max_in_flight
+    st.set_params_random(seed=0)
+    st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM
+    if opt_kind is not None:
+        st.optimizer_bind(opt_kind)
+    step_no = [0]
+
+    def update():
+        if opt_kind is not None:
+            step_no[0] += 1
+            st.apply_gradients(opt_kind, lr=1e-4 / w.n_microbatches, weight_decay=0.01, step=step_no[0])
+
+    for _ in range(warmup):
+        st.zero_grads()
+        st.run()
+        update()
+    st.sync()
+    torch.cuda.synchronize()
+    # per-step marks on the stage's compute stream (every run is joined back into it), recorded
+    # without waiting: the host keeps enqueueing while the GPU works
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    with ClockSampler() as clocks:
+        t0 = time.perf_counter()
+        marks[0].record(st.compute)
+        for k in range(steps):
+            st.zero_grads()
+            st.run()
+            update()
+            marks[k + 1].record(st.compute)
+        st.sync()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    ms_per_step = dt / steps * 1e3
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+    flops_step = algorithmic_flops_per_microbatch(w) * w.n_microbatches
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    opt_info = None
+    if opt_kind is not None:
+        # the update alone: HBM-bound, 4 (g) + 2 x esz (w) bytes per parameter for SGD,
+        # 16 read + 12 written in fp32 state plus esz written for AdamW
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st.compute)
+        for _ in range(3):
+            update()
+        e1.record(st.compute)
+        st.sync()
+        ms_u = e0.elapsed_time(e1) / 3
+        esz = 2 if w.dtype == inp.DT_BF16 else 4
+        per = (4 + 2 * esz) if opt_kind == B.JPP_OPT_SGD else (28 + esz)
+        nbytes = per * st.pcount * len(w.stage_ids)
+        opt_info = {"kind": optimizer_name, "ms": ms_u, "bytes": nbytes, "achieved_GBps": nbytes / ms_u / 1e6,
+                    "peak_GBps": PEAK_HBM_GBS, "frac": nbytes / ms_u / 1e6 / PEAK_HBM_GBS}
+    # sanity: the run produced finite gradients
+    finite = bool(torch.isfinite(st.grads_tensor(0)).all().item())
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    return {"tflops": tflops, "ms_per_step": ms_per_step, "per_step": per_step, "finite": finite,
+            "streams": streams, "arena_gb": arena_gb, "stash_slots": stash_slots, "optimizer": opt_info,
+            "clocks": clocks.summary(), "microbatches_per_s": w.n_microbatches / (ms_per_step * 1e-3)}
+
+
+def brief(w, r, steps, warmup):
+    """One configuration in a few fields (the secondary entries of the bench line)."""
+    return {"workload": w.name, "value": r["tflops"], "unit": "TFLOP/s",
+            "pct_of_bf16_mfma_peak": 100.0 * r["tflops"] / PEAK_BF16_TFLOPS, "ms_per_step": r["ms_per_step"],
+            "microbatches_per_s": r["microbatches_per_s"], "steps": steps, "warmup": warmup,
+            "wgrad_group": max(1, w.wgrad_group), "streams": r["streams"], "arena_gb": r["arena_gb"],
+            "stash_slots": r["stash_slots"], "grads_finite": r["finite"],
+            "sclk_mhz_mean": (r["clocks"] or {}).get("sclk_mhz_mean")}
+
+
+def oracle_threads():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        return max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count()
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "seconds": dt, "microbatches_per_s_extrapolated_to_workload": None,
-            "sample": "fp64 numpy oracle, forward+backward of ONE microbatch of ONE layer of a shrunk twin "
-                      "(d_model 8192, 64 heads x 128, FFN 32768, seq 2048, GeLU, LayerNorm); "
-                      f"{flops / 1e9:.0f} algorithmic GFLOP"}
+        return os.cpu_count()
+
+
+# Structure-matched twins for the oracle's timed sample: the configuration's own norm, activation,
+# bias, RoPE, head_dim and query/kv head ratio (and loss head), at a width that keeps one
+# microbatch of one layer at 5-10 algorithmic TFLOP (10-30 s of host time).
+CPU_TWINS = {
+    "C2": dict(d_model=8192, n_q_heads=64, d_ffn=32768, seq_len=2048, microbatch=1),
+    "C4": dict(d_model=8192, n_q_heads=64, d_ffn=32768, seq_len=2048, microbatch=1),
+    "C3": dict(d_model=4096, n_q_heads=32, d_ffn=14336, seq_len=2048, microbatch=1),
+    "C5": dict(d_model=4096, n_q_heads=32, d_ffn=16384, seq_len=2048, microbatch=1, vocab=50304),
+}
+
+
+def cpu_baseline(config, w):
+    """The fp64 oracle, as it stands, timed on the host: for C1 the whole run (all microbatches,
+    forward and backward, the configuration's own task list) on all cores and on one; for the
+    other configurations one microbatch, forward + backward, of ONE layer (plus the loss head for
+    C5) of a structure-matched twin, the rate extrapolated to the workload by FLOP count."""
+    import numpy as np
+    from dataclasses import replace
+    from oracle import stage_oracle as so
+    from paper_2412_14374_amd import binding as B
+    from paper_2412_14374_amd import inputs as inp
+
+    def spec_of(t):
+        return so.StageSpec(n_layers=t.n_layers, d_model=t.d_model, n_q_heads=t.n_q_heads, n_kv_heads=t.n_kv_heads,
+                            head_dim=t.head_dim, d_ffn=t.d_ffn, seq_len=t.seq_len, microbatch=t.microbatch,
+                            norm=t.norm, act=t.act, use_bias=bool(t.use_bias), rope=bool(t.rope),
+                            rope_theta=t.rope_theta, norm_eps=t.norm_eps, loss_head=bool(t.loss_head), vocab=t.vocab)
+
+    if config == "C1":
+        base = inp.C1
+        spec = spec_of(base)
+        params, x, cot, tg = inp.draw_stage_inputs(base, so.layer_param_shapes(spec), None)
+        tasks = [(i, "fwd" if ty == B.JPP_FWD else "bwd", s_)
+                 for (i, ty, s_) in B.jpp_schedule_make(base.sched, base.P, base.rank, base.V, base.n_microbatches)]
+        flops = so.algorithmic_flops_per_microbatch(spec) * base.n_microbatches
+
+        def whole_run():
+            t0 = time.perf_counter()
+            for _ in range(20):
+                so.run_task_list(spec, params, tasks, x, cot, tg)
+            return (time.perf_counter() - t0) / 20
+        all_cores = whole_run()
+        try:
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                one_core = whole_run()
+        except Exception:
+            one_core = None
+        return {"value": flops / all_cores / 1e12, "unit": "TFLOP/s", "cores": oracle_threads(), "kind": "oracle",
+                "seconds": all_cores, "seconds_one_core": one_core,
+                "steps_per_s": 1.0 / all_cores, "steps_per_s_one_core": (1.0 / one_core) if one_core else None,
+                "microbatches_per_s_extrapolated_to_workload": base.n_microbatches / all_cores,
+                "sample": "fp64 numpy oracle, the WHOLE C1 step (4 microbatches, forward + backward, GPipe list), "
+                          f"mean of 20 runs, on all cores and on one; {flops / 1e9:.2f} algorithmic GFLOP per step"}
+    kw = dict(CPU_TWINS[config])
+    ratio = w.n_q_heads // w.n_kv_heads
+    t = replace(w, n_layers=1, n_kv_heads=kw["n_q_heads"] // ratio, n_microbatches=1, **kw)
+    spec = spec_of(t)
+    rng = np.random.default_rng(0)
+    p = {"layers": [{k: rng.standard_normal(shp) * 0.02 for k, shp in so.layer_param_shapes(spec)}]}
+    if t.loss_head:
+        p["head"] = {k: rng.standard_normal(shp) * 0.02 for k, shp in so.head_param_shapes(spec)}
+    x = rng.standard_normal((t.microbatch, t.seq_len, t.d_model))
+    c = None if t.loss_head else rng.standard_normal((t.microbatch, t.seq_len, t.d_model))
+    tg = rng.integers(0, t.vocab, size=(t.microbatch, t.seq_len)).astype(np.int32) if t.loss_head else None
+    t0 = time.perf_counter()
+    out, cache = so.stage_forward(spec, p, x, tg)
+    so.stage_backward(spec, p, cache, c)
+    dt = time.perf_counter() - t0
+    flops = so.algorithmic_flops_per_microbatch(spec)
+    what = ["LayerNorm", "RMSNorm"][t.norm] + ", " + ["GeLU", "tanh-GeLU", "SwiGLU"][t.act] + \
+        (", RoPE" if t.rope else "") + (f", {t.n_q_heads}/{t.n_kv_heads} query/kv heads" if ratio > 1 else "") + \
+        (f", final norm + LM head {t.vocab} + cross-entropy" if t.loss_head else "")
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle_threads(), "kind": "oracle",
+            "seconds": dt,
+            "microbatches_per_s_extrapolated_to_workload": (flops / dt) / algorithmic_flops_per_microbatch(w),
+            "sample": "fp64 numpy oracle, forward+backward of ONE microbatch of ONE layer of a structure-matched twin of "
+                      f"{config} (d_model {t.d_model}, {t.n_q_heads} heads x {t.head_dim}, FFN {t.d_ffn}, seq {t.seq_len}, "
+                      f"{what}); {flops / 1e9:.0f} algorithmic GFLOP; the workload's rate is extrapolated by FLOP count"}
 
 
 def bench_kernels(w, torch, B, inp):
@@ -288,6 +481,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the secondary entries of the default run (the same workload with per-task weight "
+                         "gradients, and C2 / C3 / C5 with the same defaults)")
     ap.add_argument("--remat", action="store_true",
                     help="rematerialisation: keep only each layer's input, recompute the layer in the backward "
                          "(the recomputation is not counted in the TFLOP/s)")
@@ -311,8 +507,8 @@ def main():
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
                          "instead of a single actor; prints a line of its own")
     ap.add_argument("--kernel-only", action="store_true",
-                    help="profiling aid: run only the dominant kernel's launches plus one 1 GiB device copy "
-                         "(the reference that scales the FETCH_SIZE / WRITE_SIZE counters)")
+                    help="profiling aid: run only the dominant kernel's launches plus the reference copies that "
+                         "calibrate the profiler's counters (one of 1 GiB, sixteen of 64 MiB)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs one pipeline stage on ONE GPU (no collectives, no sharding); "
@@ -339,11 +535,21 @@ def main():
     group = a.wgrad_group if a.wgrad_group is not None else (1 if a.remat or a.pipeline else min(8, w.n_microbatches))
     w = replace(w, remat=1 if a.remat else 0, sched=kind, wgrad_group=group)
     if a.kernel_only:
+        # references for the profiler's counters: a 1 GiB copy (every read misses every cache: the
+        # scale of FETCH_SIZE / WRITE_SIZE and the read latency of HBM) and 16 copies of the same
+        # 64 MiB (larger than the L2s together, far smaller than the 256 MB last-level cache: the
+        # read latency when that cache answers)
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+        small = torch.ones(1 << 25, dtype=torch.bfloat16, device="cuda:0")    # 64 MiB
+        small2 = torch.empty_like(small)
+        for _ in range(16):
+            small2.copy_(small)
+        torch.cuda.synchronize()
+        del small, small2
         avg_ms, flops = time_dominant_kernel(w, torch, B)
         print(json.dumps({"kernel_only": True, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
                           "tflops": flops / avg_ms / 1e9}))
@@ -352,73 +558,11 @@ def main():
         return bench_kernels(w, torch, B, inp)
     if a.pipeline:
         return bench_pipeline(a, w, torch, B, inp)
-    tasks = None
-    if w.sched == inp.SCHED_GPIPE and w.V > 1:
-        # GPipe on a circular placement: every forward of every owned stage, then every backward
-        tasks = [(i, B.JPP_FWD, s) for s in w.stage_ids for i in range(w.n_microbatches)]
-        tasks += [(i, B.JPP_BWD, s) for s in reversed(w.stage_ids) for i in range(w.n_microbatches)]
-    st = Stage(w, tasks=tasks)
-    streams = 3 - B.jpp_stage_stream_mode(st.h)
-    arena_gb = B.jpp_stage_arena_bytes(st.cfg, st.M, st.max_in_flight) / 1e9
-    stash_slots = st.max_in_flight
-    st.set_params_random(seed=0)
-    st.bind(None, None, None, seed=1)           # synthetic boundary tensors generated in HBM
     opt_kind = {None: None, "sgd": B.JPP_OPT_SGD, "adamw": B.JPP_OPT_ADAMW}[a.optimizer]
-    if opt_kind is not None:
-        st.optimizer_bind(opt_kind)
-    step_no = [0]
-
-    def update():
-        if opt_kind is not None:
-            step_no[0] += 1
-            st.apply_gradients(opt_kind, lr=1e-4 / w.n_microbatches, weight_decay=0.01, step=step_no[0])
-
-    for _ in range(a.warmup):
-        st.zero_grads()
-        st.run()
-        update()
-    st.sync()
-    torch.cuda.synchronize()
-    # per-step marks on the stage's compute stream (every run is joined back into it), recorded
-    # without waiting: the host keeps enqueueing while the GPU works
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
-    t0 = time.perf_counter()
-    marks[0].record(st.compute)
-    for k in range(a.steps):
-        st.zero_grads()
-        st.run()
-        update()
-        marks[k + 1].record(st.compute)
-    st.sync()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / a.steps * 1e3
-    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(a.steps))
-    flops_step = algorithmic_flops_per_microbatch(w) * w.n_microbatches
-    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
-    mb_per_s = w.n_microbatches / (ms_per_step * 1e-3)
-    opt_info = None
-    if opt_kind is not None:
-        # the update alone: HBM-bound, 4 (g) + 2 x esz (w) bytes per parameter for SGD,
-        # 16 read + 12 written in fp32 state plus esz written for AdamW
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(st.compute)
-        for _ in range(3):
-            update()
-        e1.record(st.compute)
-        st.sync()
-        ms_u = e0.elapsed_time(e1) / 3
-        esz = 2 if w.dtype == inp.DT_BF16 else 4
-        per = (4 + 2 * esz) if opt_kind == B.JPP_OPT_SGD else (28 + esz)
-        nbytes = per * st.pcount * len(w.stage_ids)
-        opt_info = {"kind": a.optimizer, "ms": ms_u, "bytes": nbytes, "achieved_GBps": nbytes / ms_u / 1e6,
-                    "peak_GBps": PEAK_HBM_GBS, "frac": nbytes / ms_u / 1e6 / PEAK_HBM_GBS}
-    # sanity: the run produced finite gradients
-    g = st.grads_tensor(0)
-    finite = bool(torch.isfinite(g).all().item())
-    st.close()
-    del st
-    torch.cuda.empty_cache()
+    r = run_stage(w, a.steps, a.warmup, torch, B, inp, Stage, opt_kind, a.optimizer)
+    tflops, ms_per_step, per_step = r["tflops"], r["ms_per_step"], r["per_step"]
+    mb_per_s, finite, opt_info = r["microbatches_per_s"], r["finite"], r["optimizer"]
+    streams, arena_gb, stash_slots = r["streams"], r["arena_gb"], r["stash_slots"]
 
     out = {
         "metric": "stage fwd+bwd TFLOP/s, % of bf16 MFMA peak, microbatches/s (1 GPU)",
@@ -439,10 +583,25 @@ def main():
                    "remat": bool(w.remat), "wgrad_group": max(1, w.wgrad_group), "streams": streams, "arena_gb": arena_gb, "stash_slots": stash_slots,
                    "algorithmic_tflop_per_microbatch": algorithmic_flops_per_microbatch(w) / 1e12},
     }
+    out["clocks"] = r["clocks"]
+    default_run = (a.config == "C4" and a.wgrad_group is None and not a.remat and a.schedule is None
+                   and a.streams is None and a.optimizer is None)
+    if default_run and not a.headline_only:
+        # Section 3.1 has every backward task add its own microbatch's gradients; the headline
+        # defers them to groups of 8 (more stash memory, a longer contraction).  The per-task form
+        # of the same workload, in the same run:
+        w1 = replace(w, wgrad_group=1)
+        out["per_task_wgrad"] = brief(w1, run_stage(w1, 3, 1, torch, B, inp, Stage), 3, 1)
+        # the other bf16 configurations with the same defaults
+        out["other_configs"] = []
+        for name in ("C2", "C3", "C5"):
+            wc = inp.CONFIGS[name]
+            wc = replace(wc, wgrad_group=min(8, wc.n_microbatches))
+            out["other_configs"].append(brief(wc, run_stage(wc, 5, 2, torch, B, inp, Stage), 5, 2))
     if w.dtype == inp.DT_BF16:
         avg_ms, flops_per_launch = time_dominant_kernel(w, torch, B)
         shapes = wgrad_shapes(w)
-        # measured for the C4 shapes only, at groups of 8 (29.8 GB) and per task (6.65 GB)
+        # L2 <-> fabric bytes per launch from the profiler, for the C4 shapes only: groups of 8 / per task
         traffic = {8: 29.8e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
         ach = flops_per_launch / (avg_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel<..., k-strided A, k-strided B> "
@@ -450,16 +609,15 @@ def main():
                            "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": ach / PEAK_BF16_TFLOPS, "avg_launch_ms": avg_ms,
                            "flops_per_launch": flops_per_launch,
-                           # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a 1 GiB copy
-                           # (profiles/gemm_wgrad_c4_hbm_traffic.md); measured for the C4 shapes only
                            "traffic": traffic, "traffic_unit": "bytes/launch",
+                           # not read in this run: the counters need the profiler (one pass each)
+                           "traffic_source": ("profiles/gemm_wgrad_c4_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE, then "
+                                              "WRITE_SIZE, of `bench.py --kernel-only`, scaled by the same counters "
+                                              "of a 1 GiB copy") if traffic else None,
                            "algorithmic_bytes_per_launch": sum(8.0 * m * n + 2.0 * k * (m + n) for m, n, k in shapes)
                            / len(shapes)}
     if not a.no_cpu_baseline:
-        cb = cpu_baseline()
-        per_mb = algorithmic_flops_per_microbatch(w)
-        cb["microbatches_per_s_extrapolated_to_workload"] = cb["value"] * 1e12 / per_mb
-        out["cpu_baseline"] = cb
+        out["cpu_baseline"] = cpu_baseline(a.config, w)
     print(json.dumps(out))
 
 
