@@ -590,7 +590,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
 }
 
 // Sums the split_s partial tiles of every split tile in ascending k order, adds bias and
-// residual and stores in the output mode.  One thread per 4 consecutive columns.
+// residual and stores in the output mode (for an accumulating output: adds the sum to the fp32
+// gradient, which this kernel alone touches).  One thread per 4 consecutive columns.
 template <int BM, int BN>
 __global__ __launch_bounds__(256) void gemm_split_fixup_kernel(int M, int N, Epilogue ep, int n_split) {
   constexpr int kQuads = BM * BN / 4;
@@ -621,8 +622,11 @@ __global__ __launch_bounds__(256) void gemm_split_fixup_kernel(int M, int N, Epi
 #pragma unroll
       for (int c = 0; c < 4; ++c) o[c] = (bf16)v[c];
       *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(ep.C) + idx) = o;
-    } else {
+    } else if (ep.out_mode == OUT_STORE_F32) {
       *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = v;
+    } else {
+      float* g = reinterpret_cast<float*>(ep.C) + idx;
+      *reinterpret_cast<f32x4*>(g) = *reinterpret_cast<const f32x4*>(g) + v;
     }
   }
 }
@@ -634,11 +638,33 @@ struct SplitPlan { int first; int s; size_t bytes; };
 template <int BM, int BN, int BKT, int WGS_PER_CU>
 SplitPlan plan_split(int M, int N, int K, int out_mode) {
   SplitPlan p{0, 0, 0};
-  if (out_mode == OUT_ACC_F32) return p;   // many rounds, and G must be added to exactly once
   const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   const int slots = kCus * WGS_PER_CU;
   const int rem = tiles % slots;
   const int nk = (K + BKT - 1) / BKT;
+  if (out_mode == OUT_ACC_F32) {
+    // A weight gradient: a long contraction into an output that may be smaller than the chip
+    // (6144 x 2048 is 192 tiles, 2048 x 2048 is 64).  With at most two rounds of tiles, ALL of
+    // them are cut into the s <= 8 ranges of k (16 k-steps or more each) that fill the rounds
+    // best; the fix-up kernel then adds the partial sums, in ascending k order, to the gradient
+    // exactly once.  Larger outputs keep the one-pass read-modify-write.
+    if (tiles >= 2 * slots) return p;
+    int best = 1;
+    double best_eff = (double)tiles / ((double)((tiles + slots - 1) / slots) * slots);
+    for (int s = 2; s <= 8 && nk / s >= 16; ++s) {
+      const long long wgs = (long long)tiles * s;
+      const double eff = (double)wgs / ((double)((wgs + slots - 1) / slots) * slots);
+      if (eff > best_eff + 0.05) { best_eff = eff; best = s; }
+    }
+    if (best < 2) return p;
+    const int per = (nk + best - 1) / best;
+    best = (nk + per - 1) / per;             // no empty part
+    if (best < 2) return p;
+    p.first = 0;
+    p.s = best;
+    p.bytes = (size_t)tiles * best * BM * BN * 4;
+    return p;
+  }
   if (rem == 0 || rem * 2 > slots) return p;
   int s = slots / rem;
   if (s > 8) s = 8;
@@ -670,6 +696,7 @@ hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   const bool split = g.workspace && sp.s >= 2 && sp.bytes <= g.workspace_bytes;
   if (split) {
     ep.split_first = sp.first; ep.split_s = sp.s; ep.split_ws = (float*)g.workspace;
+    ep.square_map = 0;                 // the fix-up kernel numbers tiles with tile_of
     grid = sp.first + (tiles - sp.first) * sp.s;
   }
   gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG, MINW><<<grid, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
@@ -716,10 +743,23 @@ bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why) {
 
 void set_gemm_variant(int v) { g_variant = v; }
 
+namespace {
+// The automatic tile choice: large tiles when they still give every CU work, smaller ones
+// otherwise.  An accumulating output (a weight gradient) with a long contraction also takes the
+// large tiles when cutting them along k fills the chip (plan_split) and the caller's scratch
+// holds the partial tiles; `scratch_bytes` = what the caller offers (SIZE_MAX: assume enough).
+bool use_large_tiles(int M, int N, int K, int out_mode, size_t scratch_bytes) {
+  const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  if (big_tiles >= 192) return true;
+  if (out_mode != OUT_ACC_F32) return false;
+  const SplitPlan sp = plan_split<256, 256, 64, 1>(M, N, K, out_mode);
+  return sp.s >= 2 && big_tiles * sp.s >= 192 && sp.bytes <= scratch_bytes;
+}
+}  // namespace
+
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, int out_mode) {
   // mirrors the automatic choice of launch_gemm_bf16
-  const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 192) return plan_split<256, 256, 64, 1>(M, N, K, out_mode).bytes;
+  if (use_large_tiles(M, N, K, out_mode, (size_t)-1)) return plan_split<256, 256, 64, 1>(M, N, K, out_mode).bytes;
   return plan_split<128, 128, 64, 2>(M, N, K, out_mode).bytes;
 }
 
@@ -734,9 +774,8 @@ hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
     case 7: return launch_layout<128, 128, 64, 2, 2, 2, true, 2>(g, s);
     default: break;
   }
-  // Large tiles when they still give every CU work; smaller ones otherwise.
-  const long long big_tiles = (long long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  if (big_tiles >= 192) return launch_layout<256, 256, 64, 2, 2, 4, true, 2>(g, s);
+  if (use_large_tiles(g.M, g.N, g.K, g.out_mode, g.workspace ? g.workspace_bytes : 0))
+    return launch_layout<256, 256, 64, 2, 2, 4, true, 2>(g, s);
   return launch_layout<128, 128, 64, 2, 2, 2, true, 2>(g, s);
 }
 

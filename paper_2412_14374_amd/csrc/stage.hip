@@ -227,6 +227,16 @@ size_t carve(jpp_stage& st, char* base) {
   }
   st.split_f = st.split_bytes ? take(st.split_bytes) : nullptr;
   st.split_b = st.split_bytes ? take(st.split_bytes) : nullptr;
+  // ... and for the weight-gradient GEMMs whose output is smaller than the chip: they contract
+  // over the tokens of a whole group and are cut along k
+  st.split_w_bytes = 0;
+  if (c.dtype == JPP_BF16) {
+    const int Kw = m.T * (int)G;
+    const int shapes[][2] = {{m.nqkv, m.d}, {m.d, m.nq}, {m.f1, m.d}, {m.d, m.f}, {c.loss_head ? m.vocab : 8, m.d}};
+    for (const auto& mn : shapes)
+      st.split_w_bytes = std::max(st.split_w_bytes, gemm_bf16_workspace_bytes(mn[0], mn[1], Kw, OUT_ACC_F32));
+  }
+  st.split_w = st.split_w_bytes ? take(st.split_w_bytes) : nullptr;
   return off;
 }
 
@@ -243,9 +253,15 @@ hipError_t gemm(const jpp_stage& st, hipStream_t s, int M, int N, int K, const v
                 const void* B, int ldb, bool bks, void* C, int ldc, int mode, const void* bias,
                 const void* residual) {
   GemmDesc g{M, N, K, A, lda, aks, B, ldb, bks, C, ldc, mode, bias, residual};
-  // one scratch per stream: launches on one stream are serial, the streams are not
-  g.workspace = s == st.cs ? st.split_f : (s == st.bs ? st.split_b : nullptr);
-  g.workspace_bytes = g.workspace ? st.split_bytes : 0;
+  // one scratch per stream: launches on one stream are serial, the streams are not.  The
+  // accumulating (weight-gradient) GEMMs, which one stream at a time launches, have their own.
+  if (mode == OUT_ACC_F32) {
+    g.workspace = st.split_w;
+    g.workspace_bytes = st.split_w ? st.split_w_bytes : 0;
+  } else {
+    g.workspace = s == st.cs ? st.split_f : (s == st.bs ? st.split_b : nullptr);
+    g.workspace_bytes = g.workspace ? st.split_bytes : 0;
+  }
   return st.cfg.dtype == JPP_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
 }
 

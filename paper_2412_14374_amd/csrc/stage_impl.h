@@ -127,6 +127,9 @@ struct jpp_stage {
   // GEMM split scratch, one per stream that launches store-mode GEMMs (forward, backward chain)
   char *split_f = nullptr, *split_b = nullptr;
   size_t split_bytes = 0;
+  // ... and for the accumulating weight-gradient GEMMs (one stream at a time launches those)
+  char* split_w = nullptr;
+  size_t split_w_bytes = 0;
 
   // boundary
   std::vector<const void*> inbox_x, inbox_cot;

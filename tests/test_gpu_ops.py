@@ -136,7 +136,10 @@ def test_gemm_bf16_split_along_k_with_scratch(M, N, K, aks, bks):
     bt, rt = dev(bias, torch.bfloat16), dev(res, torch.bfloat16)
     need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_STORE)
     assert need > 0                                           # these shapes are meant to split
-    assert B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_ACC_F32) == 0
+    need_acc = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_ACC_F32)
+    # accumulating outputs are cut when that fills at least a twentieth more of the chip with
+    # ranges of 16 k-steps or more: of these shapes only 63 tiles of 128 x 128 with 33 k-steps
+    assert (need_acc > 0) == ((M, N, K) == (1032, 776, 2056))
     ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device=DEV)
     a = (B.JPP_BF16, M, N, K, At.data_ptr(), lda, aks, Bt.data_ptr(), ldb, bks)
     Cb = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
@@ -153,6 +156,21 @@ def test_gemm_bf16_split_along_k_with_scratch(M, N, K, aks, bks):
     assert rel_l2(host(Cb), ref + bias[None, :] + res) < 4e-3
     assert torch.equal(Cs, Cu)                                # scratch too small: the unsplit launch
     assert bool(torch.isnan(ws[need // 4:]).all())            # nothing written past the stated size
+    if need_acc:
+        # the accumulating mode cut along k: the partial sums are added to C once per launch
+        wa = torch.full((need_acc // 4 + 64,), float("nan"), dtype=torch.float32, device=DEV)
+        Ca = torch.ones((M, N), dtype=torch.float32, device=DEV)
+        Cv = torch.ones((M, N), dtype=torch.float32, device=DEV)
+        Cw = torch.ones((M, N), dtype=torch.float32, device=DEV)
+        for _ in range(2):
+            B.jpp_op_gemm_ws(*a, Ca.data_ptr(), N, B.OUT_ACC_F32, None, None, wa.data_ptr(), need_acc, stream())
+        B.jpp_op_gemm_ws(*a, Cv.data_ptr(), N, B.OUT_ACC_F32, None, None, wa.data_ptr(), need_acc - 16, stream())
+        B.jpp_op_gemm(*a, Cw.data_ptr(), N, B.OUT_ACC_F32, None, None, stream())
+        torch.cuda.synchronize()
+        assert rel_l2(host(Ca), 1.0 + 2 * ref) < 1e-5
+        assert np.abs(host(Ca) - (1.0 + 2 * ref)).max() < 2e-3 * math.sqrt(K)
+        assert torch.equal(Cv, Cw)
+        assert bool(torch.isnan(wa[need_acc // 4:]).all())
 
 
 SPLIT_FULL = [
@@ -187,6 +205,43 @@ def test_gemm_split_full_shape_sampled_entries(name, M, N, K, aks, bks):
     got = Cc[mi, ni].double().cpu().numpy()
     assert rel_l2(got, ref) < 4e-3, name
     assert bool(torch.isfinite(Cc.float()).all())
+
+
+WGRAD_SPLIT_FULL = [
+    # weight gradients of the d = 2048 configuration over a group of 8 microbatches: outputs of 192 and
+    # 64 tiles of 256 x 256, every tile cut into four ranges of k
+    ("qkv wgrad", 6144, 2048, 65536), ("attn-out wgrad", 2048, 2048, 65536),
+]
+
+
+@pytest.mark.parametrize("name,M,N,K", WGRAD_SPLIT_FULL)
+def test_gemm_wgrad_split_full_shape_sampled_entries(name, M, N, K):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(M + N + K + 2)
+    A = (torch.randn((K, M), generator=g, device=DEV) * 0.01).to(torch.bfloat16)       # cotangents, k-strided
+    Bm = torch.randn((K, N), generator=g, device=DEV).to(torch.bfloat16)               # activations, k-strided
+    need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_ACC_F32)
+    assert need == (M // 256) * (N // 256) * 4 * 256 * 256 * 4
+    ws = torch.empty(need // 4, dtype=torch.float32, device=DEV)
+    G0 = torch.randn((M, N), generator=g, device=DEV)
+    outs = []
+    for _ in range(2):                                  # twice: the same bits (fixed order, no atomics)
+        G = G0.clone()
+        B.jpp_op_gemm_ws(B.JPP_BF16, M, N, K, A.data_ptr(), M, 1, Bm.data_ptr(), N, 1, G.data_ptr(), N, B.OUT_ACC_F32,
+                         None, None, ws.data_ptr(), need, stream())
+        torch.cuda.synchronize()
+        outs.append(G)
+    assert torch.equal(outs[0], outs[1])
+    rng = np.random.default_rng(2)
+    ms = np.concatenate([rng.integers(0, M, 4096), [0, 0, M - 1, M - 1, 255, 256, M - 256, M - 257]])
+    ns = np.concatenate([rng.integers(0, N, 4096), [0, N - 1, 0, N - 1, 255, 256, N - 256, N - 257]])
+    mi, ni = torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)
+    a_cols = A[:, mi].T.float().cpu().numpy().astype(np.float64)
+    b_cols = Bm[:, ni].T.float().cpu().numpy().astype(np.float64)
+    ref = np.einsum("sk,sk->s", a_cols, b_cols) + G0[mi, ni].double().cpu().numpy()
+    got = outs[0][mi, ni].double().cpu().numpy()
+    assert rel_l2(got, ref) < 1e-5, name
+    assert bool(torch.isfinite(outs[0]).all())
 
 
 def test_gemm_bf16_padded_leading_dimensions_do_not_touch_neighbours():
