@@ -143,9 +143,15 @@ class ClockSampler:
         return out
 
 
+def progress(msg):
+    """One line on stderr when a part of the run is done (stdout carries the JSON line only)."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def run_stage(w, steps, warmup, torch, B, inp, Stage, opt_kind=None, optimizer_name=None):
     """K timed steps of one configuration (a step = jpp_stage_zero_grads + jpp_stage_run of the
     whole task list, inputs resident in HBM).  Returns the figures of the bench line's top level."""
+    progress(f"{w.name}: wgrad_group {max(1, w.wgrad_group)}, {warmup} warm-up + {steps} timed steps")
     task_list = None
     if w.sched == inp.SCHED_GPIPE and w.V > 1:
         # GPipe on a circular placement: every forward of every owned stage, then every backward
@@ -160,6 +166,7 @@ def run_stage(w, steps, warmup, torch, B, inp, Stage, opt_kind=None, optimizer_n
     if opt_kind is not None:
         st.optimizer_bind(opt_kind)
     step_no = [0]
+    progress(f"  arena {arena_gb:.1f} GB, parameters and boundary tensors in HBM")
 
     def update():
         if opt_kind is not None:
@@ -172,6 +179,7 @@ def run_stage(w, steps, warmup, torch, B, inp, Stage, opt_kind=None, optimizer_n
         update()
     st.sync()
     torch.cuda.synchronize()
+    progress("  warm-up done")
     # per-step marks on the stage's compute stream (every run is joined back into it), recorded
     # without waiting: the host keeps enqueueing while the GPU works
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
@@ -187,6 +195,7 @@ def run_stage(w, steps, warmup, torch, B, inp, Stage, opt_kind=None, optimizer_n
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
     ms_per_step = dt / steps * 1e3
+    progress(f"  timed steps done: {ms_per_step:.1f} ms per step")
     per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
     flops_step = algorithmic_flops_per_microbatch(w) * w.n_microbatches
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -409,6 +418,24 @@ def bench_kernels(w, torch, B, inp):
     emit("activation fwd", f"{T}x{f}", ms, (6.0 if swiglu else 4.0) * T * f, "hbm")
     ms = timed(lambda: B.jpp_op_act_bwd(B.JPP_BF16, w.act, T, f, h.data_ptr(), da.data_ptr(), dh.data_ptr(), strm))
     emit("activation bwd", f"{T}x{f}", ms, (10.0 if swiglu else 6.0) * T * f, "hbm")
+    if not swiglu:
+        # the same two activations applied by the epilogues of the GEMMs around them
+        n2 = torch.randn(T, d, device=dev).to(bf)
+        W1 = (torch.randn(f, d, device=dev) * 0.02).to(bf)
+        b1 = torch.zeros(f, dtype=bf, device=dev)
+        need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, T, f, d, 0)
+        ws = torch.empty(max(need // 4, 4), dtype=torch.float32, device=dev)
+        ms = timed(lambda: B.jpp_op_gemm_gelu(T, f, d, n2.data_ptr(), d, 0, W1.data_ptr(), d, 0, h.data_ptr(), f,
+                                              b1.data_ptr(), w.act, 0, a_.data_ptr(), ws.data_ptr() if need else None,
+                                              need, strm))
+        emit("gemm ffn-up fwd with GeLU epilogue (h and a)", f"{T}x{f}x{d}", ms, 2.0 * T * f * d, "mfma")
+        del n2, W1
+        dy2 = torch.randn(T, d, device=dev).to(bf)
+        W2 = (torch.randn(d, f, device=dev) * 0.02).to(bf)
+        ms = timed(lambda: B.jpp_op_gemm_gelu(T, f, d, dy2.data_ptr(), d, 0, W2.data_ptr(), f, 1, dh.data_ptr(), f,
+                                              None, w.act, 1, h.data_ptr(), ws.data_ptr() if need else None, need, strm))
+        emit("gemm ffn-down dgrad with GeLU' epilogue (dh)", f"{T}x{f}x{d}", ms, 2.0 * T * f * d, "mfma")
+        del dy2, W2, ws
     del h, a_, da, dh
     if w.loss_head:
         # the last stage's head: logits (fp32), cross-entropy with its gradient (bf16), the two backward GEMMs
@@ -502,6 +529,9 @@ def main():
                     help="streams a run computes on: 3 = forward, input-gradient chain and weight-gradient GEMMs "
                          "on their own streams, 2 = forward + backward, 1 = everything on one; default: the "
                          "library picks 1 or 3 from the stage's GEMM sizes")
+    ap.add_argument("--fused-activation", type=int, choices=[0, 1, 2, 3], default=None,
+                    help="where GeLU is evaluated (jpp_set_fused_activation): bit 0 = in the FFN-up GEMM's epilogue, "
+                         "bit 1 = in the FFN-down input-gradient GEMM's; default: the library's (3)")
     ap.add_argument("--pipeline", action="store_true",
                     help="run the configuration's layers as a whole pipeline of P actors on this one GPU "
                          "(one layer-stack slice per actor, 1F1B lists, real stage-to-stage hand-offs) "
@@ -526,6 +556,7 @@ def main():
         sys.exit(2)
     w = inp.CONFIGS[a.config]
     B.jpp_set_stream_mode(-1 if a.streams is None else 3 - a.streams)
+    B.jpp_set_fused_activation(-1 if a.fused_activation is None else a.fused_activation)
     from dataclasses import replace
     kind = {"gpipe": inp.SCHED_GPIPE, "1f1b": inp.SCHED_1F1B, "interleaved": inp.SCHED_INTERLEAVED,
             None: w.sched}[a.schedule]
@@ -600,6 +631,7 @@ def main():
             out["other_configs"].append(brief(wc, run_stage(wc, 5, 2, torch, B, inp, Stage), 5, 2))
     if w.dtype == inp.DT_BF16:
         avg_ms, flops_per_launch = time_dominant_kernel(w, torch, B)
+        progress(f"dominant kernel timed: {avg_ms:.3f} ms per launch")
         shapes = wgrad_shapes(w)
         # L2 <-> fabric bytes per launch from the profiler, for the C4 shapes only: groups of 8 / per task
         traffic = {8: 29.8e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
@@ -618,6 +650,7 @@ def main():
                            / len(shapes)}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a.config, w)
+        progress(f"oracle timed on the host: {out['cpu_baseline']['seconds']:.1f} s")
     print(json.dumps(out))
 
 

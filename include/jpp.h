@@ -247,6 +247,18 @@ jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* st
  * other's cache when they run side by side, else 0, where overlap fills the gaps that short
  * kernels leave.  Results are identical in every mode. */
 void jpp_set_stream_mode(int mode);
+/* Process-wide, read by every task: where GeLU (either form, bf16 storage) is evaluated.
+ * Bit 0: by the epilogue of the FFN-up GEMM of a forward pass, which then stores h and
+ * a = gelu(h); bit 1: by the epilogue of the FFN-down input-gradient GEMM of a backward pass,
+ * which then stores dh = da * gelu'(h) and never da.  A clear bit leaves that direction to
+ * the element-wise kernel after the GEMM.  Default (and any negative value): 3.  On MI355X
+ * the choice moves the step of a GPT-3-175B-shaped stage (d 12288, 2048 tokens) by less than its run-to-run spread (all four values within
+ * 0.15 %): the epilogue's extra arithmetic and second store come when a whole round of tiles
+ * ends at once and no MFMA work is left to hide them, which costs about what the streaming
+ * kernel did; fusing saves that kernel's 0.4 GB (forward) and 0.6 GB (backward) of HBM
+ * traffic per layer and microbatch.  Results are identical for every value (both routes
+ * round h, a and da to bf16 at the same points and share the GeLU arithmetic). */
+void jpp_set_fused_activation(int mask);
 /* The mode (0, 1 or 2) that the next run of `st` uses under the current setting. */
 int jpp_stage_stream_mode(const jpp_stage* st);
 
@@ -346,6 +358,18 @@ jpp_status jpp_op_gemm_ws(int dtype, int M, int N, int K, const void* A, int lda
                           const void* B, int ldb, int b_kstrided, void* C, int ldc, int out_mode,
                           const void* bias, const void* residual, void* workspace,
                           size_t workspace_bytes, void* stream);
+
+/* The bf16 GEMM with GeLU fused into its epilogue, as the stage runs its feed-forward block
+ * (act: JPP_GELU or JPP_GELU_TANH; aux has the shape, type and leading dimension of C; bias and
+ * workspace as in jpp_op_gemm_ws, storage-type output).
+ *   backward = 0: C receives h = A B^T (+ bias) and aux receives gelu(h), evaluated on the stored
+ *                 (rounded) h: the bits of jpp_op_gemm followed by jpp_op_act_fwd.
+ *   backward = 1: aux holds h; the product, rounded to bf16, is the cotangent da of gelu(h) and C
+ *                 receives da * gelu'(h): the bits of jpp_op_gemm followed by jpp_op_act_bwd,
+ *                 without da ever being stored. */
+jpp_status jpp_op_gemm_gelu(int M, int N, int K, const void* A, int lda, int a_kstrided, const void* B, int ldb,
+                            int b_kstrided, void* C, int ldc, const void* bias, int act, int backward, void* aux,
+                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* Benchmarking knob: 0 (default) lets the library pick the bf16 GEMM tile configuration
  * from the problem size; 1..7 force one (tile M x N x K-stage, LDS stages, waves):

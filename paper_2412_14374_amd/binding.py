@@ -82,6 +82,7 @@ _SIGNATURES = {
     "jpp_last_error": (C.c_char_p, []),
     "jpp_set_gemm_variant": (None, [C.c_int]),
     "jpp_set_stream_mode": (None, [C.c_int]),
+    "jpp_set_fused_activation": (None, [C.c_int]),
     "jpp_stage_stream_mode": (C.c_int, [C.c_void_p]),
     "jpp_op_gemm_workspace_bytes": (C.c_size_t, [C.c_int] * 5),
     "jpp_op_gemm_ws": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
@@ -89,6 +90,9 @@ _SIGNATURES = {
                                                   C.c_void_p, C.c_size_t, C.c_void_p]),
     "jpp_op_gemm": (C.c_int, [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
                               C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "jpp_op_gemm_gelu": (C.c_int, [C.c_int] * 3 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                   C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                   C.c_size_t, C.c_void_p]),
     "jpp_op_attention_fwd": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 4),
     "jpp_op_attention_bwd": (C.c_int, [C.c_int] * 6 + [C.c_void_p] * 7),
     "jpp_op_norm_fwd": (C.c_int, [C.c_int] * 4 + [C.c_float] + [C.c_void_p] * 6),
@@ -340,6 +344,10 @@ def jpp_set_stream_mode(mode):
     lib().jpp_set_stream_mode(mode)
 
 
+def jpp_set_fused_activation(mask):
+    lib().jpp_set_fused_activation(mask)
+
+
 def jpp_stage_stream_mode(h):
     return lib().jpp_stage_stream_mode(h)
 
@@ -361,6 +369,12 @@ def jpp_op_gemm_ws(dtype, M, N, K, A, lda, a_ks, B, ldb, b_ks, Cp, ldc, out_mode
                    workspace_bytes, stream):
     _check(lib().jpp_op_gemm_ws(dtype, M, N, K, A, lda, int(a_ks), B, ldb, int(b_ks), Cp, ldc, out_mode, bias,
                                 residual, workspace, workspace_bytes, stream))
+
+
+def jpp_op_gemm_gelu(M, N, K, A, lda, a_ks, B, ldb, b_ks, Cp, ldc, bias, act, backward, aux, workspace,
+                     workspace_bytes, stream):
+    _check(lib().jpp_op_gemm_gelu(M, N, K, A, lda, int(a_ks), B, ldb, int(b_ks), Cp, ldc, bias, act, int(backward), aux,
+                                  workspace, workspace_bytes, stream))
 
 
 def jpp_op_attention_fwd(dtype, mb, seq, Hq, Hkv, hd, qkv, out, lse, stream):

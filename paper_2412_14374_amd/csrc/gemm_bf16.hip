@@ -108,7 +108,49 @@ struct Epilogue {
   int split_first; int split_s; float* split_ws;
   // 1: tile_of_square (outputs whose tile counts are multiples of 16 in both directions)
   int square_map;
+  // fused GeLU (GemmDesc::act) and its second tensor
+  int act; bf16* aux;
 };
+
+// Stores four consecutive outputs of a bf16 store-mode GEMM, applying the fused activation ACT:
+// forward, h goes to C and gelu(h), evaluated on the rounded h, to aux; backward, the rounded
+// value is da and C receives da * gelu'(h) with h read from aux.
+template <int ACT>
+__device__ inline void store_bf16x4_act(const Epilogue& ep, size_t idx, const f32x4& v, bf16x4 h = bf16x4{}) {
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+  bf16* c = reinterpret_cast<bf16*>(ep.C) + idx;
+  if constexpr (ACT == ACT_NONE) {
+    *reinterpret_cast<bf16x4*>(c) = o;
+  } else if constexpr (ACT == ACT_FWD_ERF || ACT == ACT_FWD_TANH) {
+    bf16x4 a;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) a[e] = (bf16)(ACT == ACT_FWD_ERF ? gelu_erf_fit((float)o[e]) : gelu_tanh((float)o[e]));
+    *reinterpret_cast<bf16x4*>(c) = o;
+    *reinterpret_cast<bf16x4*>(ep.aux + idx) = a;
+  } else {
+    bf16x4 d;   // h: the four values of aux at idx, loaded by the caller
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      d[e] = (bf16)((float)o[e] * (ACT == ACT_BWD_ERF ? gelu_erf_grad_fit((float)h[e]) : gelu_tanh_grad((float)h[e])));
+    *reinterpret_cast<bf16x4*>(c) = d;
+  }
+}
+// The same with the activation chosen at run time (the fix-up kernel of split tiles).
+__device__ inline void store_bf16x4_act_rt(const Epilogue& ep, size_t idx, const f32x4& v) {
+  switch (ep.act) {
+    case ACT_FWD_ERF: store_bf16x4_act<ACT_FWD_ERF>(ep, idx, v); break;
+    case ACT_FWD_TANH: store_bf16x4_act<ACT_FWD_TANH>(ep, idx, v); break;
+    case ACT_BWD_ERF:
+      store_bf16x4_act<ACT_BWD_ERF>(ep, idx, v, *reinterpret_cast<const bf16x4*>(ep.aux + idx));
+      break;
+    case ACT_BWD_TANH:
+      store_bf16x4_act<ACT_BWD_TANH>(ep, idx, v, *reinterpret_cast<const bf16x4*>(ep.aux + idx));
+      break;
+    default: store_bf16x4_act<ACT_NONE>(ep, idx, v); break;
+  }
+}
 
 struct Operand {
   const bf16* p; int ld; int rows;  // rows = M (for A) or N (for B)
@@ -278,7 +320,10 @@ __device__ inline void wait_loads_and_barrier() {
 }
 
 // MINW: waves per SIMD the register allocation must leave room for (1 = use the whole file).
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false, int MINW = 1>
+// ACT: the fused GeLU of the store-mode epilogue (ACT_NONE in all but the few instantiations
+// that the feed-forward block uses, so that the common kernels carry none of its code).
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false, int MINW = 1,
+          int ACT = ACT_NONE>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, int N, int K, Operand A, Operand B,
                                                                         Epilogue ep) {
   constexpr int NT = 64 * WM * WN;
@@ -556,6 +601,18 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
           prev[s] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(ep.C) + (size_t)m * ep.ldc + n);
       }
     }
+    // backward GeLU: the block's pre-activations are requested before the staging pass, so
+    // that their latency is spent there and not once per row step
+    constexpr bool kActBwd = ACT == ACT_BWD_ERF || ACT == ACT_BWD_TANH;
+    bf16x4 hpre[kActBwd ? kSteps : 1];
+    if constexpr (kActBwd) {
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        const int m = mbase + s * RPI + erow;
+        hpre[s] = bf16x4{};
+        if (n_ok && m < M) hpre[s] = *reinterpret_cast<const bf16x4*>(ep.aux + (size_t)m * ep.ldc + n);
+      }
+    }
     wave_lds_sync();  // the previous pass's reads are done before its region is rewritten
 #pragma unroll
     for (int j = 0; j < NI; ++j)
@@ -563,6 +620,17 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
       for (int r = 0; r < 16; ++r)
         stg[(8 * (r >> 2) + 4 * half + (r & 3)) * LDW + j * 32 + l32] = acc[i][j][r];
     wave_lds_sync();
+    if constexpr (ACT != ACT_NONE) {
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        const int m = mbase + s * RPI + erow;
+        if (!(n_ok && m < M)) continue;
+        f32x4 v = *reinterpret_cast<const f32x4*>(stg + (s * RPI + erow) * LDW + ecol);
+        v += bias4;
+        store_bf16x4_act<ACT>(ep, (size_t)m * ep.ldc + n, v, hpre[kActBwd ? s : 0]);
+      }
+      continue;
+    }
 #pragma unroll
     for (int s = 0; s < kSteps; ++s) {
       const int m = mbase + s * RPI + erow;
@@ -576,10 +644,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
         for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
       }
       if (ep.out_mode == OUT_STORE) {
-        bf16x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-        *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(ep.C) + idx) = o;
+        store_bf16x4_act<ACT_NONE>(ep, idx, v);
       } else if (ep.out_mode == OUT_STORE_F32) {
         *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = v;
       } else {
@@ -618,10 +683,7 @@ __global__ __launch_bounds__(256) void gemm_split_fixup_kernel(int M, int N, Epi
       for (int c = 0; c < 4; ++c) v[c] += (float)rv[c];
     }
     if (ep.out_mode == OUT_STORE) {
-      bf16x4 o;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) o[c] = (bf16)v[c];
-      *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(ep.C) + idx) = o;
+      store_bf16x4_act_rt(ep, idx, v);
     } else if (ep.out_mode == OUT_STORE_F32) {
       *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = v;
     } else {
@@ -679,14 +741,15 @@ SplitPlan plan_split(int M, int N, int K, int out_mode) {
   return p;
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false, int MINW = 1>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, bool AKS, bool BKS, bool VG = false, int MINW = 1,
+          int ACT = ACT_NONE>
 hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
   constexpr int NT = 64 * WM * WN;
   constexpr int kWgsPerCu = BM * BN >= 256 * 256 ? 1 : 2;
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   Operand A{(const bf16*)g.A, g.lda, g.M};
   Operand B{(const bf16*)g.B, g.ldb, g.N};
-  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual, 0, 0, nullptr, 0};
+  Epilogue ep{g.C, g.ldc, g.out_mode, (const bf16*)g.bias, (const bf16*)g.residual, 0, 0, nullptr, 0, ACT, (bf16*)g.aux};
   {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     ep.square_map = BM == 256 && BN == 256 && g.out_mode == OUT_ACC_F32 && tiles_m % 16 == 0 && tiles_n % 16 == 0;
@@ -699,7 +762,7 @@ hipError_t launch_cfg(const GemmDesc& g, hipStream_t s) {
     ep.square_map = 0;                 // the fix-up kernel numbers tiles with tile_of
     grid = sp.first + (tiles - sp.first) * sp.s;
   }
-  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG, MINW><<<grid, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
+  gemm_bf16_kernel<BM, BN, BKT, NS, WM, WN, AKS, BKS, VG, MINW, ACT><<<grid, NT, 0, s>>>(g.M, g.N, g.K, A, B, ep);
   if (split) {
     const long long quads = (long long)(tiles - sp.first) * (BM * BN / 4);
     const int blocks = (int)((quads + 255) / 256 < 4096 ? (quads + 255) / 256 : 4096);
@@ -738,6 +801,11 @@ bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why) {
     return false;
   }
   if (g.bias && ((uintptr_t)g.bias % 8) != 0) { why = "bias must be 8-byte aligned"; return false; }
+  if (g.act != ACT_NONE && (g.act < ACT_FWD_ERF || g.act > ACT_BWD_TANH || !g.aux || g.out_mode != OUT_STORE ||
+                            ((uintptr_t)g.aux % 8) != 0 || g.aux == g.C)) {
+    why = "a fused activation needs a storage-type output, and a second tensor of its shape that is not the output";
+    return false;
+  }
   return true;
 }
 
@@ -763,7 +831,41 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, int out_mode) {
   return plan_split<128, 128, 64, 2>(M, N, K, out_mode).bytes;
 }
 
+namespace {
+// The fused-GeLU instantiations: the two automatically chosen tile configurations, forward in
+// the forward layout (both operands k-contiguous), backward in the input-gradient layout.
+template <int BM, int BN, int WN, int MINW>
+hipError_t launch_act(const GemmDesc& g, hipStream_t s) {
+  switch (g.act) {
+    case ACT_FWD_ERF: return launch_cfg<BM, BN, 64, 2, 2, WN, false, false, true, MINW, ACT_FWD_ERF>(g, s);
+    case ACT_FWD_TANH: return launch_cfg<BM, BN, 64, 2, 2, WN, false, false, true, MINW, ACT_FWD_TANH>(g, s);
+    case ACT_BWD_ERF: return launch_cfg<BM, BN, 64, 2, 2, WN, false, true, true, MINW, ACT_BWD_ERF>(g, s);
+    default: return launch_cfg<BM, BN, 64, 2, 2, WN, false, true, true, MINW, ACT_BWD_TANH>(g, s);
+  }
+}
+}  // namespace
+
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
+  if (g.act != ACT_NONE) {
+    const bool fwd = g.act == ACT_FWD_ERF || g.act == ACT_FWD_TANH;
+    const bool layout_ok = !g.a_kstrided && g.b_kstrided == !fwd;
+    const bool tiles_ok = g_variant == 0 || g_variant == 6 || g_variant == 7;
+    if (g.out_mode == OUT_STORE && layout_ok && tiles_ok) {
+      const bool large = g_variant == 6 || (g_variant == 0 && use_large_tiles(g.M, g.N, g.K, g.out_mode, 0));
+      return large ? launch_act<256, 256, 4, 2>(g, s) : launch_act<128, 128, 2, 2>(g, s);
+    }
+    // another layout or a forced tile configuration: the plain GEMM, then the element-wise
+    // kernel (in place for the backward: C holds da, then dh) -- the same bits
+    GemmDesc plain = g;
+    plain.act = ACT_NONE;
+    plain.aux = nullptr;
+    hipError_t e = launch_gemm_bf16(plain, s);
+    if (e != hipSuccess) return e;
+    const int act = (g.act == ACT_FWD_ERF || g.act == ACT_BWD_ERF) ? JPP_GELU : JPP_GELU_TANH;
+    if (g.ldc != g.N) return hipErrorInvalidValue;   // the element-wise kernels take dense rows
+    return fwd ? launch_act_fwd(JPP_BF16, act, g.M, g.N, g.C, g.aux, s)
+               : launch_act_bwd(JPP_BF16, act, g.M, g.N, g.aux, g.C, g.C, s);
+  }
   switch (g_variant) {
     case 1: return launch_layout<256, 256, 32, 4, 2, 2>(g, s);
     case 2: return launch_layout<256, 256, 32, 5, 2, 2>(g, s);

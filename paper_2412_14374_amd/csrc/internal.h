@@ -34,7 +34,15 @@ struct GemmDesc {
   // split along k and summed by a second kernel.  Must not be shared by concurrent launches.
   void* workspace = nullptr;
   size_t workspace_bytes = 0;
+  // Optional fused activation (bf16 GEMM, out_mode OUT_STORE; `aux` has the shape, type and
+  // leading dimension of C).  ACT_FWD_*: C receives h = the product (+ bias), aux receives
+  // a = gelu(h) evaluated on the stored (rounded) h.  ACT_BWD_*: the product, rounded to the
+  // storage type, is the cotangent da of a; C receives dh = da * gelu'(h) with h read from aux.
+  // Either way the values are the bits that the separate activation kernels produce.
+  int act = 0;
+  void* aux = nullptr;
 };
+enum { ACT_NONE = 0, ACT_FWD_ERF = 1, ACT_FWD_TANH = 2, ACT_BWD_ERF = 3, ACT_BWD_TANH = 4 };
 hipError_t launch_gemm_f32(const GemmDesc& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s);
 bool gemm_bf16_shape_ok(const GemmDesc& g, std::string& why);

@@ -80,6 +80,24 @@ jpp_status jpp_op_gemm_ws(int dtype, int M, int N, int K, const void* A, int lda
   return e == hipSuccess ? JPP_OK : fail_hip(e, "gemm launch");
 }
 
+jpp_status jpp_op_gemm_gelu(int M, int N, int K, const void* A, int lda, int a_kstrided, const void* B, int ldb,
+                            int b_kstrided, void* C, int ldc, const void* bias, int act, int backward, void* aux,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  if (!A || !B || !C || !aux) return fail(JPP_EINVAL, "null operand");
+  if (M < 1 || N < 1 || K < 1) return fail(JPP_EINVAL, "sizes must be positive");
+  if (act != JPP_GELU && act != JPP_GELU_TANH) return fail(JPP_EINVAL, "act must be JPP_GELU or JPP_GELU_TANH");
+  if (workspace && ((uintptr_t)workspace % 16) != 0) return fail(JPP_EINVAL, "workspace must be 16-byte aligned");
+  GemmDesc g{M, N, K, A, lda, a_kstrided != 0, B, ldb, b_kstrided != 0, C, ldc, OUT_STORE, bias, nullptr};
+  g.workspace = workspace;
+  g.workspace_bytes = workspace ? workspace_bytes : 0;
+  g.act = backward ? (act == JPP_GELU ? ACT_BWD_ERF : ACT_BWD_TANH) : (act == JPP_GELU ? ACT_FWD_ERF : ACT_FWD_TANH);
+  g.aux = aux;
+  std::string why;
+  if (!gemm_bf16_shape_ok(g, why)) return fail(JPP_EINVAL, why);
+  hipError_t e = launch_gemm_bf16(g, (hipStream_t)stream);
+  return e == hipSuccess ? JPP_OK : fail_hip(e, "gemm launch");
+}
+
 static jpp_status attn_check(int dtype, int mb, int seq, int Hq, int Hkv, int hd) {
   if (!dtype_ok(dtype)) return fail(JPP_EINVAL, "bad dtype");
   if (mb < 1 || seq < 1 || Hq < 1 || Hkv < 1 || hd < 1) return fail(JPP_EINVAL, "sizes must be positive");

@@ -295,22 +295,6 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __res
 // a' = Phi(h) + h * phi(h).  Tanh form: 0.5 h (1 + tanh(k0 (h + k1 h^3))).
 // SwiGLU on h = [gate | up]: a = silu(gate) * up, silu(t) = t * sigmoid(t),
 // silu'(t) = sigmoid(t) * (1 + t * (1 - sigmoid(t))).
-__device__ inline float gelu_erf(float h) { return 0.5f * h * (1.f + erff(h * 0.70710678118654752f)); }
-__device__ inline float gelu_erf_grad(float h) {
-  const float cdf = 0.5f * (1.f + erff(h * 0.70710678118654752f));
-  const float pdf = 0.3989422804014327f * __expf(-0.5f * h * h);
-  return cdf + h * pdf;
-}
-__device__ inline float gelu_tanh(float h) {
-  const float u = 0.7978845608028654f * (h + 0.044715f * h * h * h);
-  return 0.5f * h * (1.f + tanhf(u));
-}
-__device__ inline float gelu_tanh_grad(float h) {
-  const float u = 0.7978845608028654f * (h + 0.044715f * h * h * h);
-  const float th = tanhf(u);
-  const float du = 0.7978845608028654f * (1.f + 3.f * 0.044715f * h * h);
-  return 0.5f * (1.f + th) + 0.5f * h * (1.f - th * th) * du;
-}
 __device__ inline float sigmoidf(float t) { return 1.f / (1.f + __expf(-t)); }
 
 // A thread owns one 16-byte column chunk and walks the rows kActRows at a time: the loads of
@@ -341,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void act_fwd_kernel(const T* __restrict__
         for (int e = 0; e < N; ++e) {
           const float t = v[j].get(e);
           if (ACT == JPP_SWIGLU) o.set(e, t * sigmoidf(t) * u[j].get(e));
-          else if (ACT == JPP_GELU) o.set(e, gelu_erf(t));
+          else if (ACT == JPP_GELU) o.set(e, gelu_erf_of<T>(t));
           else o.set(e, gelu_tanh(t));
         }
         store_chunk(a + (size_t)(r0 + j) * f + (size_t)c * N, o);
@@ -385,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void act_bwd_kernel(const T* __restrict__
           Chunk<T> o;
 #pragma unroll
           for (int e = 0; e < N; ++e)
-            o.set(e, d[j].get(e) * (ACT == JPP_GELU ? gelu_erf_grad(v[j].get(e)) : gelu_tanh_grad(v[j].get(e))));
+            o.set(e, d[j].get(e) * (ACT == JPP_GELU ? gelu_erf_grad_of<T>(v[j].get(e)) : gelu_tanh_grad(v[j].get(e))));
           store_chunk(out, o);
         }
       }

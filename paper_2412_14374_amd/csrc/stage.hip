@@ -33,6 +33,7 @@ namespace jpp {
 
 static thread_local std::string g_last_error;
 static int g_stream_mode = -1;
+static int g_fused_act = 3;   // jpp_set_fused_activation
 
 jpp_status fail(jpp_status code, const std::string& msg) {
   g_last_error = msg;
@@ -251,8 +252,10 @@ void ev_destroy(Event& e) { if (e.ev) (void)hipEventDestroy(e.ev); e.ev = nullpt
 
 hipError_t gemm(const jpp_stage& st, hipStream_t s, int M, int N, int K, const void* A, int lda, bool aks,
                 const void* B, int ldb, bool bks, void* C, int ldc, int mode, const void* bias,
-                const void* residual) {
+                const void* residual, int act = ACT_NONE, void* aux = nullptr) {
   GemmDesc g{M, N, K, A, lda, aks, B, ldb, bks, C, ldc, mode, bias, residual};
+  g.act = act;
+  g.aux = aux;
   // one scratch per stream: launches on one stream are serial, the streams are not.  The
   // accumulating (weight-gradient) GEMMs, which one stream at a time launches, have their own.
   if (mode == OUT_ACC_F32) {
@@ -263,6 +266,15 @@ hipError_t gemm(const jpp_stage& st, hipStream_t s, int M, int N, int K, const v
     g.workspace_bytes = g.workspace ? st.split_bytes : 0;
   }
   return st.cfg.dtype == JPP_BF16 ? launch_gemm_bf16(g, s) : launch_gemm_f32(g, s);
+}
+
+// GeLU (either form) in bf16 storage can be applied by the epilogue of the GEMM that produces
+// its argument (forward: h and a = gelu(h) from the FFN-up product) or its cotangent (backward:
+// dh = da * gelu'(h) from the FFN-down input gradient, da never stored); which of the two is
+// in use is jpp_set_fused_activation's.  SwiGLU pairs columns f apart and fp32 storage has no
+// fused epilogue: both keep the element-wise kernels.
+bool act_fused(const jpp_stage& st, bool backward) {
+  return st.cfg.dtype == JPP_BF16 && st.cfg.act != JPP_SWIGLU && (g_fused_act & (backward ? 2 : 1));
 }
 
 hipError_t attention_fwd(const jpp_stage& st, hipStream_t s, const AttnDesc& a) {
@@ -306,9 +318,14 @@ hipError_t layer_forward(jpp_stage& st, hipStream_t s, int v, int l, const Layer
              OUT_STORE, pptr(st, v, o.bo), x));
   K_TRY(launch_norm_fwd(dt, c.norm, m.T, m.d, c.norm_eps, w.x1, pptr(st, v, o.ln2_g),
                         pptr(st, v, o.ln2_b), w.n2, (float*)(w.stats2), s));
-  K_TRY(gemm(st, s, m.T, m.f1, m.d, w.n2, m.d, false, pptr(st, v, o.w1), m.d, false, w.h, m.f1,
-             OUT_STORE, pptr(st, v, o.b1), nullptr));
-  K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, w.h, w.a, s));
+  if (act_fused(st, false)) {
+    K_TRY(gemm(st, s, m.T, m.f1, m.d, w.n2, m.d, false, pptr(st, v, o.w1), m.d, false, w.h, m.f1,
+               OUT_STORE, pptr(st, v, o.b1), nullptr, c.act == JPP_GELU ? ACT_FWD_ERF : ACT_FWD_TANH, w.a));
+  } else {
+    K_TRY(gemm(st, s, m.T, m.f1, m.d, w.n2, m.d, false, pptr(st, v, o.w1), m.d, false, w.h, m.f1,
+               OUT_STORE, pptr(st, v, o.b1), nullptr));
+    K_TRY(launch_act_fwd(dt, c.act, m.T, m.f, w.h, w.a, s));
+  }
   if (y)
     K_TRY(gemm(st, s, m.T, m.d, m.f, w.a, m.f, false, pptr(st, v, o.w2), m.f, false, y, m.d, OUT_STORE,
                pptr(st, v, o.b2), w.x1));
@@ -406,9 +423,14 @@ hipError_t enqueue_backward(jpp_stage& st, int v, int i, Slot& slot, const char*
     // FFN down projection
     if (wg_members) K_TRY(wgrad(st, m.d, m.f, K, wdy, m.d, g.a, m.f, gptr(st, v, o.w2)));
     if (o.b2 >= 0 && wg_members) K_TRY(launch_bias_grad(dt, K, m.d, wdy, m.d, gptr(st, v, o.b2), st.partial, s));
-    K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, st.da, m.f, OUT_STORE, nullptr,
-               nullptr));
-    K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, w.h, st.da, dh, s));
+    if (act_fused(st, true)) {
+      K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, dh, m.f, OUT_STORE, nullptr,
+                 nullptr, c.act == JPP_GELU ? ACT_BWD_ERF : ACT_BWD_TANH, w.h));
+    } else {
+      K_TRY(gemm(st, s, m.T, m.f, m.d, dy, m.d, false, pptr(st, v, o.w2), m.f, true, st.da, m.f, OUT_STORE, nullptr,
+                 nullptr));
+      K_TRY(launch_act_bwd(dt, c.act, m.T, m.f, w.h, st.da, dh, s));
+    }
     // FFN up projection
     if (wg_members) K_TRY(wgrad(st, m.f1, m.d, K, wdh, m.f1, g.n2, m.d, gptr(st, v, o.w1)));
     if (o.b1 >= 0 && wg_members) K_TRY(launch_bias_grad(dt, K, m.f1, wdh, m.f1, gptr(st, v, o.b1), st.partial, s));
@@ -970,6 +992,7 @@ jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* o,
   return JPP_OK;
 }
 
+void jpp_set_fused_activation(int mask) { jpp::g_fused_act = mask < 0 ? 3 : (mask & 3); }
 void jpp_set_stream_mode(int mode) { jpp::g_stream_mode = mode < 0 || mode > 2 ? -1 : mode; }
 
 int jpp_stage_stream_mode(const jpp_stage* st) {

@@ -244,6 +244,61 @@ def test_gemm_wgrad_split_full_shape_sampled_entries(name, M, N, K):
     assert bool(torch.isfinite(outs[0]).all())
 
 
+GELU_FUSED_SHAPES = [
+    # M, N, K, with workspace (the last round of tiles cut along k, GeLU applied by the fix-up kernel)
+    (136, 72, 200, False), (264, 520, 328, False), (1032, 776, 2056, True), (2048, 12288, 2048, True),
+]
+
+
+@pytest.mark.parametrize("M,N,K,with_ws", GELU_FUSED_SHAPES)
+@pytest.mark.parametrize("act", [inp.ACT_GELU, inp.ACT_GELU_TANH])
+def test_gemm_with_fused_gelu_gives_the_bits_of_the_separate_kernels(M, N, K, with_ws, act):
+    """The feed-forward block as the stage runs it: forward, one GEMM writes h = x W1^T + b1 and
+    a = gelu(h); backward, one GEMM writes dh = (dy W2) * gelu'(h) without storing dy W2.
+    Both against the unfused sequence (jpp_op_gemm, then jpp_op_act_fwd / _bwd): identical
+    bits, and against the definition in float64."""
+    rng = np.random.default_rng(M + N + K + act)
+    x = inp.round_to_dtype(rng.standard_normal((M, K)), inp.DT_BF16)
+    w = inp.round_to_dtype(rng.standard_normal((N, K)) * 0.05, inp.DT_BF16)
+    b = inp.round_to_dtype(rng.standard_normal(N) * 0.1, inp.DT_BF16)
+    xt, wt, bt = dev(x, torch.bfloat16), dev(w, torch.bfloat16), dev(b, torch.bfloat16)
+    need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_STORE) if with_ws else 0
+    assert (need > 0) == with_ws
+    ws = torch.empty(max(need // 4, 4), dtype=torch.float32, device=DEV)
+    wsp = ws.data_ptr() if need else None
+    z = lambda: torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    h0, a0, h1, a1 = z(), z(), z(), z()
+    B.jpp_op_gemm_ws(B.JPP_BF16, M, N, K, xt.data_ptr(), K, 0, wt.data_ptr(), K, 0, h0.data_ptr(), N, B.OUT_STORE,
+                     bt.data_ptr(), None, wsp, need, stream())
+    B.jpp_op_act_fwd(B.JPP_BF16, act, M, N, h0.data_ptr(), a0.data_ptr(), stream())
+    B.jpp_op_gemm_gelu(M, N, K, xt.data_ptr(), K, 0, wt.data_ptr(), K, 0, h1.data_ptr(), N, bt.data_ptr(), act, 0,
+                       a1.data_ptr(), wsp, need, stream())
+    torch.cuda.synchronize()
+    assert torch.equal(h0.view(torch.int16), h1.view(torch.int16))
+    assert torch.equal(a0.view(torch.int16), a1.view(torch.int16))
+    spec = so.StageSpec(n_layers=1, d_model=8, n_q_heads=1, n_kv_heads=1, head_dim=8, d_ffn=N, seq_len=1,
+                        microbatch=1, act=act)
+    href = x @ w.T + b[None, :]
+    assert rel_l2(host(h1), href) < 4e-3
+    assert rel_l2(host(a1), so.act_forward(spec, host(h1))) < 4e-3
+    # backward: dy [M, K] times W2 [K, N] (k-strided, as the stage reads it), h from above
+    dy = inp.round_to_dtype(rng.standard_normal((M, K)) * 0.01, inp.DT_BF16)
+    w2 = inp.round_to_dtype(rng.standard_normal((K, N)) * 0.05, inp.DT_BF16)
+    dyt, w2t = dev(dy, torch.bfloat16), dev(w2, torch.bfloat16)
+    da0, dh0, dh1 = z(), z(), z()
+    B.jpp_op_gemm_ws(B.JPP_BF16, M, N, K, dyt.data_ptr(), K, 0, w2t.data_ptr(), N, 1, da0.data_ptr(), N, B.OUT_STORE,
+                     None, None, wsp, need, stream())
+    B.jpp_op_act_bwd(B.JPP_BF16, act, M, N, h0.data_ptr(), da0.data_ptr(), dh0.data_ptr(), stream())
+    B.jpp_op_gemm_gelu(M, N, K, dyt.data_ptr(), K, 0, w2t.data_ptr(), N, 1, dh1.data_ptr(), N, None, act, 1,
+                       h1.data_ptr(), wsp, need, stream())
+    torch.cuda.synchronize()
+    assert torch.equal(dh0.view(torch.int16), dh1.view(torch.int16))
+    assert rel_l2(host(dh1), so.act_backward(spec, host(h1), dy @ w2)) < 6e-3
+    with pytest.raises(B.JppError):          # the second tensor must not be the output
+        B.jpp_op_gemm_gelu(M, N, K, dyt.data_ptr(), K, 0, w2t.data_ptr(), N, 1, dh1.data_ptr(), N, None, act, 1,
+                           dh1.data_ptr(), wsp, need, stream())
+
+
 def test_gemm_bf16_padded_leading_dimensions_do_not_touch_neighbours():
     """Sub-matrix views: ld > row length.  The cells outside C's view must stay untouched."""
     rng = np.random.default_rng(0)

@@ -209,6 +209,43 @@ def assert_same_bits(a, b):
         assert np.array_equal(a[3], b[3])
 
 
+@pytest.mark.parametrize("variant", [0, 6])
+def test_every_fused_activation_setting_matches_oracle_with_identical_bits(variant):
+    """jpp_set_fused_activation: GeLU by the element-wise kernels (0), by the FFN-up GEMM's
+    epilogue in the forward pass (1), by the FFN-down input-gradient GEMM's in the backward
+    pass (2), or both (3, the default); with the tile configuration the library picks for the
+    twin (128-tiles) and with the benchmark's 256-tiles forced.  Every setting against the
+    oracle (Section 3.1: the tasks' arithmetic) and the four against each other bit for bit."""
+    from dataclasses import replace
+    w = replace(TWINS["C4"], P=2, rank=0)
+    assert w.act == inp.ACT_GELU and w.dtype == inp.DT_BF16
+    spec = spec_of(w)
+    params, x, cot, tg = inp.draw_stage_inputs(w, so.layer_param_shapes(spec), None, seed=5, perturb=True)
+    ref, bits = None, []
+    try:
+        B.jpp_set_gemm_variant(variant)
+        for mask in (0, 1, 2, 3):
+            B.jpp_set_fused_activation(mask)
+            st = Stage(w)
+            st.set_params_host(params)
+            st.bind(x, cot, tg)
+            st.zero_grads()
+            st.run()
+            got = st.results()
+            if ref is None:
+                ref = so.run_task_list(spec, params, oracle_tasks(st.tasks), x, cot, tg)
+            worst, err = compare(w, got, ref)
+            print("variant", variant, "mask", mask, "worst", worst, err)
+            assert err <= TOL[w.dtype], (mask, worst, err)
+            bits.append(raw_outputs(st, w))
+            st.close()
+    finally:
+        B.jpp_set_fused_activation(-1)
+        B.jpp_set_gemm_variant(0)
+    for other in bits[1:]:
+        assert_same_bits(bits[0], other)
+
+
 STREAM_MODE_CASES = {**{n: (TWINS[n], 5) for n in TWINS},
                      **{"fp32-" + n: (None, 11) for n in FP32_VARIANTS}}
 

@@ -5,6 +5,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from oracle import schedules as osch
@@ -200,3 +202,29 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_normal_tail_fit_reproduces_the_kernel_coefficients_and_error():
+    """The coefficient list of normal_cdf_fit in device_utils.h is what normal_tail_fit.py
+    computes, and the fp32 evaluation of that polynomial stays within 3e-7 of the cumulative
+    normal (so within 5e-7 of the erf-form GeLU over [-8, 8]), far below bf16 rounding."""
+    import importlib.util
+    import re
+    from scipy.special import erf
+    here = os.path.dirname(os.path.abspath(__file__))
+    csrc = os.path.join(here, "..", "paper_2412_14374_amd", "csrc")
+    spec = importlib.util.spec_from_file_location("normal_tail_fit", os.path.join(csrc, "normal_tail_fit.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    coef = mod.fit()
+    src = open(os.path.join(csrc, "device_utils.h")).read()
+    body = src[src.index("inline float normal_cdf_fit"):src.index("inline float gelu_erf_fit")]
+    in_kernel = [float(x) for x in re.findall(r"(-?\d\.\d+e[+-]\d+)f", body)]
+    assert len(in_kernel) == len(coef) == 9
+    for have, want in zip(in_kernel, coef[::-1]):       # Horner: highest power first
+        assert np.float32(have) == np.float32(want), (have, want)
+    h = np.linspace(-8, 8, 200001).astype(np.float32)
+    exact = 0.5 * (1 + erf(h.astype(np.float64) / np.sqrt(2.0)))
+    phi = mod.normal_cdf_f32(coef, h)
+    assert np.abs(phi - exact).max() < 3e-7
+    assert np.abs(h * phi - h * exact).max() < 5e-7
