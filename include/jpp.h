@@ -374,9 +374,10 @@ jpp_status jpp_op_gemm_gelu(int M, int N, int K, const void* A, int lda, int a_k
 /* Benchmarking knob: 0 (default) lets the library pick the bf16 GEMM tile configuration
  * from the problem size; 1..7 force one (tile M x N x K-stage, LDS stages, waves):
  * 1 = 256x256x32, 4, 4;  2 = 256x256x32, 5, 4;  3 = 128x128x32, 4, 4;  4 = 256x256x64, 2, 4;
- * 5 = 256x256x64, 2, 8 (all with HBM->LDS direct loads);  6 = 256x256x64, 2, 8 and
- * 7 = 128x128x64, 2, 4 with register-staged loads (0 picks 6 for large outputs, else 7).
- * Process-wide; results are identical for every value. */
+ * 5 = 256x256x64, 2, 8 (all with HBM->LDS direct loads);  6 = 256x256x64, 2, 8,
+ * 7 = 128x128x64, 2, 4 and 8 = 256x256x64, 2, 4 (one wave per SIMD, 128x128 wave tiles with
+ * the accumulators in the accumulation registers) with register-staged loads (0 picks 6 for
+ * large outputs, else 7).  Process-wide; results are identical for every value. */
 void jpp_set_gemm_variant(int variant);
 
 /* Causal self-attention over a fused qkv tensor [mb*seq, (Hq + 2*Hkv)*hd] (q heads, then

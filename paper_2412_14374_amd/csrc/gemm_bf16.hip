@@ -13,7 +13,10 @@
 //
 // Design (one workgroup = one BM x BN tile of C):
 //  * The default is a 256 x 256 x 64 tile, eight waves (wave tile 128 x 64), two LDS stages
-//    of 64 KB.  A 64-wide stage makes every row of a k-contiguous tile one full 128-byte
+//    of 64 KB.  (Four waves with 128 x 128 wave tiles, forced variant 8, read a third less
+//    from LDS per MFMA and run at a 10 % higher clock under the board's power limit, but a
+//    lone wave per SIMD has nobody to hide its waits behind: 73 % matrix-pipe occupancy
+//    against 84 %, 1.24-1.28 against 1.31-1.33 PFLOP/s.)  A 64-wide stage makes every row of a k-contiguous tile one full 128-byte
 //    cache line (32-wide stages fetch every line twice and lose more than a deeper ring
 //    gains), and 256 x 256 is the largest tile whose accumulators fit the register file --
 //    the L2 -> CU path is the busiest resource beside the matrix pipe, so bytes per flop matter most.
@@ -26,7 +29,12 @@
 //    so the swizzle is applied to WHICH global chunk each lane fetches.  Its loads are inline
 //    assembly and the cross-wave hand-over is an explicit "s_waitcnt vmcnt(loads still
 //    allowed in flight); s_barrier": the compiler's wait-count pass cannot tell the stages
-//    apart and would wait for every load in flight.  It is slower on every shape measured.
+//    apart and would wait for every load in flight.  The lane's byte offset of every load is
+//    computed once per kernel; a k-tile costs the scalar arithmetic of its descriptor.  It is
+//    slower on every shape measured (1.03-1.19 against 1.31 PFLOP/s at the feed-forward
+//    shapes), also when every tile is requested at the very start of its iteration: with
+//    all operands resident in L2 the eight-wave form reaches 1.39, so what it lacks is the
+//    second iteration of flight time that the registers give a load.
 //  * LDS layouts, the same for both loaders, bank-conflict free by an XOR swizzle of the
 //    16-byte chunk index:
 //      k-contiguous tile: LDS [rows][BKT] bf16; fragment = one 16-byte read per lane.
@@ -188,6 +196,24 @@ struct KContigTile {
     const uint32_t off = (k0 + kc * 8 < K) ? (uint32_t)(row * op.ld + kc * 8) * 2u : kOOB;
     dma16(rs, tile + blk * 1024, off);
   }
+  // The same load split into what depends on the tile (the descriptor: base and range) and what
+  // does not (the lane's byte offset, computed once per kernel): lane_offset() leaves out the
+  // k-range predicate, so issue_fast() serves every k-tile that lies wholly inside K.
+  __device__ static inline uint32_t lane_offset(const Operand& op, int r0, int i) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
+    const int blk = i * (NT / 64) + wave;
+    const int row = blk * kRowsPerInstr + lane / CPR;
+    const int kc = (lane % CPR) ^ swz(row);
+    return (uint32_t)(row * op.ld + kc * 8) * 2u;
+  }
+  __device__ static inline bool fast_ok(int k0, int K) { return k0 + BKT <= K; }
+  __device__ static inline i32x4 tile_rsrc(const Operand& op, int r0, int k0, int K) {
+    return make_rsrc(op.p + (size_t)r0 * op.ld + k0, ((long long)(op.rows - r0) * op.ld - k0) * 2);
+  }
+  __device__ static inline void issue_fast(const i32x4& rs, uint32_t tile, int i, uint32_t voff) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    dma16(rs, tile + (i * (NT / 64) + wave) * 1024, voff);
+  }
   // Register-staged variant: chunk i*NT + tid of the tile; 8 consecutive lanes read one
   // 128-byte row segment, the swizzle is applied when the chunk is written to LDS.
   __device__ static inline u32x4 load_one(const Operand& op, int r0, int k0, int K, int i) {
@@ -233,6 +259,23 @@ struct KStridedTile {
     const int c = (lane % CPR) ^ ((k & 3) << 2);
     const uint32_t off = (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
     dma16(rs, tile + blk * 1024, off);
+  }
+  // tile-independent lane offset (the row-range predicate does not depend on k) and the
+  // descriptor of one k-tile, whose range makes k-rows at and beyond K read as zero
+  __device__ static inline uint32_t lane_offset(const Operand& op, int r0, int i) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
+    const int blk = i * (NT / 64) + wave;
+    const int k = blk * kRowsPerInstr + lane / CPR;
+    const int c = (lane % CPR) ^ ((k & 3) << 2);
+    return (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
+  }
+  __device__ static inline bool fast_ok(int, int) { return true; }
+  __device__ static inline i32x4 tile_rsrc(const Operand& op, int r0, int k0, int K) {
+    return make_rsrc(op.p + (size_t)k0 * op.ld + r0, ((long long)(K - k0) * op.ld - r0) * 2);
+  }
+  __device__ static inline void issue_fast(const i32x4& rs, uint32_t tile, int i, uint32_t voff) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    dma16(rs, tile + (i * (NT / 64) + wave) * 1024, voff);
   }
   __device__ static inline u32x4 load_one(const Operand& op, int r0, int k0, int K, int i) {
     const int cidx = i * NT + threadIdx.x;
@@ -375,13 +418,26 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, half = lane >> 5;
 
+  // A wave tile of more than 128 accumulator registers leaves no room for them beside the
+  // operands in the 256 ordinary registers: they live in the accumulation half of the file.
+  // Defined there by an MFMA of zeros and pinned, or the register allocator would carry them
+  // through the loop in ordinary registers and copy every tile in and out around each MFMA.
+  constexpr bool kAccInAgprs = MINW == 1 && MI * NI * 16 > 128;
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < NI; ++j)
+    for (int j = 0; j < NI; ++j) {
+      if constexpr (kAccInAgprs) {
+        const bf16x8 z = {};
+        const f32x16 zero = {};
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(z, z, zero, 0, 0, 0);
+        asm volatile("" : "+a"(acc[i][j]));
+      } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      }
+    }
 
   int a_base[MI], b_base[NI];
 #pragma unroll
@@ -391,9 +447,24 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
 
   bf16x8 af[2][MI], bfr[2][NI];
   // one load of k-tile kt (A loads first, then B loads) into the stage at LDS address dst
+  // (the lane offsets are computed once; a k-tile that reaches beyond K takes the general form)
+  uint32_t a_voff[VG ? 1 : TA::kLoads], b_voff[VG ? 1 : TB::kLoads];
+  if constexpr (!VG) {
+#pragma unroll
+    for (int l = 0; l < TA::kLoads; ++l) a_voff[l] = TA::lane_offset(A, m0, l);
+#pragma unroll
+    for (int l = 0; l < TB::kLoads; ++l) b_voff[l] = TB::lane_offset(B, n0, l);
+  }
   auto issue_load = [&](int kt, uint32_t dst, int idx) {
-    if (idx < TA::kLoads) TA::issue_one(A, m0, (kbeg + kt) * BKT, K, dst, idx);
-    else TB::issue_one(B, n0, (kbeg + kt) * BKT, K, dst + kABytes, idx - TA::kLoads);
+    const int k0 = (kbeg + kt) * BKT;
+    if (idx < TA::kLoads) {
+      if (TA::fast_ok(k0, K)) TA::issue_fast(TA::tile_rsrc(A, m0, k0, K), dst, idx, a_voff[VG ? 0 : idx]);
+      else TA::issue_one(A, m0, k0, K, dst, idx);
+    } else {
+      const int j = idx - TA::kLoads;
+      if (TB::fast_ok(k0, K)) TB::issue_fast(TB::tile_rsrc(B, n0, k0, K), dst + kABytes, j, b_voff[VG ? 0 : j]);
+      else TB::issue_one(B, n0, k0, K, dst + kABytes, j);
+    }
   };
   auto mfma_row = [&](int set, int i) {
 #pragma unroll
@@ -402,6 +473,19 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
   };
   // the part of k-step kk's fragments that is fetched while MFMA row i runs
   auto read_frag_part = [&](const char* tile, int kk, int set, int i) {
+    if constexpr (MI == NI && MI % 2 == 0) {
+      // square wave tile, one wave per SIMD: nothing hides a late fragment, so the column
+      // fragments (all needed by the next k-step's first group) are read first, two per group,
+      // then the row fragments in the order the groups use them: every fragment is requested
+      // at least two groups (8 MFMAs) before its first use
+      const int first = 2 * i;
+#pragma unroll
+      for (int q = first; q < first + 2; ++q) {
+        if (q < NI) bfr[set][q] = TB::frag(tile, b_base[q], kk);
+        else af[set][q - NI] = TA::frag(tile, a_base[q - NI], kk);
+      }
+      return;
+    }
     af[set][i] = TA::frag(tile, a_base[i], kk);
 #pragma unroll
     for (int j = 0; j < NI; ++j)
@@ -413,7 +497,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
   // the matrix pipe: the loads of tile kt+NS-1 are spread over the first kSpread groups of
   // iteration kt, and the fragment reads of k-step kk+1 over the groups of k-step kk.
   constexpr int kGroups = KSTEPS * MI;
-  constexpr int kSpread = NS == 2 ? kGroups / 2 : kGroups;   // with 2 stages the tile is needed at the end
+  constexpr int kSpread = NS == 2 ? 4 : kGroups;   // with 2 stages the tile is needed at the end: request it at once
   constexpr int LPG = (kLoadsPerStage + kSpread - 1) / kSpread;
   // loads of the refill tile issued before the barrier of an iteration
   constexpr int kGroupsBeforeBarrier = (KSTEPS - 1) * MI + MI / 2;
@@ -874,6 +958,7 @@ hipError_t launch_gemm_bf16(const GemmDesc& g, hipStream_t s) {
     case 5: return launch_layout<256, 256, 64, 2, 2, 4, false, 2>(g, s);
     case 6: return launch_layout<256, 256, 64, 2, 2, 4, true, 2>(g, s);
     case 7: return launch_layout<128, 128, 64, 2, 2, 2, true, 2>(g, s);
+    case 8: return launch_layout<256, 256, 64, 2, 2, 2, true, 1>(g, s);
     default: break;
   }
   if (use_large_tiles(g.M, g.N, g.K, g.out_mode, g.workspace ? g.workspace_bytes : 0))

@@ -73,7 +73,7 @@ def test_gemm_bf16_all_layouts_and_epilogues(M, N, K, aks, bks):
     assert rel_l2(host(Cb), ref + bias[None, :] + res) < 4e-3  # one bf16 rounding of the result
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("aks,bks", [(0, 0), (0, 1), (1, 1), (1, 0)])
 def test_gemm_bf16_every_tile_configuration_gives_the_same_bits(variant, aks, bks):
     """The automatic choice depends on the shape, so each configuration is forced in turn on
