@@ -566,20 +566,38 @@ def main():
     group = a.wgrad_group if a.wgrad_group is not None else (1 if a.remat or a.pipeline else min(8, w.n_microbatches))
     w = replace(w, remat=1 if a.remat else 0, sched=kind, wgrad_group=group)
     if a.kernel_only:
-        # references for the profiler's counters: a 1 GiB copy (every read misses every cache: the
-        # scale of FETCH_SIZE / WRITE_SIZE and the read latency of HBM) and 16 copies of the same
-        # 64 MiB (larger than the L2s together, far smaller than the 256 MB last-level cache: the
-        # read latency when that cache answers)
-        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
+        # References for the profiler's counters.  Bandwidth-bound: a 1 GiB copy (every read
+        # misses every cache: the scale of FETCH_SIZE / WRITE_SIZE) and 16 copies of the same
+        # 64 MiB (larger than the L2s together, far smaller than the 256 MB last-level cache).
+        # Latency-bound (a few thousand 128-byte reads in flight, no queueing): 4096 random rows
+        # of 128 bytes gathered (jpp_op_embed_fwd) from a 4 GiB table, of which that cache can
+        # hold a sixteenth -- HBM answers -- and from the 64 MiB buffer right after its copies --
+        # the last-level cache answers.  TCC_EA0_RDREQ_LEVEL / TCC_EA0_RDREQ of each is the
+        # mean time a read request of the L2s spends outside them under that condition.
+        dev = "cuda:0"
+        strm = torch.cuda.current_stream().cuda_stream
+        rows_out = torch.empty(4096, 64, dtype=torch.bfloat16, device=dev)
+
+        def gather(table, n_rows):
+            ids = torch.randint(0, n_rows, (4096,), dtype=torch.int32, device=dev)
+            torch.cuda.synchronize()
+            B.jpp_op_embed_fwd(B.JPP_BF16, 4096, 64, n_rows, ids.data_ptr(), table.data_ptr(), rows_out.data_ptr(), strm)
+            torch.cuda.synchronize()
+
+        table = torch.ones(1 << 31, dtype=torch.bfloat16, device=dev)         # 4 GiB
+        gather(table, (1 << 31) // 64)
+        del table
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)           # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-        small = torch.ones(1 << 25, dtype=torch.bfloat16, device="cuda:0")    # 64 MiB
+        small = torch.ones(1 << 25, dtype=torch.bfloat16, device=dev)         # 64 MiB
         small2 = torch.empty_like(small)
         for _ in range(16):
             small2.copy_(small)
         torch.cuda.synchronize()
+        gather(small, (1 << 25) // 64)
         del small, small2
         avg_ms, flops = time_dominant_kernel(w, torch, B)
         print(json.dumps({"kernel_only": True, "avg_launch_ms": avg_ms, "flops_per_launch": flops,
@@ -634,7 +652,7 @@ def main():
         progress(f"dominant kernel timed: {avg_ms:.3f} ms per launch")
         shapes = wgrad_shapes(w)
         # L2 <-> fabric bytes per launch from the profiler, for the C4 shapes only: groups of 8 / per task
-        traffic = {8: 29.8e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
+        traffic = {8: 30.6e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
         ach = flops_per_launch / (avg_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel<..., k-strided A, k-strided B> "
                            "(weight gradient with fused fp32 accumulate)",
@@ -645,7 +663,10 @@ def main():
                            # not read in this run: the counters need the profiler (one pass each)
                            "traffic_source": ("profiles/gemm_wgrad_c4_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE, then "
                                               "WRITE_SIZE, of `bench.py --kernel-only`, scaled by the same counters "
-                                              "of a 1 GiB copy") if traffic else None,
+                                              "of a 1 GiB copy; bytes between the L2s and the fabric, of which the "
+                                              "256 MB last-level cache serves at least three quarters (mean read "
+                                              "time 600 L2 cycles against 520 / 867 for that cache / HBM idle)")
+                           if traffic else None,
                            "algorithmic_bytes_per_launch": sum(8.0 * m * n + 2.0 * k * (m + n) for m, n, k in shapes)
                            / len(shapes)}
     if not a.no_cpu_baseline:
