@@ -74,19 +74,22 @@ def time_dominant_kernel(w, torch, B, reps=3):
             A = (torch.randn((K, M), device="cuda:0") * w.cot_std).to(torch.bfloat16)
             Bm = torch.randn((K, N), device="cuda:0").to(torch.bfloat16)
             C = torch.zeros((M, N), dtype=torch.float32, device="cuda:0")
+            # with the scratch the executor gives it (outputs of few tiles are cut along k)
+            need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_ACC_F32)
+            ws = torch.empty(max(need // 4, 4), dtype=torch.float32, device="cuda:0")
             args = (B.JPP_BF16, M, N, K, A.data_ptr(), M, 1, Bm.data_ptr(), N, 1, C.data_ptr(), N, B.OUT_ACC_F32,
-                    None, None, s.cuda_stream)
-            B.jpp_op_gemm(*args)
+                    None, None, ws.data_ptr() if need else None, need, s.cuda_stream)
+            B.jpp_op_gemm_ws(*args)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(s)
             for _ in range(reps):
-                B.jpp_op_gemm(*args)
+                B.jpp_op_gemm_ws(*args)
             e1.record(s)
             s.synchronize()
             total_ms += e0.elapsed_time(e1)
             total_flops += reps * 2.0 * M * N * K
             n += reps
-            del A, Bm, C
+            del A, Bm, C, ws
     avg_ms = total_ms / n
     return avg_ms, total_flops / n
 
@@ -324,7 +327,7 @@ def cpu_baseline(config, w):
                       f"{what}); {flops / 1e9:.0f} algorithmic GFLOP; the workload's rate is extrapolated by FLOP count"}
 
 
-def bench_kernels(w, torch, B, inp):
+def bench_kernels(w, torch, B, inp, fixed_reps=False):
     """Every kernel of one layer (forward and backward) alone on the device at the
     configuration's shapes: milliseconds, achieved rate and fraction of the roofline that bounds
     it (MFMA peak for GEMMs and attention with the counted FLOPs, HBM peak for the row-wise and
@@ -345,15 +348,23 @@ def bench_kernels(w, torch, B, inp):
             for _ in range(30):
                 fn()
             warm[0] = True
-        fn(); fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+
+        def once(n):
+            fn(); fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        ms = once(reps)
+        if ms * reps < 20.0 and not fixed_reps:
+            # a short kernel: five launches are over before the queue is full and the clock has
+            # settled; time 20 ms of back-to-back launches instead, as a step issues them
+            ms = once(min(2000, int(20.0 / ms) + 1))
+        return ms
 
     def emit(name, shape, ms, work, bound):
         peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBS
@@ -460,7 +471,12 @@ def bench_kernels(w, torch, B, inp):
                                                   row_loss.data_ptr(), loss.data_ptr(), strm))
         emit("cross-entropy (loss + dz)", f"{T}x{V}", ms, 6.0 * T * V, "hbm")
         emit("gemm head dgrad", f"{T}x{d}x{V}", gemm(T, d, V, dz, V, 0, Wh, d, 1, dn, 0), 2.0 * T * V * d, "mfma")
-        emit("gemm head wgrad", f"{V}x{d}x{T}", gemm(V, d, T, dz, V, 1, nf, d, 1, G, 2), 2.0 * T * V * d, "mfma")
+        # the head's weight gradient contracts over its group like the layers' (dz and the
+        # normalised activations of the group's members are contiguous in the stash)
+        del z, dz, nf
+        dzg = torch.zeros(Tg, V, dtype=bf, device=dev).normal_(0, 1e-3)
+        nfg = torch.randn(Tg, d, device=dev).to(bf)
+        emit("gemm head wgrad", f"{V}x{d}x{Tg}", gemm(V, d, Tg, dzg, V, 1, nfg, d, 1, G, 2), 2.0 * Tg * V * d, "mfma")
 
 
 def bench_pipeline(a, w, torch, B, inp):
@@ -525,6 +541,9 @@ def main():
     ap.add_argument("--kernels", action="store_true",
                     help="time every kernel of one layer alone at the configuration's shapes and print one "
                          "JSON line per kernel with its rate against its own roofline")
+    ap.add_argument("--fixed-reps", action="store_true",
+                    help="with --kernels: 2 + 5 launches per kernel whatever their length (keeps a counter pass of "
+                         "the profiler short); by default kernels shorter than 4 ms are timed over 20 ms of launches")
     ap.add_argument("--streams", type=int, choices=[1, 2, 3], default=None,
                     help="streams a run computes on: 3 = forward, input-gradient chain and weight-gradient GEMMs "
                          "on their own streams, 2 = forward + backward, 1 = everything on one; default: the "
@@ -604,7 +623,7 @@ def main():
                           "tflops": flops / avg_ms / 1e9}))
         return
     if a.kernels:
-        return bench_kernels(w, torch, B, inp)
+        return bench_kernels(w, torch, B, inp, a.fixed_reps)
     if a.pipeline:
         return bench_pipeline(a, w, torch, B, inp)
     opt_kind = {None: None, "sgd": B.JPP_OPT_SGD, "adamw": B.JPP_OPT_ADAMW}[a.optimizer]

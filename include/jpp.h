@@ -243,7 +243,7 @@ jpp_status jpp_stage_apply_gradients(jpp_stage* st, const jpp_optimizer_step* st
  * overlap with the forward stream); 1: both on one library-owned stream; 2: everything on
  * compute_stream.  -1 (default): chosen per stage from its size: 2 when the layer's
  * smallest GEMM (the attention output projection, 2 T d n_q_heads head_dim flop) has at
- * least 1e11 flop, because kernels that fill the whole device on their own only disturb each
+ * least 5e10 flop, because kernels that fill the whole device on their own only disturb each
  * other's cache when they run side by side, else 0, where overlap fills the gaps that short
  * kernels leave.  Results are identical in every mode. */
 void jpp_set_stream_mode(int mode);

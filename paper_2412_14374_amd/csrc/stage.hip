@@ -998,7 +998,7 @@ void jpp_set_stream_mode(int mode) { jpp::g_stream_mode = mode < 0 || mode > 2 ?
 int jpp_stage_stream_mode(const jpp_stage* st) {
   if (jpp::g_stream_mode >= 0 || !st) return std::max(0, jpp::g_stream_mode);
   const jpp::Dims& m = st->dm;
-  return 2.0 * m.T * m.d * m.nq >= 1e11 ? 2 : 0;
+  return 2.0 * m.T * m.d * m.nq >= 5e10 ? 2 : 0;
 }
 
 int jpp_stage_peak_in_flight(const jpp_stage* st) { return st ? st->peak_in_flight : -1; }
