@@ -345,12 +345,12 @@ jpp_status jpp_op_gemm(int dtype, int M, int N, int K, const void* A, int lda, i
                        const void* bias, const void* residual, void* stream);
 
 /* jpp_op_gemm with a scratch buffer (device, fp32, 16-byte aligned, caller-owned, not shared
- * by launches that may overlap).  The bf16 path uses it in two cases.  Store modes: when the
+ * by launches that may overlap).  The bf16 path uses it in two cases.  Every mode: when the
  * last round of output tiles would fill at most half of the GPU, those tiles are cut into 2..8
  * ranges of k, the partial tiles go to the scratch and a second kernel sums them in ascending k
- * order and applies bias / residual / rounding.  Accumulating mode (out_mode 2): when the whole
- * output is at most two rounds of tiles (a weight gradient smaller than the chip with a long
- * contraction), every tile is cut the same way and the second kernel adds the sum to C, once.
+ * order and applies bias / residual / rounding (or, out_mode 2, adds the sum to C, once).
+ * Accumulating mode (out_mode 2) only: when the whole output is at most two rounds of tiles
+ * (a weight gradient smaller than the chip with a long contraction), every tile is cut.
  * jpp_op_gemm_workspace_bytes returns the bytes a shape needs (0: never split); with less (or
  * NULL) the launch is the unsplit one.  The result does not depend on timing either way. */
 size_t jpp_op_gemm_workspace_bytes(int dtype, int M, int N, int K, int out_mode);

@@ -793,8 +793,10 @@ SplitPlan plan_split(int M, int N, int K, int out_mode) {
     // (6144 x 2048 is 192 tiles, 2048 x 2048 is 64).  With at most two rounds of tiles, ALL of
     // them are cut into the s <= 8 ranges of k (16 k-steps or more each) that fill the rounds
     // best; the fix-up kernel then adds the partial sums, in ascending k order, to the gradient
-    // exactly once.  Larger outputs keep the one-pass read-modify-write.
-    if (tiles >= 2 * slots) return p;
+    // exactly once.  Larger outputs keep the one-pass read-modify-write for their full rounds
+    // and have a last round that is at most half full cut like a store-mode output's (below:
+    // 50304 x 4096, a vocabulary's gradient, is 12.3 rounds).
+    if (tiles < 2 * slots) {
     int best = 1;
     double best_eff = (double)tiles / ((double)((tiles + slots - 1) / slots) * slots);
     for (int s = 2; s <= 8 && nk / s >= 16; ++s) {
@@ -810,6 +812,7 @@ SplitPlan plan_split(int M, int N, int K, int out_mode) {
     p.s = best;
     p.bytes = (size_t)tiles * best * BM * BN * 4;
     return p;
+    }
   }
   if (rem == 0 || rem * 2 > slots) return p;
   int s = slots / rem;

@@ -211,6 +211,9 @@ WGRAD_SPLIT_FULL = [
     # weight gradients of the d = 2048 configuration over a group of 8 microbatches: outputs of 192 and
     # 64 tiles of 256 x 256, every tile cut into four ranges of k
     ("qkv wgrad", 6144, 2048, 65536), ("attn-out wgrad", 2048, 2048, 65536),
+    # a vocabulary's weight gradient (one microbatch of it): 197 x 16 tiles are 12.3 rounds, the 80 tiles
+    # of the last round are cut into three ranges of k, all others accumulate in one pass
+    ("head wgrad", 50304, 4096, 4096),
 ]
 
 
@@ -221,7 +224,8 @@ def test_gemm_wgrad_split_full_shape_sampled_entries(name, M, N, K):
     A = (torch.randn((K, M), generator=g, device=DEV) * 0.01).to(torch.bfloat16)       # cotangents, k-strided
     Bm = torch.randn((K, N), generator=g, device=DEV).to(torch.bfloat16)               # activations, k-strided
     need = B.jpp_op_gemm_workspace_bytes(B.JPP_BF16, M, N, K, B.OUT_ACC_F32)
-    assert need == (M // 256) * (N // 256) * 4 * 256 * 256 * 4
+    tiles = -(-M // 256) * (N // 256)
+    assert need == (tiles * 4 if tiles < 512 else (tiles % 256) * 3) * 256 * 256 * 4
     ws = torch.empty(need // 4, dtype=torch.float32, device=DEV)
     G0 = torch.randn((M, N), generator=g, device=DEV)
     outs = []
@@ -233,8 +237,11 @@ def test_gemm_wgrad_split_full_shape_sampled_entries(name, M, N, K):
         outs.append(G)
     assert torch.equal(outs[0], outs[1])
     rng = np.random.default_rng(2)
-    ms = np.concatenate([rng.integers(0, M, 4096), [0, 0, M - 1, M - 1, 255, 256, M - 256, M - 257]])
-    ns = np.concatenate([rng.integers(0, N, 4096), [0, N - 1, 0, N - 1, 255, 256, N - 256, N - 257]])
+    # (tiles are numbered along bands of 8 tile rows, so the last tiles of a launch, the ones a
+    # tail split cuts, are its last rows: a quarter of the samples come from the last 1024 rows)
+    ms = np.concatenate([rng.integers(0, M, 4096), rng.integers(max(0, M - 1024), M, 1024),
+                         [0, 0, M - 1, M - 1, 255, 256, M - 256, M - 257]])
+    ns = np.concatenate([rng.integers(0, N, 4096 + 1024), [0, N - 1, 0, N - 1, 255, 256, N - 256, N - 257]])
     mi, ni = torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)
     a_cols = A[:, mi].T.float().cpu().numpy().astype(np.float64)
     b_cols = Bm[:, ni].T.float().cpu().numpy().astype(np.float64)
