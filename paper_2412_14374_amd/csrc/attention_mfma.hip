@@ -174,6 +174,36 @@ __device__ inline bf16x8 global_frag(const bf16* base, int ld, int row, bool val
   if (!valid) return z;
   return *reinterpret_cast<const bf16x8*>(base + (size_t)row * ld + kd * 16 + half * 8);
 }
+// Stores a wave's 32 x 128 result, held transposed in four accumulator tiles (register r of lane
+// (l32, half) in tile dt is column 32 dt + 8 (r / 4) + 4 half + r % 4 of row l32), times the
+// lane's `scale`, as bf16 rows: rows row0 .. row0 + 31 of `base` (row pitch ld elements), those
+// below `n_rows` only.  The lanes' own 8-byte pieces would make every store instruction touch
+// 32 rows; they go through `stage` (8 KiB of LDS that only this wave uses at this point, chunk
+// c of row r at chunk c ^ (r & 15): no bank conflict either way) and leave as whole rows, four
+// rows of 256 bytes per instruction.
+__device__ inline void store_rows_bf16(char* stage, const f32x16 (&acc)[4], float scale, bf16* base, size_t ld,
+                                       int row0, int n_rows, int lane) {
+  const int l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      bf16x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (bf16)(acc[dt][4 * gq + e] * scale);
+      const int c = (dt * 4 + gq) ^ (l32 & 15);
+      *reinterpret_cast<bf16x4*>(stage + l32 * 256 + c * 16 + half * 8) = v;
+    }
+  wave_lds_sync();
+  const int c = lane & 15;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const int r = 4 * p + (lane >> 4);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((c ^ (r & 15)) << 4));
+    if (row0 + r < n_rows) *reinterpret_cast<u32x4*>(base + (size_t)(row0 + r) * ld + c * 8) = v;
+  }
+  wave_lds_sync();   // the region may be rewritten (the next tensor of this wave)
+}
 // B operand for k-step s2 (0 or 1) of a 32-row accumulator tile: registers 8*s2 .. 8*s2+7.
 __device__ inline bf16x8 acc_frag(const f32x16& a, int s2) {
   bf16x8 p;
@@ -311,20 +341,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_mfma_kernel(const bf16* 
     }
   }
   const float ltot = l + __shfl_xor(l, 32, 64);
-  if (qrow < seq) {
-    const float inv = 1.f / ltot;
-    bf16* orow = out + (tok0 + qrow) * ((size_t)Hq * HD) + (size_t)h * HD;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[dt][4 * gq + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * gq + 4 * half) = v;
-      }
-    if (half == 0) lse[((size_t)b * Hq + h) * seq + qrow] = (m + log2f(ltot)) * kLn2;
-  }
+  if (qrow < seq && half == 0) lse[((size_t)b * Hq + h) * seq + qrow] = (m + log2f(ltot)) * kLn2;
+  __syncthreads();   // every wave is done with the tiles: LDS becomes the staging area of the stores
+  store_rows_bf16(lds + wave * 8192, o, 1.f / ltot, out + tok0 * ((size_t)Hq * HD) + (size_t)h * HD, (size_t)Hq * HD,
+                  qw0, seq, lane);
 }
 
 // ---- backward: D = rowsum(dO * O) ----------------------------------------------------------
@@ -360,8 +380,8 @@ __global__ __launch_bounds__(kThreads) void attn_delta_kernel(const bf16* __rest
 // dS_i = P_i (dP_i - D); C(i): dV^T += dO_i^T P_i, dK^T += Q_i^T dS_i (16 MFMAs).
 // A wave has its SIMD to itself (the dK / dV accumulators fill half of the register file), so
 // nothing hides an LDS read that is waited for right before its MFMA: every fragment is
-// requested two MFMA pairs ahead (a ring of three), and scheduling barriers pin the order
-// "MFMA, one softmax element, MFMA, one softmax element".  On the tiles that cross the diagonal
+// requested four MFMA pairs ahead (a ring of five that runs through all four phases), and
+// scheduling barriers pin the order "MFMA, one softmax element, MFMA, one softmax element".  On the tiles that cross the diagonal
 // (`diag`, uniform over the wave) P and dS of a half are masked in a pass of their own before
 // the half's C phase: query 32 i + 8 (r / 4) + (r % 4) + 4 half of the tile is hidden from this
 // lane's key when that index, without the lane's 4 half, is below `first_q`.
@@ -384,9 +404,22 @@ __device__ __forceinline__ void dkv_step(const char* q_tile, const char* do_tile
     s[i][r] = p;
     dp[i][r] = p * (dp[i][r] - delta_v[i][r >> 2][r & 3]);
   };
-  // fragment rings: a fragment is requested kAhead MFMA pairs before the pair that uses it
+  // Fragment rings.  The 32 MFMA pairs of a step -- A(0), A(1), C(0), C(1), eight pairs each --
+  // form ONE sequence: pair n multiplies the fragments requested kAhead pairs earlier, across
+  // the phase boundaries (none of them depends on anything a phase computes), so only the
+  // step's first pairs wait for LDS.
   constexpr int kAhead = 4, kRing = kAhead + 1;
   bf16x8 fq[kRing], fd[kRing];
+  auto fetch = [&](int n) {
+    const int ph = n >> 3, k = n & 7;
+    if (ph < 2) {          // A(ph): rows of Q / dO, k-step k
+      fq[n % kRing] = row_frag(q_tile, ph, k, l32, half);
+      fd[n % kRing] = row_frag(do_tile, ph, k, l32, half);
+    } else {               // C(ph - 2): transposed, d block k & 3, k-step 2 (ph - 2) + (k >> 2)
+      fd[n % kRing] = trans_frag(do_tile, to, k & 3, 2 * (ph - 2) + (k >> 2));
+      fq[n % kRing] = trans_frag(q_tile, to, k & 3, 2 * (ph - 2) + (k >> 2));
+    }
+  };
   auto mask = [&](int i) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
@@ -395,52 +428,40 @@ __device__ __forceinline__ void dkv_step(const char* q_tile, const char* do_tile
   // A(i); `between(n)` runs after MFMA n of the phase, n = 0..15
   auto phase_a = [&](int i, auto&& between) {
 #pragma unroll
-    for (int kd = 0; kd < kAhead; ++kd) {
-      fq[kd] = row_frag(q_tile, i, kd, l32, half);
-      fd[kd] = row_frag(do_tile, i, kd, l32, half);
-    }
-#pragma unroll
     for (int kd = 0; kd < 8; ++kd) {
-      if (kd + kAhead < 8) {
-        fq[(kd + kAhead) % kRing] = row_frag(q_tile, i, kd + kAhead, l32, half);
-        fd[(kd + kAhead) % kRing] = row_frag(do_tile, i, kd + kAhead, l32, half);
-      }
+      const int n = 8 * i + kd;
+      if (n + kAhead < 32) fetch(n + kAhead);
       __builtin_amdgcn_sched_barrier(0);
-      s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[kd % kRing], kf[kd], kd == 0 ? kZero16 : s[i], 0, 0, 0);
+      s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n % kRing], kf[kd], kd == 0 ? kZero16 : s[i], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       between(2 * kd);
       __builtin_amdgcn_sched_barrier(0);
-      dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[kd % kRing], vf[kd], kd == 0 ? kZero16 : dp[i], 0, 0, 0);
+      dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[n % kRing], vf[kd], kd == 0 ? kZero16 : dp[i], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       between(2 * kd + 1);
     }
   };
   // C(i): k-steps 2 i and 2 i + 1 (the 16 queries each of P_i / dS_i), four d blocks each
   auto phase_c = [&](int i, auto&& between) {
-#pragma unroll
-    for (int m = 0; m < kAhead; ++m) {
-      fd[m] = trans_frag(do_tile, to, m & 3, 2 * i + (m >> 2));
-      fq[m] = trans_frag(q_tile, to, m & 3, 2 * i + (m >> 2));
-    }
     bf16x8 pf, dsf;
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
+      const int n = 16 + 8 * i + m;
       const int dt = m & 3, s2 = m >> 2;
-      if (m + kAhead < 8) {
-        fd[(m + kAhead) % kRing] = trans_frag(do_tile, to, (m + kAhead) & 3, 2 * i + ((m + kAhead) >> 2));
-        fq[(m + kAhead) % kRing] = trans_frag(q_tile, to, (m + kAhead) & 3, 2 * i + ((m + kAhead) >> 2));
-      }
+      if (n + kAhead < 32) fetch(n + kAhead);
       if (dt == 0) { pf = acc_frag(s[i], s2); dsf = acc_frag(dp[i], s2); }
       __builtin_amdgcn_sched_barrier(0);
-      dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[m % kRing], pf, dv[dt], 0, 0, 0);
+      dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[n % kRing], pf, dv[dt], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       between(2 * m);
       __builtin_amdgcn_sched_barrier(0);
-      dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[m % kRing], dsf, dk[dt], 0, 0, 0);
+      dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n % kRing], dsf, dk[dt], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       between(2 * m + 1);
     }
   };
+#pragma unroll
+  for (int n = 0; n < kAhead; ++n) fetch(n);
   phase_a(0, [&](int) {});
   load_stat(0, 0);
   phase_a(1, [&](int n) {
@@ -500,8 +521,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
     kf[kd] = global_frag(kbase, ld, krow, krow < seq, kd, half);
     vf[kd] = global_frag(vbase, ld, krow, krow < seq, kd, half);
   }
-#pragma unroll
-  for (int kd = 0; kd < 8; ++kd) { settle(kf[kd]); settle(vf[kd]); }
+  // (these loads are settled below, after the first tiles' loads have been issued: the two
+  // latencies of a workgroup's start then overlap)
   // The accumulators start as the result of an MFMA (0 * 0 + 0) rather than of a zero fill, and
   // are pinned once: they then live in the accumulation registers from here to the epilogue.  A
   // tile that ordinary arithmetic defines is kept in architectural registers instead and copied,
@@ -550,6 +571,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
     if (threadIdx.x < 64) { lse_s[j & 1][threadIdx.x] = lse_r * kLog2e; delta_s[j & 1][threadIdx.x] = delta_r; }
   };
   issue(0);
+#pragma unroll
+  for (int kd = 0; kd < 8; ++kd) { settle(kf[kd]); settle(vf[kd]); }
   publish(0);
   for (int j = 0; j < n_steps; ++j) {
     const int qt0 = (first_tile + j % per_head) * 64;
@@ -584,20 +607,10 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkv_mfma_kernel(
     }
     return;
   }
-  if (krow < seq) {
-    bf16* dkrow = dqkv + (tok0 + krow) * ld + (size_t)(Hq + g) * HD;
-    bf16* dvrow = dkrow + (size_t)Hkv * HD;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        bf16x4 a, c;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { a[e] = (bf16)(dk[dt][4 * gq + e] * scale); c[e] = (bf16)dv[dt][4 * gq + e]; }
-        *reinterpret_cast<bf16x4*>(dkrow + dt * 32 + 8 * gq + 4 * half) = a;
-        *reinterpret_cast<bf16x4*>(dvrow + dt * 32 + 8 * gq + 4 * half) = c;
-      }
-  }
+  __syncthreads();   // every wave is done with the tiles: LDS becomes the staging area of the stores
+  bf16* dkbase = dqkv + tok0 * ld + (size_t)(Hq + g) * HD;
+  store_rows_bf16(lds + wave * 8192, dk, scale, dkbase, (size_t)ld, kw0, seq, lane);
+  store_rows_bf16(lds + wave * 8192, dv, 1.f, dkbase + (size_t)Hkv * HD, (size_t)ld, kw0, seq, lane);
 }
 
 // Sums the per-query-head partial dK / dV rows of a kv head in ascending head order, scales dK
@@ -740,18 +753,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_mfma_kernel(
       }
     }
   }
-  if (q_ok) {
-    bf16* dqrow = dqkv + (tok0 + qrow) * ld + (size_t)h * HD;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16)(dq[dt][4 * gq + e] * scale);
-        *reinterpret_cast<bf16x4*>(dqrow + dt * 32 + 8 * gq + 4 * half) = v;
-      }
-  }
+  __syncthreads();   // every wave is done with the tiles: LDS becomes the staging area of the stores
+  store_rows_bf16(lds + wave * 8192, dq, scale, dqkv + tok0 * ld + (size_t)h * HD, (size_t)ld, qw0, seq, lane);
 }
 
 }  // namespace
