@@ -93,6 +93,21 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc_v(const void* p, long long by
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)n, 0x00020000);
 }
 
+// The same from a byte count that is known to fit (what a tile can touch, see records() of the
+// tile classes): no 64-bit compares, which this target only has as vector instructions.
+__device__ inline i32x4 make_rsrc32(const void* p, uint32_t bytes) {
+  const unsigned long long a = (unsigned long long)p;
+  i32x4 r;
+  r[0] = (int)(uint32_t)a;
+  r[1] = (int)((uint32_t)(a >> 32) & 0xffffu);
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc32_v(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
 // 16 bytes per lane, HBM -> LDS without passing through registers: the wave's 64 lanes fill
 // the 1 KiB at LDS byte address `lds_addr` in lane order; lanes whose byte offset `voff` is
 // outside the descriptor's range store zeros.  Issued as inline assembly on purpose: the
@@ -207,8 +222,18 @@ struct KContigTile {
     return (uint32_t)(row * op.ld + kc * 8) * 2u;
   }
   __device__ static inline bool fast_ok(int k0, int K) { return k0 + BKT <= K; }
+  // Bytes from (r0, k0) that the descriptor of a tile must cover: up to the end of the tile's
+  // last row inside the matrix, and never into the row after it, whose lanes must read zero
+  // (lanes at k >= K are sent out of range one by one).  The same for every k-tile of a row
+  // block, and at most R * ld * 2 < 2^31 (gemm_bf16_shape_ok).
+  __device__ static inline uint32_t records(const Operand& op, int r0) {
+    const int valid = op.rows - r0 < R ? op.rows - r0 : R;
+    if (valid <= 0) return 0u;
+    const int last = (valid - 1) * op.ld + BKT, all = valid * op.ld;
+    return (uint32_t)(last < all ? last : all) * 2u;
+  }
   __device__ static inline i32x4 tile_rsrc(const Operand& op, int r0, int k0, int K) {
-    return make_rsrc(op.p + (size_t)r0 * op.ld + k0, ((long long)(op.rows - r0) * op.ld - k0) * 2);
+    return make_rsrc32(op.p + (size_t)r0 * op.ld + k0, records(op, r0));
   }
   __device__ static inline void issue_fast(const i32x4& rs, uint32_t tile, int i, uint32_t voff) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
@@ -220,7 +245,7 @@ struct KContigTile {
     const int cidx = i * NT + threadIdx.x;
     const int row = cidx / CPR, c = cidx % CPR;
     const bf16* base = op.p + (size_t)r0 * op.ld + k0;
-    const auto rs = make_rsrc_v(base, ((long long)(op.rows - r0) * op.ld - k0) * 2);
+    const auto rs = make_rsrc32_v(base, records(op, r0));
     const uint32_t off = (k0 + c * 8 < K) ? (uint32_t)(row * op.ld + c * 8) * 2u : kOOB;
     return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
   }
@@ -270,8 +295,17 @@ struct KStridedTile {
     return (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
   }
   __device__ static inline bool fast_ok(int, int) { return true; }
+  // Bytes from (k0, r0) that the descriptor of a tile must cover: up to the end of its last
+  // k-row below K (none: a tile requested beyond the contraction reads zeros), never into the
+  // k-row after it; columns beyond the matrix are sent out of range lane by lane.
+  __device__ static inline uint32_t records(const Operand& op, int k0, int K) {
+    const int valid = K - k0 < BKT ? K - k0 : BKT;
+    if (valid <= 0) return 0u;
+    const int last = (valid - 1) * op.ld + R, all = valid * op.ld;
+    return (uint32_t)(last < all ? last : all) * 2u;
+  }
   __device__ static inline i32x4 tile_rsrc(const Operand& op, int r0, int k0, int K) {
-    return make_rsrc(op.p + (size_t)k0 * op.ld + r0, ((long long)(K - k0) * op.ld - r0) * 2);
+    return make_rsrc32(op.p + (size_t)k0 * op.ld + r0, records(op, k0, K));
   }
   __device__ static inline void issue_fast(const i32x4& rs, uint32_t tile, int i, uint32_t voff) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
@@ -281,7 +315,7 @@ struct KStridedTile {
     const int cidx = i * NT + threadIdx.x;
     const int k = cidx / CPR, c = cidx % CPR;
     const bf16* base = op.p + (size_t)k0 * op.ld + r0;
-    const auto rs = make_rsrc_v(base, ((long long)(K - k0) * op.ld - r0) * 2);
+    const auto rs = make_rsrc32_v(base, records(op, k0, K));
     const uint32_t off = (r0 + c * 8 < op.rows) ? (uint32_t)(k * op.ld + c * 8) * 2u : kOOB;
     return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
   }
@@ -539,6 +573,40 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
         if (kt < nk) {
           const char* cur = stage(s);
           char* nxt = stage(s ^ 1);
+          if constexpr (MI == 4 && NI == 4 && KSTEPS == 4 && L == 16) {
+            // One wave per SIMD (128 x 128 wave tile): nobody covers for a wave whose MFMA is held
+            // up behind several memory instructions that wait to be issued, so the iteration's 64
+            // memory instructions (16 LDS writes, 16 global loads, 32 fragment reads) go one into
+            // each of the 64 gaps between its MFMAs.  MFMA n = (k-step n / 16, row block, column
+            // block); in k-steps 0..2 the odd gaps read the next k-step's eight fragments (columns
+            // first: the next k-step's first MFMAs need all four) and the even gaps alternate "write
+            // chunk t to LDS" and "reload its register"; the first half of k-step 3 does the last
+            // four chunks, the barrier follows, and the second half reads the next tile's first
+            // fragments.  (Reading the fragments in the exact order of their use, or the barrier
+            // four MFMAs earlier, lengthens register lifetimes enough to spill in the k-strided
+            // layouts, and gains nothing in the k-contiguous one.)
+#pragma unroll
+            for (int n = 0; n < 64; ++n) {
+              const int kk = n / 16, i = (n / 4) % 4, j = n % 4, e = n % 16;
+              if (n == 56) __syncthreads();   // tile kt+1 is complete in `nxt`; nobody reads `cur` any more
+              __builtin_amdgcn_sched_barrier(0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+              __builtin_amdgcn_sched_barrier(0);
+              if (n >= 56) {
+                const int q = n - 56;
+                if (q < 4) bfr[0][q] = TB::frag(nxt, b_base[q], 0);
+                else af[0][q - 4] = TA::frag(nxt, a_base[q - 4], 0);
+              } else if (kk < 3 && (e & 1)) {
+                const int q = e / 2, set = (kk + 1) & 1;
+                if (q < 4) bfr[set][q] = TB::frag(cur, b_base[q], kk + 1);
+                else af[set][q - 4] = TA::frag(cur, a_base[q - 4], kk + 1);
+              } else {
+                const int t = kk < 3 ? kk * 8 + e / 2 : 24 + (n - 48);
+                if (t % 2 == 0) vstore(nxt, t / 2);
+                else vload(kt + 2, t / 2);
+              }
+            }
+          } else {
 #pragma unroll
           for (int kk = 0; kk < KSTEPS; ++kk) {
 #pragma unroll
@@ -581,6 +649,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
                 for (int ii = first; ii < first + 2 && ii < MI; ++ii) af[0][ii] = TA::frag(nxt, a_base[ii], 0);
               }
             }
+          }
           }
         }
       }
