@@ -179,8 +179,8 @@ __device__ inline bf16x8 global_frag(const bf16* base, int ld, int row, bool val
 // lane's `scale`, as bf16 rows: rows row0 .. row0 + 31 of `base` (row pitch ld elements), those
 // below `n_rows` only.  The lanes' own 8-byte pieces would make every store instruction touch
 // 32 rows; they go through `stage` (8 KiB of LDS that only this wave uses at this point, chunk
-// c of row r at chunk c ^ (r & 15): no bank conflict either way) and leave as whole rows, four
-// rows of 256 bytes per instruction.
+// c of row r at chunk c ^ (r & 15), its halves swapped in rows 16..31: no bank conflict either
+// way) and leave as whole rows, four rows of 256 bytes per instruction.
 __device__ inline void store_rows_bf16(char* stage, const f32x16 (&acc)[4], float scale, bf16* base, size_t ld,
                                        int row0, int n_rows, int lane) {
   const int l32 = lane & 31, half = lane >> 5;
@@ -192,14 +192,16 @@ __device__ inline void store_rows_bf16(char* stage, const f32x16 (&acc)[4], floa
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = (bf16)(acc[dt][4 * gq + e] * scale);
       const int c = (dt * 4 + gq) ^ (l32 & 15);
-      *reinterpret_cast<bf16x4*>(stage + l32 * 256 + c * 16 + half * 8) = v;
+      // (rows r and r + 16 share a chunk position: they take opposite 8-byte halves of it)
+      *reinterpret_cast<bf16x4*>(stage + l32 * 256 + c * 16 + ((half ^ (l32 >> 4)) << 3)) = v;
     }
   wave_lds_sync();
   const int c = lane & 15;
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
     const int r = 4 * p + (lane >> 4);
-    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((c ^ (r & 15)) << 4));
+    u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((c ^ (r & 15)) << 4));
+    if (r & 16) v = u32x4{v[2], v[3], v[0], v[1]};
     if (row0 + r < n_rows) *reinterpret_cast<u32x4*>(base + (size_t)(row0 + r) * ld + c * 8) = v;
   }
   wave_lds_sync();   // the region may be rewritten (the next tensor of this wave)
