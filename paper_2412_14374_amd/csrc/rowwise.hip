@@ -281,10 +281,21 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T* __res
   float acc[N];
 #pragma unroll
   for (int e = 0; e < N; ++e) acc[e] = 0.f;
-  for (int r = blockIdx.y; r < rows; r += gridDim.y) {
-    const Chunk<T> v = load_chunk(dy + (size_t)r * ld + (size_t)c * N);
+  // four of the thread's rows are requested before the first is added (the additions keep
+  // their order, so the sums are the same bits as with one row at a time)
+  constexpr int kAhead = 4;
+  const int step = gridDim.y;
+  for (int r = blockIdx.y; r < rows; r += kAhead * step) {
+    Chunk<T> v[kAhead];
 #pragma unroll
-    for (int e = 0; e < N; ++e) acc[e] += v.get(e);
+    for (int j = 0; j < kAhead; ++j)
+      if (r + j * step < rows) v[j] = load_chunk(dy + (size_t)(r + j * step) * ld + (size_t)c * N);
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j)
+      if (r + j * step < rows) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] += v[j].get(e);
+      }
   }
 #pragma unroll
   for (int e = 0; e < N; ++e) partial[(size_t)blockIdx.y * n + (size_t)c * N + e] = acc[e];
