@@ -8,6 +8,7 @@
 #include <cmath>
 
 #include <type_traits>
+#include <utility>
 
 #include "device_utils.h"
 #include "internal.h"
@@ -465,61 +466,57 @@ __global__ __launch_bounds__(kThreads) void cross_entropy_kernel(const float* __
   }
 }
 
-// The same with the row held in registers: one workgroup of 1024 threads per row, every thread
-// CH chunks of four logits, so the fp32 logits are read once (16-byte loads) instead of three
-// times.  For vocab a multiple of 4 and at most 4096 * CH.
-constexpr int kCeThreads = 1024;
-template <typename T, int CH>
-__global__ __launch_bounds__(kCeThreads) void cross_entropy_reg_kernel(const float* __restrict__ z,
-                                                                       const int32_t* __restrict__ targets,
-                                                                       T* __restrict__ dz, float* __restrict__ row_loss,
-                                                                       int rows, int vocab) {
-  constexpr int NW = kCeThreads / kWave;
+// The same with the row held in registers: one workgroup of NT threads per row, every thread CH
+// chunks of four logits (chunk j of thread t is chunk t + j * NT of the row), so the fp32 logits
+// are read once, by 16-byte loads that are all in flight together, instead of three times.
+// For vocab a multiple of 4 with (CH - 1) * NT < vocab / 4 <= CH * NT: only a thread's last
+// chunk can lie beyond the row's end, every other load and store is unconditional.
+template <typename T, int CH, int NT, int kMinWaves>
+__global__ __launch_bounds__(NT, kMinWaves) void cross_entropy_reg_kernel(const float* __restrict__ z,
+                                                                          const int32_t* __restrict__ targets,
+                                                                          T* __restrict__ dz,
+                                                                          float* __restrict__ row_loss, int rows,
+                                                                          int vocab) {
+  constexpr int NW = NT / kWave;
   __shared__ float red[NW];
   typedef T T4 __attribute__((ext_vector_type(4)));
-  const size_t base = (size_t)blockIdx.x * vocab;
-  const int nchunks = vocab / 4;
+  const float* zr = z + (size_t)blockIdx.x * vocab;
+  T* dzr = dz + (size_t)blockIdx.x * vocab;
+  const bool last_ok = (int)threadIdx.x + (CH - 1) * NT < vocab / 4;
   f32x4 x[CH];
+#pragma unroll
+  for (int j = 0; j < CH - 1; ++j) x[j] = *reinterpret_cast<const f32x4*>(zr + (threadIdx.x + j * NT) * 4);
+  x[CH - 1] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};   // exp(-inf - m) adds nothing to the sum
+  if (last_ok) x[CH - 1] = *reinterpret_cast<const f32x4*>(zr + (threadIdx.x + (CH - 1) * NT) * 4);
   float m = -INFINITY;
 #pragma unroll
-  for (int j = 0; j < CH; ++j) {
-    const int c = threadIdx.x + j * kCeThreads;
-    if (c < nchunks) {
-      x[j] = *reinterpret_cast<const f32x4*>(z + base + (size_t)c * 4);
+  for (int j = 0; j < CH; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) m = fmaxf(m, x[j][e]);
-    }
-  }
+    for (int e = 0; e < 4; ++e) m = fmaxf(m, x[j][e]);
   m = block_max<NW>(m, red);
   float s = 0.f;
 #pragma unroll
-  for (int j = 0; j < CH; ++j) {
-    const int c = threadIdx.x + j * kCeThreads;
-    if (c < nchunks) {
+  for (int j = 0; j < CH; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) s += __expf(x[j][e] - m);
-    }
-  }
+    for (int e = 0; e < 4; ++e) s += __expf(x[j][e] - m);
   s = block_sum<NW>(s, red);
   const float lse = m + __logf(s);
   const int tgt = targets[blockIdx.x];
   // An id outside [0, vocab) cannot be indexed: its row reports NaN instead of reading out of bounds.
   const bool tgt_ok = (unsigned)tgt < (unsigned)vocab;
-  if (threadIdx.x == 0) row_loss[blockIdx.x] = tgt_ok ? lse - z[base + tgt] : NAN;
+  if (threadIdx.x == 0) row_loss[blockIdx.x] = tgt_ok ? lse - zr[tgt] : NAN;
   const float inv_rows = 1.f / (float)rows;
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
-    const int c = threadIdx.x + j * kCeThreads;
-    if (c < nchunks) {
-      T4 o;
+    const int c = threadIdx.x + j * NT;
+    T4 o;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float p = __expf(x[j][e] - lse);
-        if (c * 4 + e == tgt) p -= 1.f;
-        o[e] = from_f32<T>(p * inv_rows);
-      }
-      *reinterpret_cast<T4*>(dz + base + (size_t)c * 4) = o;
+    for (int e = 0; e < 4; ++e) {
+      float p = __expf(x[j][e] - lse);
+      if (c * 4 + e == tgt) p -= 1.f;
+      o[e] = from_f32<T>(p * inv_rows);
     }
+    if (j < CH - 1 || last_ok) *reinterpret_cast<T4*>(dzr + c * 4) = o;
   }
 }
 
@@ -834,24 +831,34 @@ hipError_t launch_rope(int dtype, int mb, int seq, int Hq, int Hkv, int hd, void
   return hipGetLastError();
 }
 
+// Launches cross_entropy_reg_kernel<T, per, NT, MW> for per in 1..sizeof...(I); false if per is not among them.
+template <int NT, int MW, int... I>
+static bool launch_ce_reg(std::integer_sequence<int, I...>, int per, int dtype, int rows, int vocab, const float* z,
+                          const int32_t* targets, void* dz, float* row_loss, hipStream_t s) {
+  auto go = [&](auto ch) {
+    constexpr int CH = decltype(ch)::value;
+    if (dtype == JPP_BF16)
+      cross_entropy_reg_kernel<bf16, CH, NT, MW><<<rows, NT, 0, s>>>(z, targets, (bf16*)dz, row_loss, rows, vocab);
+    else
+      cross_entropy_reg_kernel<float, CH, NT, MW><<<rows, NT, 0, s>>>(z, targets, (float*)dz, row_loss, rows, vocab);
+    return true;
+  };
+  return ((per == I + 1 && go(std::integral_constant<int, I + 1>{})) || ...);
+}
+
 hipError_t launch_cross_entropy(int dtype, int rows, int vocab, const float* z, const int32_t* targets,
                                 void* dz, float* row_loss, float* loss, hipStream_t s) {
-  const int per = (vocab / 4 + kCeThreads - 1) / kCeThreads;   // chunks of four logits per thread
-  if (vocab % 4 == 0 && per <= 16) {
-    // the row fits the registers of one workgroup
-    auto go = [&](auto ch) {
-      constexpr int CH = decltype(ch)::value;
-      if (dtype == JPP_BF16)
-        cross_entropy_reg_kernel<bf16, CH><<<rows, kCeThreads, 0, s>>>(z, targets, (bf16*)dz, row_loss, rows, vocab);
-      else
-        cross_entropy_reg_kernel<float, CH><<<rows, kCeThreads, 0, s>>>(z, targets, (float*)dz, row_loss, rows, vocab);
-    };
-    if (per <= 1) go(std::integral_constant<int, 1>{});
-    else if (per <= 2) go(std::integral_constant<int, 2>{});
-    else if (per <= 4) go(std::integral_constant<int, 4>{});
-    else if (per <= 8) go(std::integral_constant<int, 8>{});
-    else if (per <= 13) go(std::integral_constant<int, 13>{});
-    else go(std::integral_constant<int, 16>{});
+  const int chunks = vocab / 4;   // chunks of four logits
+  const int per512 = (chunks + 511) / 512, per1024 = (chunks + 1023) / 1024;
+  if (vocab % 4 == 0 && vocab > 0 && per512 <= 25) {
+    // 512 threads hold a row in at most 100 registers each: two rows are resident per compute unit
+    // (4 waves per SIMD, 128 registers per lane), so one row's loads overlap the other's stores
+    launch_ce_reg<512, 4>(std::make_integer_sequence<int, 25>{}, per512, dtype, rows, vocab, z, targets, dz, row_loss,
+                          s);
+  } else if (vocab % 4 == 0 && vocab > 0 && per1024 <= 16) {
+    // one row per compute unit in the registers of 1024 threads
+    launch_ce_reg<1024, 1>(std::make_integer_sequence<int, 16>{}, per1024, dtype, rows, vocab, z, targets, dz,
+                           row_loss, s);
   } else if (dtype == JPP_BF16) {
     cross_entropy_kernel<bf16><<<rows, kThreads, 0, s>>>(z, targets, (bf16*)dz, row_loss, rows, vocab);
   } else {
