@@ -35,6 +35,28 @@ __device__ inline void block_sum2(float& a, float& b, float* red /* >= 2*NW */) 
   a = ta; b = tb;
 }
 
+// Reduces NV values at once over a workgroup of NW waves (one pass through LDS for all of them);
+// for a value, the same order of additions as block_sum2.
+template <int NV, int NW>
+__device__ inline void block_sum_many(float (&v)[NV], float* red /* >= NV*NW */) {
+#pragma unroll
+  for (int q = 0; q < NV; ++q) v[q] = wave_sum(v[q]);
+  const int w = threadIdx.x / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+#pragma unroll
+    for (int q = 0; q < NV; ++q) red[q * NW + w] = v[q];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < NV; ++q) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) t += red[q * NW + i];
+    v[q] = t;
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Norm forward.  LayerNorm: y = (x - mean) * rstd * gamma + beta, rstd = 1/sqrt(var + eps),
 // biased variance.  RMSNorm: y = x * rstd * gamma, rstd = 1/sqrt(mean(x^2) + eps).
@@ -50,13 +72,29 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const T* __restrict_
   constexpr int N = Chunk<T>::N;
   const int nchunks = d / N;
   const size_t base = (size_t)blockIdx.x * d;
+  // Every load is unconditional (a chunk index beyond the row reads the row's last chunk
+  // instead, and its values are not used): loads inside the `c < nchunks` branches would each be
+  // waited for before the next is issued.
   Chunk<T> xs[MAXC];
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    xs[j] = load_chunk(x + base + (size_t)(c < nchunks ? c : nchunks - 1) * N);
+  }
+  // gain and offset are requested behind the row: they arrive during the reductions
+  Chunk<T> gs[MAXC], bs[MAXC];
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int c = threadIdx.x + j * kThreads;
+    const size_t o = (size_t)(c < nchunks ? c : nchunks - 1) * N;
+    gs[j] = load_chunk(gamma + o);
+    if (beta != nullptr) bs[j] = load_chunk(beta + o);
+  }
   float s = 0.f, ss = 0.f;
 #pragma unroll
   for (int j = 0; j < MAXC; ++j) {
     const int c = threadIdx.x + j * kThreads;
     if (c < nchunks) {
-      xs[j] = load_chunk(x + base + (size_t)c * N);
 #pragma unroll
       for (int e = 0; e < N; ++e) { const float v = xs[j].get(e); s += v; ss += v * v; }
     }
@@ -89,15 +127,13 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const T* __restrict_
   for (int j = 0; j < MAXC; ++j) {
     const int c = threadIdx.x + j * kThreads;
     if (c < nchunks) {
-      const Chunk<T> g = load_chunk(gamma + (size_t)c * N);
       Chunk<T> o;
       if (beta != nullptr) {
-        const Chunk<T> b = load_chunk(beta + (size_t)c * N);
 #pragma unroll
-        for (int e = 0; e < N; ++e) o.set(e, (xs[j].get(e) - mean) * rstd * g.get(e) + b.get(e));
+        for (int e = 0; e < N; ++e) o.set(e, (xs[j].get(e) - mean) * rstd * gs[j].get(e) + bs[j].get(e));
       } else {
 #pragma unroll
-        for (int e = 0; e < N; ++e) o.set(e, (xs[j].get(e) - mean) * rstd * g.get(e));
+        for (int e = 0; e < N; ++e) o.set(e, (xs[j].get(e) - mean) * rstd * gs[j].get(e));
       }
       store_chunk(y + base + (size_t)c * N, o);
     }
@@ -116,14 +152,16 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const T* __restrict_
 // NT threads per workgroup.  The narrow form (256 threads, up to 8 chunks per thread) fetches
 // dx_add when a row is processed; the wide form (512 threads, for rows of 1024 chunks and more)
 // has the registers to fetch it with the row, one row ahead, so that nothing a row needs is
-// still on its way when the row's turn comes.
-template <typename T, int MAXC, int NT = kThreads, bool WIDE = false>
+// still on its way when the row's turn comes.  A turn of a workgroup is R of its rows (the next
+// R in its ascending order), reduced together in one pass through LDS: narrow rows, whose single
+// row would leave a compute unit with a few KB of loads in flight, take R = 2 or 4.
+template <typename T, int MAXC, int NT = kThreads, bool WIDE = false, int R = 1>
 __global__ __launch_bounds__(NT) void norm_bwd_kernel(
     const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
     const T* __restrict__ dy, const T* __restrict__ dx_add, T* __restrict__ dx,
     float* __restrict__ partial_g, float* __restrict__ partial_b, int rows, int d, int norm) {
   constexpr int NW = NT / kWave;
-  __shared__ float red[2 * NW];
+  __shared__ float red[2 * R * NW];
   constexpr int N = Chunk<T>::N;
   const int nchunks = d / N;
   const float inv_d = 1.f / (float)d;
@@ -136,95 +174,127 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
 #pragma unroll
     for (int e = 0; e < N; ++e) { pg[j][e] = 0.f; pb[j][e] = 0.f; }
   }
-  // One row's operands in registers.  The next row of this workgroup is fetched while the
-  // current one is reduced and written, so a row costs one memory latency, not three.
-  struct Row { Chunk<T> xs[MAXC], ds[MAXC], as[WIDE ? MAXC : 1]; float mean, rstd; };
-  auto fetch = [&](int r, Row& w) {
-    const size_t base = (size_t)r * d;
-    w.mean = stats[2 * (size_t)r];
-    w.rstd = stats[2 * (size_t)r + 1];
+  // One turn's operands in registers.  The next turn of this workgroup is fetched while the
+  // current one is reduced and written, so a turn costs one memory latency, not three.
+  struct Turn { Chunk<T> xs[R][MAXC], ds[R][MAXC], as[R][WIDE ? MAXC : 1]; float mean[R], rstd[R]; };
+  const int stride = gridDim.x;
+  // row i of the turn that starts at row r0
+  auto row_of = [&](int r0, int i) { return r0 + i * stride; };
+  auto fetch = [&](int r0, Turn& w) {
 #pragma unroll
-    for (int j = 0; j < MAXC; ++j) {
-      const int c = threadIdx.x + j * NT;
-      if (c < nchunks) {
-        w.xs[j] = load_chunk(x + base + (size_t)c * N);
-        w.ds[j] = load_chunk(dy + base + (size_t)c * N);
-        if constexpr (WIDE) {
-          if (dx_add != nullptr) w.as[j] = load_chunk(dx_add + base + (size_t)c * N);
+    for (int i = 0; i < R; ++i) {
+      const int r = row_of(r0, i);
+      if (r < rows) {
+        const size_t base = (size_t)r * d;
+        w.mean[i] = stats[2 * (size_t)r];
+        w.rstd[i] = stats[2 * (size_t)r + 1];
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+          const int c = threadIdx.x + j * NT;
+          if (c < nchunks) {
+            w.xs[i][j] = load_chunk(x + base + (size_t)c * N);
+            w.ds[i][j] = load_chunk(dy + base + (size_t)c * N);
+            if constexpr (WIDE) {
+              if (dx_add != nullptr) w.as[i][j] = load_chunk(dx_add + base + (size_t)c * N);
+            }
+          }
         }
       }
     }
   };
-  auto process = [&](int r, const Row& w) {
-    const size_t base = (size_t)r * d;
-    const float mean = w.mean, rstd = w.rstd;
+  auto process = [&](int r0, const Turn& w) {
     // the tensor added to the result is only needed after the reduction: its latency hides there
-    Chunk<T> as[MAXC];
+    Chunk<T> as[R][MAXC];
     if constexpr (WIDE) {
 #pragma unroll
-      for (int j = 0; j < MAXC; ++j) as[j] = w.as[j];
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) as[i][j] = w.as[i][j];
     } else if (dx_add != nullptr) {
 #pragma unroll
-      for (int j = 0; j < MAXC; ++j) {
-        const int c = threadIdx.x + j * NT;
-        if (c < nchunks) as[j] = load_chunk(dx_add + base + (size_t)c * N);
-      }
-    }
-    float s1 = 0.f, s2 = 0.f;
+      for (int i = 0; i < R; ++i) {
+        const int r = row_of(r0, i);
+        if (r < rows) {
 #pragma unroll
-    for (int j = 0; j < MAXC; ++j) {
-      const int c = threadIdx.x + j * NT;
-      if (c < nchunks) {
-#pragma unroll
-        for (int e = 0; e < N; ++e) {
-          const float xh = (w.xs[j].get(e) - mean) * rstd;
-          const float dv = w.ds[j].get(e);
-          const float dxh = dv * gs[j].get(e);
-          s1 += dxh;
-          s2 += dxh * xh;
-          pg[j][e] += dv * xh;
-          pb[j][e] += dv;
+          for (int j = 0; j < MAXC; ++j) {
+            const int c = threadIdx.x + j * NT;
+            if (c < nchunks) as[i][j] = load_chunk(dx_add + (size_t)r * d + (size_t)c * N);
+          }
         }
       }
     }
-    block_sum2<NW>(s1, s2, red);
-    const float m1 = (norm == JPP_LAYERNORM) ? s1 * inv_d : 0.f;
-    const float m2 = s2 * inv_d;
+    float sums[2 * R];
 #pragma unroll
-    for (int j = 0; j < MAXC; ++j) {
-      const int c = threadIdx.x + j * NT;
-      if (c < nchunks) {
-        Chunk<T> o;
+    for (int i = 0; i < R; ++i) {
+      float s1 = 0.f, s2 = 0.f;
+      if (row_of(r0, i) < rows) {
+        const float mean = w.mean[i], rstd = w.rstd[i];
 #pragma unroll
-        for (int e = 0; e < N; ++e) {
-          const float xh = (w.xs[j].get(e) - mean) * rstd;
-          const float dxh = w.ds[j].get(e) * gs[j].get(e);
-          float v = rstd * (dxh - m1 - xh * m2);
-          if (dx_add != nullptr) v += as[j].get(e);
-          o.set(e, v);
+        for (int j = 0; j < MAXC; ++j) {
+          const int c = threadIdx.x + j * NT;
+          if (c < nchunks) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+              const float xh = (w.xs[i][j].get(e) - mean) * rstd;
+              const float dv = w.ds[i][j].get(e);
+              const float dxh = dv * gs[j].get(e);
+              s1 += dxh;
+              s2 += dxh * xh;
+              pg[j][e] += dv * xh;
+              pb[j][e] += dv;
+            }
+          }
         }
-        store_chunk(dx + base + (size_t)c * N, o);
+      }
+      sums[2 * i] = s1;
+      sums[2 * i + 1] = s2;
+    }
+    block_sum_many<2 * R, NW>(sums, red);
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int r = row_of(r0, i);
+      if (r < rows) {
+        const float mean = w.mean[i], rstd = w.rstd[i];
+        const float m1 = (norm == JPP_LAYERNORM) ? sums[2 * i] * inv_d : 0.f;
+        const float m2 = sums[2 * i + 1] * inv_d;
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+          const int c = threadIdx.x + j * NT;
+          if (c < nchunks) {
+            Chunk<T> o;
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+              const float xh = (w.xs[i][j].get(e) - mean) * rstd;
+              const float dxh = w.ds[i][j].get(e) * gs[j].get(e);
+              float v = rstd * (dxh - m1 - xh * m2);
+              if (dx_add != nullptr) v += as[i][j].get(e);
+              o.set(e, v);
+            }
+            store_chunk(dx + (size_t)r * d + (size_t)c * N, o);
+          }
+        }
       }
     }
   };
+  const int turn = R * stride;   // rows between the first rows of two turns of a workgroup
   if constexpr (MAXC > 6) {
     // two rows of this width do not fit the register file: one at a time
-    Row a;
-    for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    Turn a;
+    for (int r = blockIdx.x; r < rows; r += turn) {
       fetch(r, a);
       process(r, a);
     }
   } else {
-    Row a, b;
+    Turn a, b;
     int r = blockIdx.x;
     if (r < rows) fetch(r, a);
     while (r < rows) {
-      int nxt = r + gridDim.x;
+      int nxt = r + turn;
       if (nxt < rows) fetch(nxt, b);
       process(r, a);
       r = nxt;
       if (r >= rows) break;
-      nxt = r + gridDim.x;
+      nxt = r + turn;
       if (nxt < rows) fetch(nxt, a);
       process(r, b);
       r = nxt;
@@ -714,8 +784,8 @@ hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamm
     else norm_bwd_kernel<T, 4, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
   } else
   switch (pick_maxc<T>(d)) {
-    case 1: norm_bwd_kernel<T, 1><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
-    case 2: norm_bwd_kernel<T, 2><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    case 1: norm_bwd_kernel<T, 1, kThreads, false, 4><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    case 2: norm_bwd_kernel<T, 2, kThreads, false, 2><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     case 4: norm_bwd_kernel<T, 4><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     case 6: norm_bwd_kernel<T, 6><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
     default: norm_bwd_kernel<T, 8><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
