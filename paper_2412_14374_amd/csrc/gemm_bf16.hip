@@ -58,6 +58,7 @@
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
 //    works on a contiguous band of tiles and shares operand panels in its own L2.
 #include <cstdlib>
+#include <type_traits>
 
 #include "device_utils.h"
 #include "internal.h"
@@ -742,6 +743,86 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
 #pragma unroll
     for (int e = 0; e < 4; ++e) bias4[e] = (float)b[e];
   }
+  constexpr bool kActBwd = ACT == ACT_BWD_ERF || ACT == ACT_BWD_TANH;
+  // A tile that lies wholly inside the matrix: no access is predicated and the output mode is
+  // a compile-time constant of the pass, so the pass is straight-line code whose loads and
+  // stores are all in flight together.  (Behind a branch the compiler waits for everything
+  // outstanding, the previous row step's store included, before it uses a loaded register: an
+  // accumulating tile then pays 32 store round trips one after the other.)  Everything a row
+  // block reads from memory -- the gradient rows of an accumulating output, for which the NEXT
+  // block's rows are requested too, the residual, the pre-activations -- is requested before
+  // the block is staged.
+  auto full_tile_pass = [&](auto mode_c, auto res_c) {
+    constexpr int MODE = decltype(mode_c)::value;
+    constexpr bool RES = decltype(res_c)::value;
+    constexpr bool ACC = MODE == OUT_ACC_F32;
+    f32x4 prev[ACC ? 2 : 1][kSteps];
+    bf16x4 resv[RES ? kSteps : 1];
+    bf16x4 hpre[kActBwd ? kSteps : 1];
+    auto index = [&](int i, int s) { return (size_t)(m0 + wm * TM + i * 32 + s * RPI + erow) * ep.ldc + n; };
+    auto load_prev = [&](int i) {
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s)
+        prev[ACC ? i & 1 : 0][s] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(ep.C) + index(i, s));
+    };
+    if constexpr (ACC) load_prev(0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      if constexpr (ACC) {
+        if (i + 1 < MI) load_prev(i + 1);
+      }
+      if constexpr (RES) {
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) resv[s] = *reinterpret_cast<const bf16x4*>(ep.residual + index(i, s));
+      }
+      if constexpr (kActBwd) {
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) hpre[s] = *reinterpret_cast<const bf16x4*>(ep.aux + index(i, s));
+      }
+      wave_lds_sync();  // the previous pass's reads are done before its region is rewritten
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          stg[(8 * (r >> 2) + 4 * half + (r & 3)) * LDW + j * 32 + l32] = acc[i][j][r];
+      wave_lds_sync();
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(stg + (s * RPI + erow) * LDW + ecol);
+        const size_t idx = index(i, s);
+        v += bias4;
+        if constexpr (RES) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += (float)resv[s][e];
+        }
+        if constexpr (ACT != ACT_NONE) {
+          store_bf16x4_act<ACT>(ep, idx, v, hpre[kActBwd ? s : 0]);
+        } else if constexpr (MODE == OUT_STORE) {
+          store_bf16x4_act<ACT_NONE>(ep, idx, v);
+        } else if constexpr (MODE == OUT_STORE_F32) {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = v;
+        } else {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.C) + idx) = prev[i & 1][s] + v;
+        }
+      }
+    }
+  };
+  if (m0 + BM <= M && n0 + BN <= N) {
+    using std::integral_constant;
+    if constexpr (ACT != ACT_NONE) {
+      full_tile_pass(integral_constant<int, OUT_STORE>{}, std::false_type{});
+    } else if (ep.out_mode == OUT_ACC_F32) {
+      full_tile_pass(integral_constant<int, OUT_ACC_F32>{}, std::false_type{});
+    } else if (ep.out_mode == OUT_STORE_F32) {
+      full_tile_pass(integral_constant<int, OUT_STORE_F32>{}, std::false_type{});
+    } else if (ep.residual) {
+      full_tile_pass(integral_constant<int, OUT_STORE>{}, std::true_type{});
+    } else {
+      full_tile_pass(integral_constant<int, OUT_STORE>{}, std::false_type{});
+    }
+    return;
+  }
+  // a tile that crosses the matrix's edge: every access predicated, the mode chosen per store
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int mbase = m0 + wm * TM + i * 32;
@@ -756,7 +837,6 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_bf16_kernel(int M, in
     }
     // backward GeLU: the block's pre-activations are requested before the staging pass, so
     // that their latency is spent there and not once per row step
-    constexpr bool kActBwd = ACT == ACT_BWD_ERF || ACT == ACT_BWD_TANH;
     bf16x4 hpre[kActBwd ? kSteps : 1];
     if constexpr (kActBwd) {
 #pragma unroll
