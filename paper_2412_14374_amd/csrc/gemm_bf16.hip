@@ -54,7 +54,11 @@
 //  * Rows beyond the matrix read as zero through the buffer range check, the contiguous
 //    dimension is predicated, so M, N, K need only be multiples of 8.
 //  * Epilogue: accumulators go through LDS so that every global access is 8 or 16 bytes per
-//    lane on full rows; the fp32 gradient tile is read with 16-byte loads issued first.
+//    lane on full rows.  A tile inside the matrix takes a pass without predicates or run-time
+//    mode branches, so that all of its loads and stores are in flight together (behind a branch
+//    the compiler waits for every outstanding access, stores included, before a loaded register
+//    is used: 32 serial store round trips per accumulating tile, 0.2 ms of a 2 ms launch at
+//    K = 2048); the fp32 gradient rows are requested one 32-row block ahead.
 //  * Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
 //    works on a contiguous band of tiles and shares operand panels in its own L2.
 #include <cstdlib>

@@ -155,7 +155,11 @@ __global__ __launch_bounds__(kThreads) void norm_fwd_kernel(const T* __restrict_
 // still on its way when the row's turn comes.  A turn of a workgroup is R of its rows (the next
 // R in its ascending order), reduced together in one pass through LDS: narrow rows, whose single
 // row would leave a compute unit with a few KB of loads in flight, take R = 2 or 4.
-template <typename T, int MAXC, int NT = kThreads, bool WIDE = false, int R = 1>
+// FAST != 0: the row is exactly MAXC * NT chunks and every workgroup has only full turns
+// (rows a multiple of R * gridDim.x), dx_add is absent (1) or present (2): nothing is predicated
+// and no branch stands between a load and its use, so the compiler counts the accesses in
+// flight instead of waiting for all of them (stores included) at every join.
+template <typename T, int MAXC, int NT = kThreads, bool WIDE = false, int R = 1, int FAST = 0>
 __global__ __launch_bounds__(NT) void norm_bwd_kernel(
     const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ stats,
     const T* __restrict__ dy, const T* __restrict__ dx_add, T* __restrict__ dx,
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
 #pragma unroll
   for (int j = 0; j < MAXC; ++j) {
     const int c = threadIdx.x + j * NT;
-    if (c < nchunks) gs[j] = load_chunk(gamma + (size_t)c * N);
+    if (FAST || c < nchunks) gs[j] = load_chunk(gamma + (size_t)c * N);
 #pragma unroll
     for (int e = 0; e < N; ++e) { pg[j][e] = 0.f; pb[j][e] = 0.f; }
   }
@@ -184,18 +188,18 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const int r = row_of(r0, i);
-      if (r < rows) {
+      if (FAST || r < rows) {
         const size_t base = (size_t)r * d;
         w.mean[i] = stats[2 * (size_t)r];
         w.rstd[i] = stats[2 * (size_t)r + 1];
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) {
           const int c = threadIdx.x + j * NT;
-          if (c < nchunks) {
+          if (FAST || c < nchunks) {
             w.xs[i][j] = load_chunk(x + base + (size_t)c * N);
             w.ds[i][j] = load_chunk(dy + base + (size_t)c * N);
             if constexpr (WIDE) {
-              if (dx_add != nullptr) w.as[i][j] = load_chunk(dx_add + base + (size_t)c * N);
+              if (FAST ? FAST == 2 : dx_add != nullptr) w.as[i][j] = load_chunk(dx_add + base + (size_t)c * N);
             }
           }
         }
@@ -210,15 +214,15 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
       for (int i = 0; i < R; ++i)
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) as[i][j] = w.as[i][j];
-    } else if (dx_add != nullptr) {
+    } else if (FAST ? FAST == 2 : dx_add != nullptr) {
 #pragma unroll
       for (int i = 0; i < R; ++i) {
         const int r = row_of(r0, i);
-        if (r < rows) {
+        if (FAST || r < rows) {
 #pragma unroll
           for (int j = 0; j < MAXC; ++j) {
             const int c = threadIdx.x + j * NT;
-            if (c < nchunks) as[i][j] = load_chunk(dx_add + (size_t)r * d + (size_t)c * N);
+            if (FAST || c < nchunks) as[i][j] = load_chunk(dx_add + (size_t)r * d + (size_t)c * N);
           }
         }
       }
@@ -227,12 +231,12 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       float s1 = 0.f, s2 = 0.f;
-      if (row_of(r0, i) < rows) {
+      if (FAST || row_of(r0, i) < rows) {
         const float mean = w.mean[i], rstd = w.rstd[i];
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) {
           const int c = threadIdx.x + j * NT;
-          if (c < nchunks) {
+          if (FAST || c < nchunks) {
 #pragma unroll
             for (int e = 0; e < N; ++e) {
               const float xh = (w.xs[i][j].get(e) - mean) * rstd;
@@ -253,21 +257,21 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const int r = row_of(r0, i);
-      if (r < rows) {
+      if (FAST || r < rows) {
         const float mean = w.mean[i], rstd = w.rstd[i];
         const float m1 = (norm == JPP_LAYERNORM) ? sums[2 * i] * inv_d : 0.f;
         const float m2 = sums[2 * i + 1] * inv_d;
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) {
           const int c = threadIdx.x + j * NT;
-          if (c < nchunks) {
+          if (FAST || c < nchunks) {
             Chunk<T> o;
 #pragma unroll
             for (int e = 0; e < N; ++e) {
               const float xh = (w.xs[i][j].get(e) - mean) * rstd;
               const float dxh = w.ds[i][j].get(e) * gs[j].get(e);
               float v = rstd * (dxh - m1 - xh * m2);
-              if (dx_add != nullptr) v += as[i][j].get(e);
+              if (FAST ? FAST == 2 : dx_add != nullptr) v += as[i][j].get(e);
               o.set(e, v);
             }
             store_chunk(dx + (size_t)r * d + (size_t)c * N, o);
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(
 #pragma unroll
   for (int j = 0; j < MAXC; ++j) {
     const int c = threadIdx.x + j * NT;
-    if (c < nchunks) {
+    if (FAST || c < nchunks) {
       const size_t o = (size_t)blockIdx.x * d + (size_t)c * N;
 #pragma unroll
       for (int e = 0; e < N; ++e) {
@@ -778,17 +782,37 @@ hipError_t norm_bwd_t(int norm, int rows, int d, const void* x, const void* gamm
   // (24 elements per thread and row: bf16 up to 12288 columns, fp32 up to 8192)
   const int nchunks = d / Chunk<T>::N;
   const int per = (nchunks + 511) / 512;
+  auto go = [&](auto maxc, auto nt, auto wide, auto r) {
+    constexpr int MAXC = decltype(maxc)::value, NT = decltype(nt)::value, R = decltype(r)::value;
+    constexpr bool WIDE = decltype(wide)::value;
+    // the unpredicated forms: narrow bf16 rows (the wide forms have no registers to spare for
+    // what the scheduler then keeps in flight; the fp32 path is the parity path)
+    if constexpr (std::is_same<T, bf16>::value && !WIDE && MAXC <= 2) {
+      if (nchunks == MAXC * NT && rows % (R * nblk) == 0) {
+        if (ap)
+          norm_bwd_kernel<T, MAXC, NT, WIDE, R, 2><<<nblk, NT, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+        else
+          norm_bwd_kernel<T, MAXC, NT, WIDE, R, 1><<<nblk, NT, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+        return;
+      }
+    }
+    norm_bwd_kernel<T, MAXC, NT, WIDE, R, 0><<<nblk, NT, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+  };
+  using std::integral_constant;
+  typedef integral_constant<int, 512> W512;
+  typedef integral_constant<int, kThreads> W256;
+  typedef integral_constant<int, 1> One;
   if (nchunks >= 1024 && per * Chunk<T>::N <= 24) {
-    if (per <= 2) norm_bwd_kernel<T, 2, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
-    else if (per == 3) norm_bwd_kernel<T, 3, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
-    else norm_bwd_kernel<T, 4, 512, true><<<nblk, 512, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm);
+    if (per <= 2) go(integral_constant<int, 2>{}, W512{}, std::true_type{}, One{});
+    else if (per == 3) go(integral_constant<int, 3>{}, W512{}, std::true_type{}, One{});
+    else go(integral_constant<int, 4>{}, W512{}, std::true_type{}, One{});
   } else
   switch (pick_maxc<T>(d)) {
-    case 1: norm_bwd_kernel<T, 1, kThreads, false, 4><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
-    case 2: norm_bwd_kernel<T, 2, kThreads, false, 2><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
-    case 4: norm_bwd_kernel<T, 4><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
-    case 6: norm_bwd_kernel<T, 6><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
-    default: norm_bwd_kernel<T, 8><<<nblk, kThreads, 0, s>>>(xp, gp, stats, dyp, ap, dxp, pg, pb, rows, d, norm); break;
+    case 1: go(integral_constant<int, 1>{}, W256{}, std::false_type{}, integral_constant<int, 4>{}); break;
+    case 2: go(integral_constant<int, 2>{}, W256{}, std::false_type{}, integral_constant<int, 2>{}); break;
+    case 4: go(integral_constant<int, 4>{}, W256{}, std::false_type{}, One{}); break;
+    case 6: go(integral_constant<int, 6>{}, W256{}, std::false_type{}, One{}); break;
+    default: go(integral_constant<int, 8>{}, W256{}, std::false_type{}, One{}); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
