@@ -671,7 +671,7 @@ def main():
         progress(f"dominant kernel timed: {avg_ms:.3f} ms per launch")
         shapes = wgrad_shapes(w)
         # L2 <-> fabric bytes per launch from the profiler, for the C4 shapes only: groups of 8 / per task
-        traffic = {8: 29.4e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
+        traffic = {8: 33.8e9, 1: 6.65e9}.get(max(1, w.wgrad_group)) if a.config == "C4" else None
         ach = flops_per_launch / (avg_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel<..., k-strided A, k-strided B> "
                            "(weight gradient with fused fp32 accumulate)",
@@ -683,8 +683,9 @@ def main():
                            "traffic_source": ("profiles/gemm_wgrad_c4_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE, then "
                                               "WRITE_SIZE, of `bench.py --kernel-only`, scaled by the same counters "
                                               "of a 1 GiB copy; bytes between the L2s and the fabric, of which the "
-                                              "256 MB last-level cache serves at least four fifths (mean read "
-                                              "time 595 L2 cycles against 528 / 861 for that cache / HBM idle)")
+                                              "256 MB last-level cache serves at least three quarters (mean read "
+                                              "time 594 L2 cycles against 519 / 857 for that cache / HBM idle); "
+                                              "27-32 GB of it fetched, varying from run to run")
                            if traffic else None,
                            "algorithmic_bytes_per_launch": sum(8.0 * m * n + 2.0 * k * (m + n) for m, n, k in shapes)
                            / len(shapes)}
