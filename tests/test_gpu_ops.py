@@ -507,10 +507,13 @@ def test_activation_forward_backward(dtype, act, rows, f):
 
 @pytest.mark.parametrize("dtype,rows,vocab", [(inp.DT_F32, 7, 1000), (inp.DT_F32, 5, 1001), (inp.DT_F32, 3, 6),
                                               (inp.DT_BF16, 9, 5024), (inp.DT_BF16, 4, 8), (inp.DT_BF16, 2, 70000),
+                                              (inp.DT_BF16, 3, 2048), (inp.DT_F32, 3, 2052), (inp.DT_BF16, 2, 51200),
+                                              (inp.DT_BF16, 3, 51204), (inp.DT_F32, 2, 60000), (inp.DT_BF16, 2, 65536),
                                               (inp.DT_BF16, 4096, 50304)])
 def test_cross_entropy(dtype, rows, vocab):
     """Loss, per-row losses and dz against the float64 definition; vocabularies that take the
-    register-resident kernel (a multiple of 4, at most 65536) and ones that do not, and the
+    register-resident kernels (a multiple of 4: up to 51200 in 512 threads, up to 65536 in 1024,
+    with the last chunk of a thread full and ragged) and ones that do not, and the
     C5 head's own shape (4096 x 50304: 256 sampled rows for dz, every row's loss)."""
     g = torch.Generator(device=DEV)
     g.manual_seed(rows + vocab)
