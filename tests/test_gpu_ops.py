@@ -446,6 +446,20 @@ def test_attention_forward_backward(dtype, mb, seq, Hq, Hkv, hd):
 def test_norm_forward_backward(dtype, norm, rows, d):
     if dtype == inp.DT_F32 and d > 8192:
         pytest.skip("fp32 rows are limited to 8192 columns")
+    _norm_case(dtype, norm, rows, d, rows % 2 == 0)
+
+
+@pytest.mark.parametrize("norm", [inp.NORM_LAYERNORM, inp.NORM_RMSNORM])
+@pytest.mark.parametrize("rows,d,with_add", [(1024, 2048, True), (1024, 2048, False), (2048, 2048, True),
+                                             (512, 4096, True), (512, 4096, False), (1536, 4096, True)])
+def test_norm_backward_rows_that_fill_the_workgroups_exactly(norm, rows, d, with_add):
+    """bf16 rows of exactly 256 or 512 chunks, in row counts that give every workgroup only full
+    turns (four or two rows at a time): the backward forms without predicates, with and without
+    the added tensor."""
+    _norm_case(inp.DT_BF16, norm, rows, d, with_add)
+
+
+def _norm_case(dtype, norm, rows, d, with_add):
     rng = np.random.default_rng(rows + d)
     spec = so.StageSpec(n_layers=1, d_model=d, n_q_heads=1, n_kv_heads=1, head_dim=8, d_ffn=8, seq_len=1,
                         microbatch=1, norm=norm)
@@ -464,7 +478,6 @@ def test_norm_forward_backward(dtype, norm, rows, d):
     gg = torch.ones(d, dtype=torch.float32, device=DEV)
     gb = torch.ones(d, dtype=torch.float32, device=DEV)
     part = torch.zeros(B.jpp_op_colreduce_scratch(rows, d), dtype=torch.float32, device=DEV)
-    with_add = rows % 2 == 0
     B.jpp_op_norm_bwd(dtype, norm, rows, d, tx.data_ptr(), tg.data_ptr(), stats.data_ptr(), tdy.data_ptr(),
                       tadd.data_ptr() if with_add else None, dx.data_ptr(), gg.data_ptr(), gb.data_ptr(),
                       part.data_ptr(), stream())
